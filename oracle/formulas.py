@@ -1,0 +1,108 @@
+"""The paper's closed forms (App. A), in exact integer / rational arithmetic.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+"""
+from fractions import Fraction
+
+
+def n_params(N_layers, S_hidden):
+    """App. A.1: N_params ~ 12 N_layers S_hidden^2 (weights of the four linears)."""
+    return 12 * N_layers * S_hidden ** 2
+
+
+def n_params_exact(N_layers, S_hidden, S_mlp):
+    """All parameters of the layer stack built here, biases and LayerNorms included."""
+    h, f = S_hidden, S_mlp
+    per = (h * 3 * h + 3 * h) + (h * h + h) + (h * f + f) + (f * h + h) + 4 * h
+    return N_layers * per
+
+
+def bubble(N_PP, N_mb, N_loop=1):
+    """Eq. bubble (Sec. 3.2) and Eq. bubble_looped (Sec. 4.1)."""
+    return Fraction(N_PP - 1, N_mb * N_loop)
+
+
+def m_act(S_seq, S_mb, S_hidden, N_heads, N_TP=1):
+    """App. A.2.2: activation bytes of one layer and micro-batch (with dropout masks
+    and unfused attention scores), as an exact fraction."""
+    return S_seq * S_mb * S_hidden * (10 + Fraction(24, N_TP) + Fraction(5 * S_seq * N_heads, S_hidden * N_TP))
+
+
+def ckpt_count(kind, N_mb, N_layers, N_PP):
+    """Number of live checkpoints, first ratio of Eq. mem_ckpt with the caps the
+    text gives for the backward-first schedules."""
+    full = Fraction(N_mb * N_layers, N_PP)
+    if kind in ("BF", "GPIPE"):
+        return full
+    if kind == "1F1B":
+        return min(full, Fraction((2 * N_PP - 1) * N_layers, N_PP))
+    if kind == "DF":
+        return min(full, Fraction(N_layers + N_PP - 1))
+    raise ValueError(kind)
+
+
+def ckpt_bytes_each(S_seq, S_mb, S_hidden, N_TP=1):
+    """Second ratio of Eq. mem_ckpt: one half-precision [S_mb, S_seq, S_hidden] tensor."""
+    return Fraction(2 * S_seq * S_mb * S_hidden, N_TP)
+
+
+def m_ckpt(kind, N_mb, N_layers, N_PP, S_seq, S_mb, S_hidden, N_TP=1):
+    return ckpt_count(kind, N_mb, N_layers, N_PP) * ckpt_bytes_each(S_seq, S_mb, S_hidden, N_TP)
+
+
+def c_gpu_per_position(N_mb, S_mb, N_layers, S_hidden, S_seq, S_voc=0, N_PP=1, N_TP=1):
+    """Eq. compute exactly as printed (flop per GPU, per sequence position)."""
+    return Fraction(96 * N_mb * S_mb * N_layers * S_hidden, N_PP * N_TP) * (
+        S_hidden + Fraction(S_seq, 6) + Fraction(S_voc, 16 * N_layers))
+
+
+def c_gpu(N_mb, S_mb, N_layers, S_hidden, S_seq, S_voc=0, N_PP=1, N_TP=1):
+    """Eq. compute times S_seq: flop per GPU and batch.  (As printed the equation has
+    no S_seq factor; with it the value is 4x the forward flops of the linears plus
+    full attention, i.e. forward + recomputed forward + backward.)"""
+    return c_gpu_per_position(N_mb, S_mb, N_layers, S_hidden, S_seq, S_voc, N_PP, N_TP) * S_seq
+
+
+def fwd_flops_layer_mb(S_hidden, S_seq, S_mb):
+    """Forward flops of one layer on one micro-batch with S_mlp = 4 S_hidden and full
+    (non-causal) attention: 2 flop per multiply-add."""
+    T = S_seq * S_mb
+    return 24 * S_hidden ** 2 * T + 4 * S_seq * T * S_hidden
+
+
+def state_memory(kind, N_params, N_layers=1, N_PP=1, N_TP=1):
+    """App. A.2.1: (low, high) bytes of state memory."""
+    if kind == "DP0":
+        return Fraction(12 * N_params, N_PP * N_TP), Fraction(20 * N_params, N_PP * N_TP)
+    if kind == "DP_PS":
+        return Fraction(2 * N_params, N_PP * N_TP), Fraction(4 * N_params, N_PP * N_TP)
+    if kind == "DP_FS":
+        v = Fraction(8 * N_params, N_layers * N_TP)
+        return v, v
+    raise ValueError(kind)
+
+
+def intensity_pp(S_hidden, N_layers, N_PP, N_loop):
+    """Eq. intensity_pipeline: I_PP = 24 S_hidden N_layers / (N_PP N_loop)."""
+    return Fraction(24 * S_hidden * N_layers, N_PP * N_loop)
+
+
+def intensity_tp(S_hidden, N_TP):
+    """App. A.3.3: I_TP = 2 S_hidden / N_TP."""
+    return Fraction(2 * S_hidden, N_TP)
+
+
+def intensity_dp(N_mb, S_mb, S_seq):
+    """App. A.3.1: I_DP0 ~ I_DP_PS = N_mb S_mb S_seq."""
+    return N_mb * S_mb * S_seq
+
+
+def intensity_fs(kind, N_mb, S_mb, S_seq, N_PP=1):
+    """App. A.3.1: fully sharded intensities."""
+    if kind == "plain":
+        return Fraction(2 * S_mb * S_seq, 3)
+    if kind == "DF":
+        return Fraction(2 * N_PP * S_mb * S_seq, 3)
+    if kind == "BF":
+        return Fraction(2 * N_mb * S_mb * S_seq, 3)
+    raise ValueError(kind)

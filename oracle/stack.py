@@ -1,0 +1,156 @@
+"""One pipeline rank's training step in breadth-first or depth-first order.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+The rank holds N_layers identical layers split into N_loop contiguous stages
+(Sec. 4.1: N_loop = N_stage / N_PP).  On one device the stages are chained, which
+is the N_PP = 1 case the paper calls breadth-first gradient accumulation (App. C).
+What is computed is ordinary gradient accumulation over N_mb micro-batches:
+
+    Y_m = Layer_{N-1}( ... Layer_0(X_m)),    L = sum_m <Y_m, dY_m>
+    G_l = sum_{m ascending} d<Y_m, dY_m>/d theta_l,   dX_m = dL/dX_m
+    then one Adam step per parameter with G (plain sum, no 1/N_mb).
+
+The two orders (Sec. 4.1):
+  BF  every micro-batch through a stage before the next stage, forward first;
+      backward stage by stage from the last, a stage's gradient is final after
+      its N_mb backwards and its optimizer step fires there.
+  DF  (N_PP = 1) each micro-batch goes through the whole forward and the whole
+      backward before the next one starts; a stage's gradient is final only in
+      the last micro-batch's backward.
+Within a stage the micro-batches are always taken in ascending order, so both
+orders add the same numbers in the same sequence and G is bitwise equal.
+
+The integer event trace records (op, stage, mb, live) where live is the number
+of activation checkpoints (one per layer and micro-batch, Eq. mem_ckpt in
+App. A.2.2) alive after the event.
+"""
+import numpy as np
+
+from . import layer as L
+
+OP_F, OP_B, OP_OPT = 0, 1, 2
+SCHED_BF, SCHED_DF = 0, 1
+
+
+def stage_layers(N_layers, N_loop, s):
+    if N_layers % N_loop:
+        raise ValueError("N_layers must be a multiple of N_loop")
+    per = N_layers // N_loop
+    return range(s * per, (s + 1) * per)
+
+
+def event_order(schedule, N_loop, N_mb):
+    """The ordered (op, stage, mb) list of one step; OPT events carry mb = -1."""
+    ev = []
+    if schedule == SCHED_BF:
+        for s in range(N_loop):
+            for m in range(N_mb):
+                ev.append((OP_F, s, m))
+        for s in reversed(range(N_loop)):
+            for m in range(N_mb):
+                ev.append((OP_B, s, m))
+            ev.append((OP_OPT, s, -1))
+    elif schedule == SCHED_DF:
+        for m in range(N_mb):
+            for s in range(N_loop):
+                ev.append((OP_F, s, m))
+            for s in reversed(range(N_loop)):
+                ev.append((OP_B, s, m))
+                if m == N_mb - 1:
+                    ev.append((OP_OPT, s, -1))
+    else:
+        raise ValueError("schedule")
+    return ev
+
+
+def adam_update(w, g, m, v, t, lr, beta1, beta2, adam_eps, weight_decay=0.0):
+    """Bias-corrected Adam (Kingma & Ba, Alg. 1), step counter t >= 1.
+
+    weight_decay is the decoupled (AdamW) kind: w -= lr * weight_decay * w.
+    Returns new (w, m, v).
+    """
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    w = w - lr * (mhat / (np.sqrt(vhat) + adam_eps) + weight_decay * w)
+    return w, m, v
+
+
+def run_step(params, x, dy, schedule, N_loop, N_heads, eps=1e-5, causal=True,
+             gelu_form="tanh", adam=None, adam_state=None):
+    """Executes one step in the given order.
+
+    params: list (one per layer) of dicts name -> float64 array
+    x, dy:  [N_mb, S_mb, S_seq, S_hidden]
+    adam:   None (no optimizer step) or dict(lr, beta1, beta2, adam_eps, weight_decay, t)
+    adam_state: list of dicts name -> (m, v); zeros if None
+    Returns dict(y, dx, grads, trace, peak_ckpt, new_params, new_adam_state)
+    """
+    N_layers = len(params)
+    N_mb = x.shape[0]
+    y = np.zeros_like(x)
+    dx = np.zeros_like(x)
+    grads = [None] * N_layers                 # main-grad buffers, created by the first micro-batch
+    caches = {}                               # (layer, mb) -> cache; its presence = one live checkpoint
+    hand = {}                                 # mb -> tensor handed from stage s to s+1 (forward) / s to s-1 (backward)
+    bhand = {}
+    new_params = [dict(p) for p in params]
+    if adam_state is None:
+        adam_state = [{k: (np.zeros_like(v), np.zeros_like(v)) for k, v in p.items()} for p in params]
+    new_state = [dict(s) for s in adam_state]
+    trace = []
+    peak = 0
+
+    for op, s, m in event_order(schedule, N_loop, N_mb):
+        if op == OP_F:
+            t = x[m] if s == 0 else hand[m]
+            for l in stage_layers(N_layers, N_loop, s):
+                t, caches[(l, m)] = L.layer_fwd(params[l], t, N_heads, eps, causal, gelu_form)
+            hand[m] = t
+            if s == N_loop - 1:
+                y[m] = t
+        elif op == OP_B:
+            d = dy[m] if s == N_loop - 1 else bhand[m]
+            for l in reversed(stage_layers(N_layers, N_loop, s)):
+                d, G = L.layer_bwd(params[l], caches.pop((l, m)), d, N_heads)
+                if grads[l] is None:
+                    grads[l] = G                       # first micro-batch writes
+                else:
+                    for k in G:
+                        grads[l][k] = grads[l][k] + G[k]   # later ones add, ascending m
+            bhand[m] = d
+            if s == 0:
+                dx[m] = d
+        else:  # OP_OPT: this stage's gradients are final
+            if adam is not None:
+                for l in stage_layers(N_layers, N_loop, s):
+                    for k in params[l]:
+                        mm, vv = adam_state[l][k]
+                        w2, m2, v2 = adam_update(params[l][k], grads[l][k], mm, vv, adam["t"], adam["lr"],
+                                                 adam["beta1"], adam["beta2"], adam["adam_eps"],
+                                                 adam.get("weight_decay", 0.0))
+                        new_params[l][k] = w2
+                        new_state[l][k] = (m2, v2)
+        live = len(caches)
+        peak = max(peak, live)
+        trace.append((op, s, m, live))
+    return dict(y=y, dx=dx, grads=grads, trace=trace, peak_ckpt=peak,
+                new_params=new_params, new_adam_state=new_state)
+
+
+def run_one_big_batch(params, x, dy, N_heads, eps=1e-5, causal=True, gelu_form="tanh"):
+    """The same gradient computed without any schedule: all N_mb*S_mb samples as
+    one batch through all layers.  Used only as a pin for run_step."""
+    N_mb, S_mb = x.shape[:2]
+    t = x.reshape((N_mb * S_mb,) + x.shape[2:])
+    d = dy.reshape(t.shape)
+    caches = []
+    for p in params:
+        t, c = L.layer_fwd(p, t, N_heads, eps, causal, gelu_form)
+        caches.append(c)
+    grads = [None] * len(params)
+    for l in reversed(range(len(params))):
+        d, grads[l] = L.layer_bwd(params[l], caches[l], d, N_heads)
+    return dict(y=t.reshape(x.shape), dx=d.reshape(x.shape), grads=grads)
