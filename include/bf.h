@@ -1,0 +1,171 @@
+/*
+ * libbf — one pipeline rank's training step in breadth-first or depth-first order,
+ * on one MI355X (gfx950).
+ *
+ * Method: "Breadth-First Pipeline Parallelism" (arXiv 2211.05953).  A rank holds
+ * N_loop looped stages (Sec. 4.1, N_loop = N_stage / N_PP), each a contiguous chunk
+ * of identical transformer layers (App. A.1), and pushes N_mb micro-batches of size
+ * S_mb through them.  On one device the stages are chained, which is the N_PP = 1
+ * case of the method (App. C, breadth-first gradient accumulation).
+ *
+ *   BF: every micro-batch through a stage before the next stage (forward-first);
+ *       a stage's gradient is final after its N_mb backwards and its fused Adam
+ *       step runs there, overlapped with the backward of the earlier stages.
+ *   DF: each micro-batch through the whole forward and backward before the next
+ *       (App. C); gradients are final only in the last micro-batch's backward.
+ *
+ * All pointers named "device" are HIP device pointers on the current device, all
+ * pointers named "host" are ordinary host memory.  The library never allocates
+ * device memory: the caller hands it one workspace of bf_workspace_bytes().  No
+ * call throws or aborts; every call returns a bf_status and bf_last_error() gives
+ * the reason for the last failure on the calling thread.
+ */
+#ifndef BF_H
+#define BF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bf_stack bf_stack; /* opaque; owned by the library, lives in host memory */
+
+typedef enum { BF_OK = 0, BF_EINVAL = -1, BF_ENOMEM = -2, BF_ESTATE = -3, BF_EDEVICE = -4 } bf_status;
+typedef enum { BF_SCHED_BF = 0, BF_SCHED_DF = 1 } bf_schedule;
+/* BF_BF16: bf16 weights and activations in HBM, fp32 accumulators, fp32 master weights,
+ * fp32 main-grads, fp32 Adam (mixed precision, App. A.1).  BF_FP32: everything fp32. */
+typedef enum { BF_FP32 = 0, BF_BF16 = 1 } bf_dtype;
+/* BF_CKPT_LAYER keeps one activation checkpoint (the layer input) per layer and
+ * micro-batch and recomputes the layer's forward before its backward (App. A.2.2,
+ * Eq. mem_ckpt).  BF_CKPT_NONE keeps every activation the backward needs. */
+typedef enum { BF_CKPT_NONE = 0, BF_CKPT_LAYER = 1 } bf_ckpt;
+/* Kernel family.  BF_KERNELS_AUTO picks the MFMA kernels wherever the shape allows in
+ * bf16 mode; BF_KERNELS_PLAIN forces the simple fp32-FMA kernels (any shape, slow). */
+typedef enum { BF_KERNELS_AUTO = 0, BF_KERNELS_PLAIN = 1 } bf_kernels;
+
+/* Parameter tensors of one layer (App. A.1: attention + two-layer MLP).  Row-major.
+ * W_QKV columns are [Q | K | V]; head a owns columns a*S_head .. (a+1)*S_head-1 of
+ * each third.  y = x W + b for every linear. */
+typedef enum {
+  BF_LN1_G = 0, BF_LN1_B = 1,
+  BF_W_QKV = 2, /* [S_hidden, 3 S_hidden] */ BF_B_QKV = 3,
+  BF_W_O = 4,   /* [S_hidden, S_hidden]   */ BF_B_O = 5,
+  BF_LN2_G = 6, BF_LN2_B = 7,
+  BF_W_FC1 = 8, /* [S_hidden, S_mlp]      */ BF_B_FC1 = 9,
+  BF_W_FC2 = 10,/* [S_mlp, S_hidden]      */ BF_B_FC2 = 11,
+  BF_N_TENSORS = 12
+} bf_tensor_id;
+
+typedef struct {
+  int32_t S_hidden, N_heads, S_head, S_mlp, S_seq; /* N_heads * S_head == S_hidden */
+  int32_t N_layers;                                /* layers held by this rank */
+  int32_t N_mb_max, S_mb_max;                      /* size the pre-allocated arena (App. D.2) */
+  int32_t dtype;                                   /* bf_dtype */
+  int32_t ckpt_mode;                               /* bf_ckpt */
+  int32_t causal;                                  /* 1: mask j > i (GPT); 0: bidirectional */
+  int32_t kernels;                                 /* bf_kernels */
+  int32_t queue_depth;  /* > 0: the host never runs more than this many stage-level ops ahead of
+                           the device (App. D.2, bounded kernel queue); 0: unbounded */
+  uint64_t seed;        /* device-side initialisation: weights ~ N(0, init_std), biases 0, LN gain 1 */
+  float init_std;
+  float ln_eps;
+  float lr, beta1, beta2, adam_eps, weight_decay;  /* Adam, bias-corrected, decoupled decay */
+} bf_config;
+
+/* Integer event trace of a step. op: 0 forward, 1 backward, 2 optimizer (mb = -1).
+ * live_ckpt: activation checkpoints (one per layer and micro-batch) alive after the
+ * event, the count of Eq. mem_ckpt. */
+typedef struct { int32_t op, stage, mb, live_ckpt; } bf_event;
+
+typedef struct {
+  double gpu_ms;            /* whole step on the device (events on the caller's stream) */
+  double adam_ms;           /* sum of the fused Adam launches (side stream in BF) */
+  double flops_model;       /* 3 x forward (linears + full attention), per step */
+  double flops_paper;       /* Eq. compute x S_seq: 4 x forward */
+  double flops_executed;    /* what the kernels ran: causal half, in-kernel recompute, checkpoint recompute */
+  int64_t peak_ckpt_count;  /* Eq. mem_ckpt first factor as executed */
+  int64_t peak_ckpt_bytes;  /* peak_ckpt_count x bytes of one [S_mb, S_seq, S_hidden] tensor */
+  int64_t peak_act_bytes;   /* peak bytes of live stored activations (checkpoints included) */
+  int64_t state_bytes;      /* weights, Adam moments, main-grads, low-precision weights */
+  int32_t n_events;
+  int32_t timed;            /* 1 if gpu_ms / adam_ms are valid (bf_run_step ... timing != 0) */
+} bf_step_report;
+
+typedef struct {
+  int64_t makespan, busy;   /* ticks; busy = N_loop N_mb (t_fwd + t_bwd) */
+  int64_t bubble_num, bubble_den; /* (makespan - busy) / busy in lowest terms: Eq. bubble, Eq. bubble_looped */
+  int64_t peak_live;        /* peak live (stage, micro-batch) inputs on this rank */
+} bf_sched_stats;
+
+/* Bytes of device workspace bf_create_stack needs for cfg; 0 if cfg is invalid. */
+size_t bf_workspace_bytes(const bf_config* cfg);
+
+/* Builds a stack inside `workspace` (device, 256-byte aligned, `bytes` long, owned by
+ * the caller and kept alive until bf_destroy_stack).  Initialises the parameters on the
+ * device from cfg->seed and zeroes the Adam moments.  `stream`: a hipStream_t (NULL =
+ * default stream) on which the initialisation is enqueued.
+ * BF_EINVAL: bad cfg (N_heads*S_head != S_hidden, sizes < 1, unknown enum ...);
+ * BF_ENOMEM: bytes too small; BF_EDEVICE: a HIP call failed. */
+bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, void* stream, bf_stack** out);
+bf_status bf_destroy_stack(bf_stack* s);
+
+/* Number of elements of tensor `tensor_id` of one layer (0 if unknown). */
+size_t bf_tensor_elems(const bf_stack* s, int tensor_id);
+
+/* Copy n = bf_tensor_elems fp32 values between host memory and the fp32 master weights
+ * (set also refreshes the low-precision copy and leaves the Adam moments alone).
+ * Synchronous.  BF_EINVAL on a bad layer / tensor / n. */
+bf_status bf_set_params(bf_stack* s, int layer, int tensor_id, const float* host_src, size_t n);
+bf_status bf_get_params(bf_stack* s, int layer, int tensor_id, float* host_dst, size_t n);
+/* fp32 main-grads accumulated by the last bf_run_step (sum over its micro-batches,
+ * ascending).  BF_ESTATE before the first step. */
+bf_status bf_get_grads(bf_stack* s, int layer, int tensor_id, float* host_dst, size_t n);
+/* Adam moments: which = 0 first moment, 1 second moment. */
+bf_status bf_get_moments(bf_stack* s, int layer, int tensor_id, int which, float* host_dst, size_t n);
+/* Zero the Adam moments and reset the step counter to 0.  Synchronous. */
+bf_status bf_reset_optimizer(bf_stack* s);
+
+/* One training step of the rank (Sec. 4.1; App. C).
+ *   schedule     BF_SCHED_BF or BF_SCHED_DF
+ *   N_loop       stages; must divide N_layers
+ *   N_mb, S_mb   1..N_mb_max, 1..S_mb_max
+ *   x            device, [N_mb, S_mb, S_seq, S_hidden] in the stack's dtype (bf16 or fp32): stage-0 input
+ *   dy           device, same shape/dtype: gradient of the loss w.r.t. the last stage's output
+ *   y, dx        device outputs, same shape/dtype; either may be NULL
+ *   apply_optimizer  0: gradients only; 1: fused Adam per stage when its gradient is final
+ *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end)
+ *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
+ *                on it (unless timing != 0); the library's side stream joins it before returning
+ *                control of the stream to later work.
+ *   report       may be NULL
+ * Main-grads stay readable until the next step starts.  x, dy, y, dx must not alias the workspace.
+ * BF_EINVAL: N_layers % N_loop != 0, sizes out of range, null x / dy, unknown schedule. */
+bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
+                      const void* x, const void* dy, void* y, void* dx,
+                      int apply_optimizer, int timing, void* stream, bf_step_report* report);
+
+/* Integer event trace of the last bf_run_step: copies min(cap, n) events, *n = total. */
+bf_status bf_get_trace(const bf_stack* s, bf_event* dst, size_t cap, size_t* n);
+
+/* Pure host arithmetic, no device needed: the order in which rank `rank` of an N_PP-deep
+ * looped pipeline runs its ops (stage index in the trace is the GLOBAL stage
+ * l*N_PP + rank) and a unit-time simulation of all ranks (forward t_fwd ticks, backward
+ * t_bwd, transfers free) giving the bubble of Eq. bubble / Eq. bubble_looped.
+ * BF needs N_mb >= N_PP; DF needs N_mb % N_PP == 0 (Sec. 4.1).  No optimizer events.
+ * dst may be NULL (cap 0) to query *n. */
+bf_status bf_schedule_trace(int schedule, int N_PP, int N_loop, int N_mb, int rank,
+                            int t_fwd, int t_bwd, bf_event* dst, size_t cap, size_t* n,
+                            bf_sched_stats* stats);
+
+/* Exact parameter count of the stack (biases and LayerNorms included). */
+int64_t bf_param_count(const bf_config* cfg);
+
+/* Reason for the last failure on this thread ("" if none). */
+const char* bf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BF_H */

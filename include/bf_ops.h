@@ -1,0 +1,76 @@
+/*
+ * libbf — the single kernels of the transformer layer (App. A.1 of arXiv 2211.05953:
+ * self-attention with N_heads heads of size S_head followed by a two-layer MLP), exported
+ * one by one so that each can be checked against the CPU oracle and timed on its own.
+ * bf_run_step (bf.h) chains exactly these.
+ *
+ * All tensor pointers are device pointers; row-major; `dtype` is a bf_dtype and names the
+ * storage type of activations and weights (bf16 or fp32; accumulation is always fp32).
+ * bias / LayerNorm parameters / statistics / lse / main-grads are fp32.
+ * `kernels` is a bf_kernels value.  `stream` is a hipStream_t (NULL = default stream);
+ * every call is asynchronous on it.  Nothing is allocated; the caller owns every buffer.
+ * Errors: BF_EINVAL for bad sizes / null pointers / unknown enums, BF_EDEVICE if the
+ * launch fails; bf_last_error() has the text.
+ */
+#ifndef BF_OPS_H
+#define BF_OPS_H
+
+#include "bf.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Operand layouts of the three linear-layer products (8 flop per parameter and token in
+ * total, App. A.1):
+ *   BF_NN  forward  C[M,N] = A[M,K] B[K,N]
+ *   BF_NT  dgrad    C[M,N] = A[M,K] Bt[N,K]^T          (B passed as [N,K])
+ *   BF_TN  wgrad    C[M,N] = At[K,M]^T B[K,N]          (A passed as [K,M]; C is fp32) */
+typedef enum { BF_NN = 0, BF_NT = 1, BF_TN = 2 } bf_layout;
+
+/* What happens to the fp32 accumulator acc[m,n] before it is stored:
+ *   BF_EPI_NONE       C = acc
+ *   BF_EPI_BIAS       C = acc + bias[n]
+ *   BF_EPI_BIAS_RES   C = acc + bias[n] + R[m,n]
+ *   BF_EPI_BIAS_GELU  C = acc + bias[n] (rounded to dtype), C2 = gelu_tanh(C)
+ *   BF_EPI_GELU_BWD   C = acc * gelu_tanh'(R[m,n])
+ *   BF_EPI_ACCUM      fp32 C = (accumulate ? C : 0) + acc        (main-grad accumulation) */
+typedef enum { BF_EPI_NONE = 0, BF_EPI_BIAS = 1, BF_EPI_BIAS_RES = 2, BF_EPI_BIAS_GELU = 3,
+               BF_EPI_GELU_BWD = 4, BF_EPI_ACCUM = 5 } bf_epilogue;
+
+bf_status bf_op_gemm(int dtype, int kernels, int layout, int epilogue, int M, int N, int K,
+                     const void* A, const void* B, void* C, const float* bias, const void* R, void* C2,
+                     int accumulate, void* stream);
+/* 1 if the MFMA kernel takes this problem in bf16 mode, 0 if the plain kernel would run. */
+int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
+
+/* y = (x - mean) * rstd * g + b per row of x[T,h]; stats[T][2] = (mean, rstd), rstd = 1/sqrt(var + eps). */
+bf_status bf_op_layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps,
+                              void* y, float* stats, void* stream);
+/* dx[T,h] = LN'(dy) (+ dres if non-null); dg[h], db[h] (fp32) = or += the column sums. */
+bf_status bf_op_layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g,
+                              const float* stats, const void* dres, void* dx, float* dg, float* db,
+                              int accumulate, void* stream);
+/* out[N] (fp32) = or += sum over rows of dY[T,N]: the bias gradient. */
+bf_status bf_op_colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, void* stream);
+
+/* Multi-head attention.  qkv [S_mb, S_seq, 3 S_hidden] packed [Q | K | V] with head a at
+ * columns a*S_head.. of each third; ctx [S_mb, S_seq, S_hidden]; lse [S_mb, N_heads, S_seq] =
+ * log-sum-exp of a row's scaled (1/sqrt(S_head)) and masked scores.  causal = 1 masks j > i. */
+bf_status bf_op_attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, void* ctx, float* lse, void* stream);
+/* dqkv from dctx; delta is fp32 scratch of S_mb * N_heads * S_seq elements. */
+bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                              void* dqkv, float* delta, void* stream);
+int bf_op_attention_uses_mfma(int S_seq, int S_head);
+
+/* Fused Adam over n contiguous fp32 parameters (bias-corrected, decoupled weight decay), step t >= 1;
+ * w_lp: bf16 copy of w to refresh, or NULL. */
+bf_status bf_op_adam(size_t n, float* w, float* m, float* v, const float* g, void* w_lp, int t,
+                     float lr, float beta1, float beta2, float adam_eps, float weight_decay, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BF_OPS_H */

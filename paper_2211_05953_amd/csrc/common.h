@@ -1,0 +1,92 @@
+// Shared declarations of the HIP path: element types, launch helpers, error plumbing.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/bf.h"
+
+namespace bf {
+
+typedef __bf16 bf16_t;
+
+// GEMM operand layouts (all row-major storage):
+//   NN  A[M,K]            B[K,N]   forward  Y = X W
+//   NT  A[M,K]            B as [N,K]  dgrad  dX = dY W^T
+//   TN  A as [K,M]        B[K,N]   wgrad   G = X^T dY   (fp32 output, optional accumulate)
+enum Layout { L_NN = 0, L_NT = 1, L_TN = 2 };
+
+// What is done to the fp32 accumulator before it is stored.
+enum Epilogue {
+  E_NONE = 0,       // C = acc
+  E_BIAS = 1,       // C = acc + bias[n]
+  E_BIAS_RES = 2,   // C = acc + bias[n] + R[m,n]
+  E_BIAS_GELU = 3,  // C = acc + bias[n];  C2 = gelu(C)
+  E_GELU_BWD = 4,   // C = acc * gelu'(R[m,n])      (R holds the pre-activation)
+  E_ACCUM = 5       // fp32 C = (accumulate ? C : 0) + acc
+};
+
+struct GemmArgs {
+  int M, N, K;
+  const void* A;
+  const void* B;
+  void* C;
+  const float* bias;  // [N] fp32 or null
+  const void* R;      // [M,N] in the activation dtype or null
+  void* C2;           // second output of E_BIAS_GELU
+  int accumulate;     // E_ACCUM only
+};
+
+void set_error(const char* fmt, ...);
+
+#define BF_HIP_CHECK(expr)                                                        \
+  do {                                                                            \
+    hipError_t e_ = (expr);                                                       \
+    if (e_ != hipSuccess) {                                                       \
+      bf::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return BF_EDEVICE;                                                          \
+    }                                                                             \
+  } while (0)
+
+// ---- kernel launchers (each returns BF_OK / BF_EINVAL / BF_EDEVICE) -------------------
+// dtype: BF_FP32 or BF_BF16 (activation storage type).
+bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStream_t st);
+// true if the MFMA kernel covers this problem (bf16, sizes multiples of its tiles)
+bool gemm_mfma_supported(int layout, int epi, int M, int N, int K);
+bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st);
+bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st);
+
+bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps,
+                        void* y, float* stats /*[T][2]: mean, rstd*/, hipStream_t st);
+// dx = LN'(dy) (+ dres if non-null);  dg/db (fp32) = or += column sums.
+bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g,
+                        const float* stats, const void* dres, void* dx, float* dg, float* db,
+                        int accumulate, hipStream_t st);
+bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, hipStream_t st);
+
+bf_status attention_fwd_plain(int dtype, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, void* ctx, float* lse, hipStream_t st);
+bf_status attention_bwd_plain(int dtype, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                              void* dqkv, float* delta, hipStream_t st);
+bool attention_mfma_supported(int S_seq, int S_head);
+bf_status attention_fwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                             const void* qkv, void* ctx, float* lse, hipStream_t st);
+bf_status attention_bwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                             const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                             void* dqkv, float* delta, hipStream_t st);
+bf_status attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                        const void* qkv, void* ctx, float* lse, hipStream_t st);
+bf_status attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                        const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                        void* dqkv, float* delta, hipStream_t st);
+
+// Fused Adam over n contiguous parameters; w_lp (bf16 copy) may be null.
+bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t,
+                    float lr, float beta1, float beta2, float eps, float wd, hipStream_t st);
+bf_status cast_f32_to_bf16(size_t n, const float* src, bf16_t* dst, hipStream_t st);
+bf_status fill_f32(size_t n, float* dst, float value, hipStream_t st);
+// N(0, std) from a counter-based hash of (seed, index)
+bf_status init_normal(size_t n, float* dst, uint64_t seed, float std, hipStream_t st);
+
+}  // namespace bf

@@ -1,0 +1,372 @@
+// HBM-bound kernels of the layer: LayerNorm forward/backward, column sums for bias
+// gradients, fused Adam with low-precision recast, initialisation helpers.
+// Row kernels: one 256-thread workgroup per token row, 16-byte vector accesses when
+// the row length allows, wavefront (64-lane) shuffles + one LDS hop for the reductions.
+// Column kernels: fixed reduction order, so results do not depend on scheduling.
+#include "common.h"
+
+namespace bf {
+
+namespace {
+
+constexpr int ROW_THREADS = 256;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Sum over a 256-thread workgroup; every thread gets the result. `red` holds 4 floats.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();  // protects `red` against the previous use
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <typename T, int VEC>
+struct alignas(sizeof(T) * VEC > 16 ? 16 : sizeof(T) * VEC) Vec {
+  T v[VEC];
+};
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_vec(const T* p, float (&out)[VEC]) {
+  typedef Vec<T, VEC> V;
+  V t = *reinterpret_cast<const V*>(p);
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) out[i] = (float)t.v[i];
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void store_vec(T* p, const float (&in)[VEC]) {
+  typedef Vec<T, VEC> V;
+  V t;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) t.v[i] = (T)in[i];
+  *reinterpret_cast<V*>(p) = t;
+}
+
+// ------------------------------------------------------------------ LayerNorm forward
+template <typename T, int VEC>
+__global__ __launch_bounds__(ROW_THREADS) void ln_fwd_kernel(const T* __restrict__ x, const float* __restrict__ g,
+                                                             const float* __restrict__ b, T* __restrict__ y,
+                                                             float* __restrict__ stats, int h, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * (size_t)h;
+  T* yr = y + row * (size_t)h;
+  float s = 0.f;
+  for (int i = threadIdx.x * VEC; i < h; i += ROW_THREADS * VEC) {
+    float v[VEC];
+    load_vec<T, VEC>(xr + i, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) s += v[j];
+  }
+  const float mean = block_sum(s, red) / (float)h;
+  float q = 0.f;
+  for (int i = threadIdx.x * VEC; i < h; i += ROW_THREADS * VEC) {
+    float v[VEC];
+    load_vec<T, VEC>(xr + i, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      const float d = v[j] - mean;
+      q += d * d;
+    }
+  }
+  const float var = block_sum(q, red) / (float)h;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (threadIdx.x == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+  for (int i = threadIdx.x * VEC; i < h; i += ROW_THREADS * VEC) {
+    float v[VEC], gg[VEC], bb[VEC], o[VEC];
+    load_vec<T, VEC>(xr + i, v);
+    load_vec<float, VEC>(g + i, gg);
+    load_vec<float, VEC>(b + i, bb);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) o[j] = (v[j] - mean) * rstd * gg[j] + bb[j];
+    store_vec<T, VEC>(yr + i, o);
+  }
+}
+
+// ------------------------------------------------------ LayerNorm backward, input gradient
+// dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)) [+ dres],  dxhat = dy * g
+template <typename T, int VEC>
+__global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                const float* __restrict__ g,
+                                                                const float* __restrict__ stats,
+                                                                const T* __restrict__ dres, T* __restrict__ dx, int h) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* dyr = dy + row * (size_t)h;
+  const T* xr = x + row * (size_t)h;
+  const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+  float s1 = 0.f, s2 = 0.f;
+  for (int i = threadIdx.x * VEC; i < h; i += ROW_THREADS * VEC) {
+    float d[VEC], v[VEC], gg[VEC];
+    load_vec<T, VEC>(dyr + i, d);
+    load_vec<T, VEC>(xr + i, v);
+    load_vec<float, VEC>(g + i, gg);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      const float dxh = d[j] * gg[j];
+      s1 += dxh;
+      s2 += dxh * ((v[j] - mean) * rstd);
+    }
+  }
+  s1 = block_sum(s1, red) / (float)h;
+  s2 = block_sum(s2, red) / (float)h;
+  for (int i = threadIdx.x * VEC; i < h; i += ROW_THREADS * VEC) {
+    float d[VEC], v[VEC], gg[VEC], r[VEC], o[VEC];
+    load_vec<T, VEC>(dyr + i, d);
+    load_vec<T, VEC>(xr + i, v);
+    load_vec<float, VEC>(g + i, gg);
+    if (dres) {
+      load_vec<T, VEC>(dres + row * (size_t)h + i, r);
+    } else {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) r[j] = 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      const float xh = (v[j] - mean) * rstd;
+      o[j] = rstd * (d[j] * gg[j] - s1 - xh * s2) + r[j];
+    }
+    store_vec<T, VEC>(dx + row * (size_t)h + i, o);
+  }
+}
+
+// ---------------------------------------------------- column reductions (fixed order)
+// Workgroup = 32 column groups x 8 row groups; thread (cx, ry) owns VEC adjacent columns
+// and rows ry, ry+8, ...  Partial sums meet in LDS and are added in ascending ry.
+// MODE 0: out[c] = sum_t dY[t,c]
+// MODE 1: dg[c] = sum_t dY[t,c] * xhat[t,c],  db[c] = sum_t dY[t,c]
+template <typename T, int VEC, int MODE>
+__global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ dY, const T* __restrict__ x,
+                                                         const float* __restrict__ stats, float* __restrict__ out0,
+                                                         float* __restrict__ out1, int T_rows, int N, int accumulate) {
+  __shared__ float part[2][8][32 * VEC];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int c0 = (blockIdx.x * 32 + cx) * VEC;
+  float a0[VEC], a1[VEC];
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) a0[j] = a1[j] = 0.f;
+  if (c0 < N) {
+    for (int t = ry; t < T_rows; t += 8) {
+      float d[VEC];
+      load_vec<T, VEC>(dY + (size_t)t * N + c0, d);
+      if (MODE == 1) {
+        float v[VEC];
+        load_vec<T, VEC>(x + (size_t)t * N + c0, v);
+        const float mean = stats[2 * t], rstd = stats[2 * t + 1];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          a0[j] += d[j] * ((v[j] - mean) * rstd);
+          a1[j] += d[j];
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) a0[j] += d[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    part[0][ry][cx * VEC + j] = a0[j];
+    if (MODE == 1) part[1][ry][cx * VEC + j] = a1[j];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 32 * VEC; c += 256) {
+    const int col = blockIdx.x * 32 * VEC + c;
+    if (col >= N) continue;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      s0 += part[0][r][c];
+      if (MODE == 1) s1 += part[1][r][c];
+    }
+    out0[col] = accumulate ? out0[col] + s0 : s0;
+    if (MODE == 1) out1[col] = accumulate ? out1[col] + s1 : s1;
+  }
+}
+
+// ------------------------------------------------------------------------- fused Adam
+// One pass: m, v, w updated in fp32; bf16 copy of w rewritten (mixed precision, App. A.1).
+template <int VEC>
+__global__ __launch_bounds__(256) void adam_kernel(size_t n, float* __restrict__ w, float* __restrict__ m,
+                                                   float* __restrict__ v, const float* __restrict__ g,
+                                                   bf16_t* __restrict__ w_lp, float lr, float beta1, float beta2,
+                                                   float eps, float wd, float c1, float c2) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x * VEC;
+  for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < n; i += stride) {
+    float ww[VEC], mm[VEC], vv[VEC], gg[VEC];
+    load_vec<float, VEC>(w + i, ww);
+    load_vec<float, VEC>(m + i, mm);
+    load_vec<float, VEC>(v + i, vv);
+    load_vec<float, VEC>(g + i, gg);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      mm[j] = beta1 * mm[j] + (1.f - beta1) * gg[j];
+      vv[j] = beta2 * vv[j] + (1.f - beta2) * gg[j] * gg[j];
+      const float mhat = mm[j] * c1, vhat = vv[j] * c2;
+      ww[j] = ww[j] - lr * (mhat / (sqrtf(vhat) + eps) + wd * ww[j]);
+    }
+    store_vec<float, VEC>(w + i, ww);
+    store_vec<float, VEC>(m + i, mm);
+    store_vec<float, VEC>(v + i, vv);
+    if (w_lp) store_vec<bf16_t, VEC>(w_lp + i, ww);
+  }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void cast_kernel(size_t n, const float* __restrict__ src, bf16_t* __restrict__ dst) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x * VEC;
+  for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < n; i += stride) {
+    float t[VEC];
+    load_vec<float, VEC>(src + i, t);
+    store_vec<bf16_t, VEC>(dst + i, t);
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(size_t n, float* __restrict__ dst, float value) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = value;
+}
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// Counter-based N(0, std): two uniforms from a hash of (seed, index), Box-Muller.
+__global__ __launch_bounds__(256) void init_normal_kernel(size_t n, float* __restrict__ dst, uint64_t seed, float std) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    const uint64_t r = mix64(seed ^ mix64(i));
+    const float u1 = ((float)(uint32_t)(r >> 40) + 1.0f) * (1.0f / 16777217.0f);  // (0, 1)
+    const float u2 = (float)(uint32_t)((r >> 8) & 0xFFFFFF) * (1.0f / 16777216.0f);
+    dst[i] = std * sqrtf(-2.0f * logf(u1)) * cosf(6.283185307179586f * u2);
+  }
+}
+
+inline int grid_for(size_t n, int per_block) {
+  size_t g = (n + per_block - 1) / per_block;
+  if (g > 256 * 16) g = 256 * 16;  // 256 CUs, a few workgroups each; kernels grid-stride
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+#define BF_LAUNCH_CHECK()                                 \
+  do {                                                    \
+    hipError_t e_ = hipGetLastError();                    \
+    if (e_ != hipSuccess) {                               \
+      set_error("kernel launch failed: %s (%s:%d)", hipGetErrorString(e_), __FILE__, __LINE__); \
+      return BF_EDEVICE;                                  \
+    }                                                     \
+  } while (0)
+
+bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps, void* y,
+                        float* stats, hipStream_t st) {
+  if (T < 1 || h < 1 || !x || !g || !b || !y || !stats) { set_error("layernorm_fwd: bad argument"); return BF_EINVAL; }
+  if (dtype == BF_BF16) {
+    const bool vec = h % 8 == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b);
+    if (vec) ln_fwd_kernel<bf16_t, 8><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+    else ln_fwd_kernel<bf16_t, 1><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+  } else {
+    const bool vec = h % 4 == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b);
+    if (vec) ln_fwd_kernel<float, 4><<<T, ROW_THREADS, 0, st>>>((const float*)x, g, b, (float*)y, stats, h, eps);
+    else ln_fwd_kernel<float, 1><<<T, ROW_THREADS, 0, st>>>((const float*)x, g, b, (float*)y, stats, h, eps);
+  }
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+template <typename T, int VEC>
+static void launch_ln_bwd(int T_rows, int h, const void* dy, const void* x, const float* g, const float* stats,
+                          const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st) {
+  ln_bwd_dx_kernel<T, VEC><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
+  const int blocks = (h + 32 * VEC - 1) / (32 * VEC);
+  col_reduce_kernel<T, VEC, 1><<<blocks, 256, 0, st>>>((const T*)dy, (const T*)x, stats, dg, db, T_rows, h, accumulate);
+}
+
+bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g, const float* stats,
+                        const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st) {
+  if (T < 1 || h < 1 || !dy || !x || !g || !stats || !dx || !dg || !db) { set_error("layernorm_bwd: bad argument"); return BF_EINVAL; }
+  const bool al = aligned16(dy) && aligned16(x) && aligned16(g) && aligned16(dx) && (!dres || aligned16(dres));
+  if (dtype == BF_BF16) {
+    if (al && h % 8 == 0) launch_ln_bwd<bf16_t, 8>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);
+    else launch_ln_bwd<bf16_t, 1>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);
+  } else {
+    if (al && h % 4 == 0) launch_ln_bwd<float, 4>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);
+    else launch_ln_bwd<float, 1>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);
+  }
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, hipStream_t st) {
+  if (T < 1 || N < 1 || !dY || !out) { set_error("colsum: bad argument"); return BF_EINVAL; }
+  if (dtype == BF_BF16) {
+    if (aligned16(dY) && N % 8 == 0)
+      col_reduce_kernel<bf16_t, 8, 0><<<(N + 255) / 256, 256, 0, st>>>((const bf16_t*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+    else
+      col_reduce_kernel<bf16_t, 1, 0><<<(N + 31) / 32, 256, 0, st>>>((const bf16_t*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+  } else {
+    if (aligned16(dY) && N % 4 == 0)
+      col_reduce_kernel<float, 4, 0><<<(N + 127) / 128, 256, 0, st>>>((const float*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+    else
+      col_reduce_kernel<float, 1, 0><<<(N + 31) / 32, 256, 0, st>>>((const float*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+  }
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t, float lr, float beta1,
+                    float beta2, float eps, float wd, hipStream_t st) {
+  if (n == 0) return BF_OK;
+  if (!w || !m || !v || !g || t < 1) { set_error("adam_step: bad argument"); return BF_EINVAL; }
+  // bias corrections in double on the host, applied as multipliers
+  const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
+  const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+  const bool vec = n % 4 == 0 && aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
+                   (!w_lp || ((uintptr_t)w_lp & 7) == 0);
+  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2);
+  else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status cast_f32_to_bf16(size_t n, const float* src, bf16_t* dst, hipStream_t st) {
+  if (n == 0) return BF_OK;
+  const bool vec = n % 4 == 0 && aligned16(src) && ((uintptr_t)dst & 7) == 0;
+  if (vec) cast_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, src, dst);
+  else cast_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, src, dst);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status fill_f32(size_t n, float* dst, float value, hipStream_t st) {
+  if (n == 0) return BF_OK;
+  fill_kernel<<<grid_for(n, 256), 256, 0, st>>>(n, dst, value);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status init_normal(size_t n, float* dst, uint64_t seed, float std, hipStream_t st) {
+  if (n == 0) return BF_OK;
+  init_normal_kernel<<<grid_for(n, 256), 256, 0, st>>>(n, dst, seed, std);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+}  // namespace bf

@@ -1,0 +1,66 @@
+// C-ABI wrappers of the single kernels (include/bf_ops.h).
+#include "../../include/bf_ops.h"
+#include "common.h"
+
+using namespace bf;
+
+static bool dtype_ok(int dtype, int kernels) {
+  if (dtype != BF_FP32 && dtype != BF_BF16) { set_error("unknown dtype %d", dtype); return false; }
+  if (kernels != BF_KERNELS_AUTO && kernels != BF_KERNELS_PLAIN) { set_error("unknown kernels %d", kernels); return false; }
+  return true;
+}
+
+extern "C" {
+
+bf_status bf_op_gemm(int dtype, int kernels, int layout, int epilogue, int M, int N, int K, const void* A, const void* B,
+                     void* C, const float* bias, const void* R, void* C2, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (epilogue == E_ACCUM && layout != L_TN) { set_error("BF_EPI_ACCUM goes with BF_TN"); return BF_EINVAL; }
+  if (epilogue != E_ACCUM && layout == L_TN) { set_error("BF_TN goes with BF_EPI_ACCUM"); return BF_EINVAL; }
+  GemmArgs a{M, N, K, A, B, C, bias, R, C2, accumulate};
+  return gemm(dtype, kernels, layout, epilogue, a, (hipStream_t)stream);
+}
+
+int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K) {
+  return gemm_mfma_supported(layout, epilogue, M, N, K) ? 1 : 0;
+}
+
+bf_status bf_op_layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps, void* y,
+                              float* stats, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return layernorm_fwd(dtype, T, h, x, g, b, eps, y, stats, (hipStream_t)stream);
+}
+
+bf_status bf_op_layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g, const float* stats,
+                              const void* dres, void* dx, float* dg, float* db, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return layernorm_bwd(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, (hipStream_t)stream);
+}
+
+bf_status bf_op_colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return colsum(dtype, T, N, dY, out, accumulate, (hipStream_t)stream);
+}
+
+bf_status bf_op_attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, void* ctx, float* lse, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  return attention_fwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, (hipStream_t)stream);
+}
+
+bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                              const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                              float* delta, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  return attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta,
+                       (hipStream_t)stream);
+}
+
+int bf_op_attention_uses_mfma(int S_seq, int S_head) { return attention_mfma_supported(S_seq, S_head) ? 1 : 0; }
+
+bf_status bf_op_adam(size_t n, float* w, float* m, float* v, const float* g, void* w_lp, int t, float lr, float beta1,
+                     float beta2, float adam_eps, float weight_decay, void* stream) {
+  return adam_step(n, w, m, v, g, (bf16_t*)w_lp, t, lr, beta1, beta2, adam_eps, weight_decay, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,643 @@
+// The rank's layer stack: workspace layout, parameter access, and the stream scheduler
+// that issues one training step in breadth-first or depth-first order (Sec. 4.1, App. C).
+//
+// Workspace layout (all offsets 256-byte aligned, everything pre-allocated, App. D.2):
+//   w32 | m | v | g32           fp32 master weights, Adam moments, main-grads  [P_total each]
+//   w_lp                        bf16 copy of the weights (bf16 mode only)        [P_total]
+//   records                     stored activations, one record per (layer, micro-batch)
+//                               (BF_CKPT_NONE) or one checkpoint per (layer, micro-batch)
+//                               plus a single scratch record (BF_CKPT_LAYER)
+//   backward temporaries, per-micro-batch gradient hand-off buffers, output scratch
+// Parameters of a layer are contiguous and layers follow each other, so a stage is one
+// contiguous range and its Adam step is one launch.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "schedule.h"
+
+namespace bf {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
+
+struct Dims {
+  int h, a, d, f, S_seq, L;
+  size_t tensor_elems[BF_N_TENSORS];
+  size_t tensor_off[BF_N_TENSORS];  // element offset inside a layer
+  size_t layer_elems;               // padded
+};
+
+void fill_dims(const bf_config& c, Dims* D) {
+  D->h = c.S_hidden; D->a = c.N_heads; D->d = c.S_head; D->f = c.S_mlp; D->S_seq = c.S_seq; D->L = c.N_layers;
+  const size_t h = c.S_hidden, f = c.S_mlp;
+  const size_t n[BF_N_TENSORS] = {h, h, h * 3 * h, 3 * h, h * h, h, h, h, h * f, f, f * h, h};
+  size_t off = 0;
+  for (int i = 0; i < BF_N_TENSORS; ++i) {
+    D->tensor_elems[i] = n[i];
+    D->tensor_off[i] = off;
+    off += up(n[i], 128);  // 128 elements: 512 B in fp32, 256 B in bf16
+  }
+  D->layer_elems = off;
+}
+
+bool valid_config(const bf_config* c) {
+  if (!c) { set_error("null config"); return false; }
+  if (c->S_hidden < 1 || c->N_heads < 1 || c->S_head < 1 || c->S_mlp < 1 || c->S_seq < 1 || c->N_layers < 1 ||
+      c->N_mb_max < 1 || c->S_mb_max < 1) { set_error("config: every size must be >= 1"); return false; }
+  if ((int64_t)c->N_heads * c->S_head != c->S_hidden) { set_error("config: N_heads * S_head != S_hidden"); return false; }
+  if (c->dtype != BF_FP32 && c->dtype != BF_BF16) { set_error("config: unknown dtype"); return false; }
+  if (c->ckpt_mode != BF_CKPT_NONE && c->ckpt_mode != BF_CKPT_LAYER) { set_error("config: unknown ckpt_mode"); return false; }
+  if (c->kernels != BF_KERNELS_AUTO && c->kernels != BF_KERNELS_PLAIN) { set_error("config: unknown kernels"); return false; }
+  if (c->causal != 0 && c->causal != 1) { set_error("config: causal must be 0 or 1"); return false; }
+  if (c->queue_depth < 0) { set_error("config: queue_depth < 0"); return false; }
+  if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
+  if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
+  return true;
+}
+
+// One stored-activation record (pointers into the workspace).
+struct Record {
+  char* a;     // LN1 output            [T, h]
+  char* qkv;   //                       [T, 3h]
+  char* ctx;   // attention output      [T, h]
+  char* x1;    // x + attention branch  [T, h]
+  char* c;     // LN2 output            [T, h]
+  char* u;     // FC1 pre-activation    [T, f]
+  char* g;     // GeLU(u)               [T, f]
+  char* y;     // layer output = next layer's input (the checkpoint of the next layer) [T, h]
+  float* ln1;  // mean, rstd            [T, 2]
+  float* ln2;
+  float* lse;  //                       [S_mb, N_heads, S_seq]
+};
+
+struct WsLayout {
+  size_t P_total;
+  size_t off_w32, off_m, off_v, off_g32, off_wlp;
+  size_t rec_bytes;        // one full record (without y)
+  size_t y_bytes;          // one [T, h] tensor
+  size_t off_records;      // NONE: L * N_mb_max full records (each with y); LAYER: 1 scratch record
+  size_t n_full_records;
+  size_t off_ckpt;         // LAYER: L * N_mb_max [T, h] tensors (outputs of each layer)
+  size_t off_tmp;          // backward temporaries
+  size_t off_bhand;        // N_mb_max [T, h]
+  size_t off_scratch_out;  // [T, h] x 2: discarded outputs / ping-pong
+  size_t total;
+};
+
+struct RecSizes { size_t a, qkv, ctx, x1, c, u, g, ln1, ln2, lse, total; };
+
+RecSizes rec_sizes(const bf_config& c) {
+  const size_t es = c.dtype == BF_BF16 ? 2 : 4;
+  const size_t T = (size_t)c.S_mb_max * c.S_seq, h = c.S_hidden, f = c.S_mlp;
+  RecSizes r;
+  r.a = up(T * h * es); r.qkv = up(T * 3 * h * es); r.ctx = up(T * h * es); r.x1 = up(T * h * es);
+  r.c = up(T * h * es); r.u = up(T * f * es); r.g = up(T * f * es);
+  r.ln1 = up(T * 2 * 4); r.ln2 = up(T * 2 * 4); r.lse = up((size_t)c.S_mb_max * c.N_heads * c.S_seq * 4);
+  r.total = r.a + r.qkv + r.ctx + r.x1 + r.c + r.u + r.g + r.ln1 + r.ln2 + r.lse;
+  return r;
+}
+
+struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, total; };
+
+TmpSizes tmp_sizes(const bf_config& c) {
+  const size_t es = c.dtype == BF_BF16 ? 2 : 4;
+  const size_t T = (size_t)c.S_mb_max * c.S_seq, h = c.S_hidden, f = c.S_mlp;
+  TmpSizes t;
+  t.du = up(T * f * es); t.dc = up(T * h * es); t.dx1 = up(T * h * es); t.dctx = up(T * h * es);
+  t.dqkv = up(T * 3 * h * es); t.delta = up((size_t)c.S_mb_max * c.N_heads * c.S_seq * 4); t.ping = up(T * h * es);
+  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping;
+  return t;
+}
+
+void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
+  const size_t es = c.dtype == BF_BF16 ? 2 : 4;
+  const size_t T = (size_t)c.S_mb_max * c.S_seq;
+  Lo->P_total = D.layer_elems * (size_t)c.N_layers;
+  size_t off = 0;
+  Lo->off_w32 = off; off += up(Lo->P_total * 4);
+  Lo->off_m = off; off += up(Lo->P_total * 4);
+  Lo->off_v = off; off += up(Lo->P_total * 4);
+  Lo->off_g32 = off; off += up(Lo->P_total * 4);
+  Lo->off_wlp = off;
+  if (c.dtype == BF_BF16) off += up(Lo->P_total * 2);
+  Lo->rec_bytes = rec_sizes(c).total;
+  Lo->y_bytes = up(T * c.S_hidden * es);
+  Lo->off_records = off;
+  const size_t slots = (size_t)c.N_layers * c.N_mb_max;
+  if (c.ckpt_mode == BF_CKPT_NONE) {
+    Lo->n_full_records = slots;
+    off += slots * (Lo->rec_bytes + Lo->y_bytes);
+    Lo->off_ckpt = off;
+  } else {
+    Lo->n_full_records = 1;
+    off += Lo->rec_bytes;
+    Lo->off_ckpt = off;
+    off += slots * Lo->y_bytes;
+  }
+  Lo->off_tmp = off; off += tmp_sizes(c).total;
+  Lo->off_bhand = off; off += (size_t)c.N_mb_max * Lo->y_bytes;
+  Lo->off_scratch_out = off; off += 2 * Lo->y_bytes;
+  Lo->total = off;
+}
+
+}  // namespace
+}  // namespace bf
+
+using namespace bf;
+
+struct bf_stack {
+  bf_config cfg;
+  Dims D;
+  WsLayout Lo;
+  char* ws;
+  float *w32, *m, *v, *g32;
+  bf16_t* wlp;
+  hipStream_t side;       // Adam stream
+  hipEvent_t ev_grad_ready, ev_side_done, ev_t0, ev_t1;
+  std::vector<hipEvent_t> adam_ev;   // pairs of events per stage for timing
+  std::vector<hipEvent_t> queue_ev;  // ring for the bounded launch queue
+  std::vector<bf_event> trace;
+  int step;               // optimizer step counter
+  bool have_grads;
+  int device;
+};
+
+namespace bf {
+namespace {
+
+float* param_ptr(bf_stack* s, float* arena, int layer, int tid) {
+  return arena + (size_t)layer * s->D.layer_elems + s->D.tensor_off[tid];
+}
+
+// weight operand of the GEMMs: bf16 copy in bf16 mode, the master itself in fp32 mode
+const void* weight_ptr(bf_stack* s, int layer, int tid) {
+  const size_t off = (size_t)layer * s->D.layer_elems + s->D.tensor_off[tid];
+  return s->cfg.dtype == BF_BF16 ? (const void*)(s->wlp + off) : (const void*)(s->w32 + off);
+}
+
+Record record_at(bf_stack* s, char* base) {
+  RecSizes r = rec_sizes(s->cfg);
+  Record R;
+  char* p = base;
+  R.a = p; p += r.a; R.qkv = p; p += r.qkv; R.ctx = p; p += r.ctx; R.x1 = p; p += r.x1; R.c = p; p += r.c;
+  R.u = p; p += r.u; R.g = p; p += r.g; R.ln1 = (float*)p; p += r.ln1; R.ln2 = (float*)p; p += r.ln2;
+  R.lse = (float*)p; p += r.lse;
+  R.y = nullptr;
+  return R;
+}
+
+// Record used by (layer, mb): its own slot without checkpointing, the shared scratch record with.
+Record record_for(bf_stack* s, int layer, int mb) {
+  if (s->cfg.ckpt_mode == BF_CKPT_NONE) {
+    const size_t slot = (size_t)layer * s->cfg.N_mb_max + mb;
+    char* base = s->ws + s->Lo.off_records + slot * (s->Lo.rec_bytes + s->Lo.y_bytes);
+    Record R = record_at(s, base);
+    R.y = base + s->Lo.rec_bytes;
+    return R;
+  }
+  Record R = record_at(s, s->ws + s->Lo.off_records);
+  R.y = s->ws + s->Lo.off_ckpt + ((size_t)layer * s->cfg.N_mb_max + mb) * s->Lo.y_bytes;
+  return R;
+}
+
+struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float* delta; };
+
+Tmp tmp_of(bf_stack* s) {
+  TmpSizes t = tmp_sizes(s->cfg);
+  Tmp T;
+  char* p = s->ws + s->Lo.off_tmp;
+  T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
+  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p;
+  return T;
+}
+
+#define BF_TRY(expr)            \
+  do {                          \
+    bf_status s__ = (expr);     \
+    if (s__ != BF_OK) return s__; \
+  } while (0)
+
+// Forward of one layer on T tokens.  x: layer input; R: where the activations go; y: output.
+// skip_fc2: recomputation before a backward does not need the layer output.
+bf_status layer_forward(bf_stack* s, int layer, int S_mb, const void* x, const Record& R, void* y, bool skip_fc2,
+                        hipStream_t st) {
+  const bf_config& c = s->cfg;
+  const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp, dt = c.dtype, kn = c.kernels;
+  auto P = [&](int tid) { return param_ptr(s, s->w32, layer, tid); };
+  BF_TRY(layernorm_fwd(dt, T, h, x, P(BF_LN1_G), P(BF_LN1_B), c.ln_eps, R.a, R.ln1, st));
+  GemmArgs g{};
+  g = GemmArgs{T, 3 * h, h, R.a, weight_ptr(s, layer, BF_W_QKV), R.qkv, P(BF_B_QKV), nullptr, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NN, E_BIAS, g, st));
+  BF_TRY(attention_fwd(dt, kn, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, R.qkv, R.ctx, R.lse, st));
+  g = GemmArgs{T, h, h, R.ctx, weight_ptr(s, layer, BF_W_O), R.x1, P(BF_B_O), x, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NN, E_BIAS_RES, g, st));
+  BF_TRY(layernorm_fwd(dt, T, h, R.x1, P(BF_LN2_G), P(BF_LN2_B), c.ln_eps, R.c, R.ln2, st));
+  g = GemmArgs{T, f, h, R.c, weight_ptr(s, layer, BF_W_FC1), R.u, P(BF_B_FC1), nullptr, R.g, 0};
+  BF_TRY(gemm(dt, kn, L_NN, E_BIAS_GELU, g, st));
+  if (!skip_fc2) {
+    g = GemmArgs{T, h, f, R.g, weight_ptr(s, layer, BF_W_FC2), y, P(BF_B_FC2), R.x1, nullptr, 0};
+    BF_TRY(gemm(dt, kn, L_NN, E_BIAS_RES, g, st));
+  }
+  return BF_OK;
+}
+
+// Backward of one layer.  dy: gradient w.r.t. the layer output; dx: gradient w.r.t. its input.
+// acc: 0 for the first micro-batch of the step (main-grads are overwritten), 1 afterwards.
+bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const Record& R, const void* dy, void* dx,
+                         int acc, hipStream_t st) {
+  const bf_config& c = s->cfg;
+  const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp, dt = c.dtype, kn = c.kernels;
+  Tmp t = tmp_of(s);
+  auto P = [&](int tid) { return param_ptr(s, s->w32, layer, tid); };
+  auto G = [&](int tid) { return param_ptr(s, s->g32, layer, tid); };
+  GemmArgs g{};
+  // y = x1 + gelu(u) W_fc2 + b_fc2
+  g = GemmArgs{f, h, T, R.g, dy, G(BF_W_FC2), nullptr, nullptr, nullptr, acc};
+  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
+  BF_TRY(colsum(dt, T, h, dy, G(BF_B_FC2), acc, st));
+  g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), t.du, nullptr, R.u, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NT, E_GELU_BWD, g, st));
+  // u = c W_fc1 + b_fc1
+  g = GemmArgs{h, f, T, R.c, t.du, G(BF_W_FC1), nullptr, nullptr, nullptr, acc};
+  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
+  BF_TRY(colsum(dt, T, f, t.du, G(BF_B_FC1), acc, st));
+  g = GemmArgs{T, h, f, t.du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
+  // c = LN2(x1); dx1 = dy + LN2'(dc)
+  BF_TRY(layernorm_bwd(dt, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, t.dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
+  // x1 = x + ctx W_o + b_o
+  g = GemmArgs{h, h, T, R.ctx, t.dx1, G(BF_W_O), nullptr, nullptr, nullptr, acc};
+  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
+  BF_TRY(colsum(dt, T, h, t.dx1, G(BF_B_O), acc, st));
+  g = GemmArgs{T, h, h, t.dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
+  BF_TRY(attention_bwd(dt, kn, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, R.qkv, R.ctx, R.lse, t.dctx, t.dqkv,
+                       t.delta, st));
+  // qkv = a W_qkv + b_qkv
+  g = GemmArgs{h, 3 * h, T, R.a, t.dqkv, G(BF_W_QKV), nullptr, nullptr, nullptr, acc};
+  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
+  BF_TRY(colsum(dt, T, 3 * h, t.dqkv, G(BF_B_QKV), acc, st));
+  g = GemmArgs{T, h, 3 * h, t.dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
+  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
+  // a = LN1(x); dx = dx1 + LN1'(da)
+  BF_TRY(layernorm_bwd(dt, T, h, t.dc, x, P(BF_LN1_G), R.ln1, t.dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
+  return BF_OK;
+}
+
+}  // namespace
+}  // namespace bf
+
+extern "C" {
+
+const char* bf_last_error(void) { return bf::g_err; }
+
+int64_t bf_param_count(const bf_config* cfg) {
+  if (!valid_config(cfg)) return 0;
+  Dims D;
+  fill_dims(*cfg, &D);
+  int64_t n = 0;
+  for (int i = 0; i < BF_N_TENSORS; ++i) n += (int64_t)D.tensor_elems[i];
+  return n * cfg->N_layers;
+}
+
+size_t bf_workspace_bytes(const bf_config* cfg) {
+  if (!valid_config(cfg)) return 0;
+  Dims D;
+  WsLayout Lo;
+  fill_dims(*cfg, &D);
+  fill_layout(*cfg, D, &Lo);
+  return Lo.total;
+}
+
+bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, void* stream, bf_stack** out) {
+  if (!out) { set_error("bf_create_stack: out is null"); return BF_EINVAL; }
+  *out = nullptr;
+  if (!valid_config(cfg)) return BF_EINVAL;
+  if (!workspace || ((uintptr_t)workspace & (ALIGN - 1))) { set_error("bf_create_stack: workspace null or not 256-byte aligned"); return BF_EINVAL; }
+  bf_stack* s = new (std::nothrow) bf_stack();
+  if (!s) { set_error("bf_create_stack: host allocation failed"); return BF_ENOMEM; }
+  s->cfg = *cfg;
+  fill_dims(*cfg, &s->D);
+  fill_layout(*cfg, s->D, &s->Lo);
+  if (bytes < s->Lo.total) {
+    set_error("bf_create_stack: workspace has %zu bytes, %zu needed", bytes, s->Lo.total);
+    delete s;
+    return BF_ENOMEM;
+  }
+  s->ws = (char*)workspace;
+  s->w32 = (float*)(s->ws + s->Lo.off_w32);
+  s->m = (float*)(s->ws + s->Lo.off_m);
+  s->v = (float*)(s->ws + s->Lo.off_v);
+  s->g32 = (float*)(s->ws + s->Lo.off_g32);
+  s->wlp = cfg->dtype == BF_BF16 ? (bf16_t*)(s->ws + s->Lo.off_wlp) : nullptr;
+  s->step = 0;
+  s->have_grads = false;
+  s->side = nullptr;
+  s->ev_grad_ready = s->ev_side_done = s->ev_t0 = s->ev_t1 = nullptr;
+  hipStream_t st = (hipStream_t)stream;
+  auto fail = [&](bf_status code) { bf_destroy_stack(s); return code; };
+#define CK(expr)                                                                                  \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) { set_error("%s failed: %s", #expr, hipGetErrorString(e_)); return fail(BF_EDEVICE); } \
+  } while (0)
+  CK(hipGetDevice(&s->device));
+  CK(hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking));
+  CK(hipEventCreateWithFlags(&s->ev_grad_ready, hipEventDisableTiming));
+  CK(hipEventCreateWithFlags(&s->ev_side_done, hipEventDisableTiming));
+  CK(hipEventCreate(&s->ev_t0));
+  CK(hipEventCreate(&s->ev_t1));
+  s->adam_ev.resize(2 * (size_t)cfg->N_layers, nullptr);
+  for (auto& e : s->adam_ev) CK(hipEventCreate(&e));
+  if (cfg->queue_depth > 0) {
+    s->queue_ev.resize(cfg->queue_depth, nullptr);
+    for (auto& e : s->queue_ev) CK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  }
+#undef CK
+  // initialise: zero everything, then weights ~ N(0, init_std), LN gains 1
+  const size_t P = s->Lo.P_total;
+  bf_status r;
+  if ((r = fill_f32(P, s->w32, 0.f, st)) != BF_OK || (r = fill_f32(P, s->m, 0.f, st)) != BF_OK ||
+      (r = fill_f32(P, s->v, 0.f, st)) != BF_OK || (r = fill_f32(P, s->g32, 0.f, st)) != BF_OK)
+    return fail(r);
+  for (int l = 0; l < cfg->N_layers; ++l) {
+    const int wt[4] = {BF_W_QKV, BF_W_O, BF_W_FC1, BF_W_FC2};
+    for (int i = 0; i < 4; ++i) {
+      const uint64_t sd = cfg->seed * 0x9E3779B97F4A7C15ull + (uint64_t)l * BF_N_TENSORS + wt[i];
+      if ((r = init_normal(s->D.tensor_elems[wt[i]], param_ptr(s, s->w32, l, wt[i]), sd, cfg->init_std, st)) != BF_OK)
+        return fail(r);
+    }
+    if ((r = fill_f32(s->D.tensor_elems[BF_LN1_G], param_ptr(s, s->w32, l, BF_LN1_G), 1.f, st)) != BF_OK) return fail(r);
+    if ((r = fill_f32(s->D.tensor_elems[BF_LN2_G], param_ptr(s, s->w32, l, BF_LN2_G), 1.f, st)) != BF_OK) return fail(r);
+  }
+  if (s->wlp && (r = cast_f32_to_bf16(P, s->w32, s->wlp, st)) != BF_OK) return fail(r);
+  hipError_t e = hipStreamSynchronize(st);
+  if (e != hipSuccess) { set_error("bf_create_stack: initialisation failed: %s", hipGetErrorString(e)); return fail(BF_EDEVICE); }
+  *out = s;
+  return BF_OK;
+}
+
+bf_status bf_destroy_stack(bf_stack* s) {
+  if (!s) return BF_OK;
+  if (s->side) { (void)hipStreamSynchronize(s->side); (void)hipStreamDestroy(s->side); }
+  hipEvent_t evs[4] = {s->ev_grad_ready, s->ev_side_done, s->ev_t0, s->ev_t1};
+  for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : s->adam_ev) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : s->queue_ev) if (e) (void)hipEventDestroy(e);
+  delete s;
+  return BF_OK;
+}
+
+size_t bf_tensor_elems(const bf_stack* s, int tensor_id) {
+  if (!s || tensor_id < 0 || tensor_id >= BF_N_TENSORS) return 0;
+  return s->D.tensor_elems[tensor_id];
+}
+
+static bf_status check_tensor(bf_stack* s, int layer, int tid, const void* host, size_t n) {
+  if (!s || !host) { set_error("null stack or host pointer"); return BF_EINVAL; }
+  if (layer < 0 || layer >= s->cfg.N_layers || tid < 0 || tid >= BF_N_TENSORS) { set_error("bad layer %d or tensor id %d", layer, tid); return BF_EINVAL; }
+  if (n != s->D.tensor_elems[tid]) { set_error("tensor %d has %zu elements, caller passed %zu", tid, s->D.tensor_elems[tid], n); return BF_EINVAL; }
+  return BF_OK;
+}
+
+bf_status bf_set_params(bf_stack* s, int layer, int tid, const float* host_src, size_t n) {
+  BF_TRY(check_tensor(s, layer, tid, host_src, n));
+  BF_HIP_CHECK(hipDeviceSynchronize());
+  float* dst = param_ptr(s, s->w32, layer, tid);
+  BF_HIP_CHECK(hipMemcpy(dst, host_src, n * sizeof(float), hipMemcpyHostToDevice));
+  if (s->wlp) {
+    BF_TRY(cast_f32_to_bf16(n, dst, s->wlp + (dst - s->w32), nullptr));
+    BF_HIP_CHECK(hipDeviceSynchronize());
+  }
+  return BF_OK;
+}
+
+static bf_status get_from(bf_stack* s, float* arena, int layer, int tid, float* host_dst, size_t n) {
+  BF_TRY(check_tensor(s, layer, tid, host_dst, n));
+  BF_HIP_CHECK(hipDeviceSynchronize());
+  BF_HIP_CHECK(hipMemcpy(host_dst, param_ptr(s, arena, layer, tid), n * sizeof(float), hipMemcpyDeviceToHost));
+  return BF_OK;
+}
+
+bf_status bf_get_params(bf_stack* s, int layer, int tid, float* host_dst, size_t n) {
+  if (!s) { set_error("null stack"); return BF_EINVAL; }
+  return get_from(s, s->w32, layer, tid, host_dst, n);
+}
+
+bf_status bf_get_grads(bf_stack* s, int layer, int tid, float* host_dst, size_t n) {
+  if (!s) { set_error("null stack"); return BF_EINVAL; }
+  if (!s->have_grads) { set_error("bf_get_grads: no step has run yet"); return BF_ESTATE; }
+  return get_from(s, s->g32, layer, tid, host_dst, n);
+}
+
+bf_status bf_get_moments(bf_stack* s, int layer, int tid, int which, float* host_dst, size_t n) {
+  if (!s) { set_error("null stack"); return BF_EINVAL; }
+  if (which != 0 && which != 1) { set_error("bf_get_moments: which must be 0 or 1"); return BF_EINVAL; }
+  return get_from(s, which ? s->v : s->m, layer, tid, host_dst, n);
+}
+
+bf_status bf_reset_optimizer(bf_stack* s) {
+  if (!s) { set_error("null stack"); return BF_EINVAL; }
+  BF_HIP_CHECK(hipDeviceSynchronize());
+  BF_TRY(fill_f32(s->Lo.P_total, s->m, 0.f, nullptr));
+  BF_TRY(fill_f32(s->Lo.P_total, s->v, 0.f, nullptr));
+  BF_HIP_CHECK(hipDeviceSynchronize());
+  s->step = 0;
+  return BF_OK;
+}
+
+bf_status bf_get_trace(const bf_stack* s, bf_event* dst, size_t cap, size_t* n) {
+  if (!s || !n) { set_error("bf_get_trace: null argument"); return BF_EINVAL; }
+  *n = s->trace.size();
+  if (dst) {
+    const size_t k = cap < s->trace.size() ? cap : s->trace.size();
+    if (k) memcpy(dst, s->trace.data(), k * sizeof(bf_event));
+  }
+  return BF_OK;
+}
+
+bf_status bf_schedule_trace(int schedule, int N_PP, int N_loop, int N_mb, int rank, int t_fwd, int t_bwd, bf_event* dst,
+                            size_t cap, size_t* n, bf_sched_stats* stats) {
+  std::vector<SchedOp> ops;
+  std::string why;
+  if (!rank_order(schedule, N_PP, N_loop, N_mb, rank, &ops, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+  if (n) *n = ops.size();
+  if (dst) {
+    int live = 0;
+    for (size_t i = 0; i < ops.size() && i < cap; ++i) {
+      live += ops[i].op == 0 ? 1 : -1;
+      dst[i] = bf_event{ops[i].op, ops[i].stage, ops[i].mb, live};
+    }
+  }
+  if (stats) {
+    std::vector<int64_t> peak;
+    if (!simulate(schedule, N_PP, N_loop, N_mb, t_fwd, t_bwd, stats, &peak, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+    stats->peak_live = peak[rank];
+  }
+  return BF_OK;
+}
+
+bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb, const void* x, const void* dy, void* y,
+                      void* dx, int apply_optimizer, int timing, void* stream, bf_step_report* report) {
+  if (!s) { set_error("bf_run_step: null stack"); return BF_EINVAL; }
+  const bf_config& c = s->cfg;
+  if (schedule != BF_SCHED_BF && schedule != BF_SCHED_DF) { set_error("bf_run_step: unknown schedule %d", schedule); return BF_EINVAL; }
+  if (N_loop < 1 || c.N_layers % N_loop) { set_error("bf_run_step: N_loop = %d must divide N_layers = %d", N_loop, c.N_layers); return BF_EINVAL; }
+  if (N_mb < 1 || N_mb > c.N_mb_max) { set_error("bf_run_step: N_mb = %d outside 1..%d", N_mb, c.N_mb_max); return BF_EINVAL; }
+  if (S_mb < 1 || S_mb > c.S_mb_max) { set_error("bf_run_step: S_mb = %d outside 1..%d", S_mb, c.S_mb_max); return BF_EINVAL; }
+  if (!x || !dy) { set_error("bf_run_step: x and dy must not be null"); return BF_EINVAL; }
+  int cur = -1;
+  BF_HIP_CHECK(hipGetDevice(&cur));
+  if (cur != s->device) { set_error("bf_run_step: stack lives on device %d, current device is %d", s->device, cur); return BF_EINVAL; }
+
+  hipStream_t st = (hipStream_t)stream;
+  const size_t es = c.dtype == BF_BF16 ? 2 : 4;
+  const int per_stage = c.N_layers / N_loop;
+  const size_t mb_bytes = (size_t)S_mb * c.S_seq * c.S_hidden * es;
+  Tmp tmp = tmp_of(s);
+  char* bhand = s->ws + s->Lo.off_bhand;
+  char* scratch_out = s->ws + s->Lo.off_scratch_out;
+
+  std::vector<SchedOp> ops;
+  std::string why;
+  if (!rank_order(schedule, 1, N_loop, N_mb, 0, &ops, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+
+  s->trace.clear();
+  s->have_grads = false;
+  if (apply_optimizer) s->step += 1;
+  int live = 0;
+  int64_t peak_live = 0;
+  size_t n_adam = 0, qi = 0;
+  if (timing) BF_HIP_CHECK(hipEventRecord(s->ev_t0, st));
+
+  // layer input of (layer, mb): the caller's x for layer 0, else the previous layer's stored output
+  auto input_of = [&](int layer, int m) -> const void* {
+    if (layer == 0) return (const char*)x + (size_t)m * mb_bytes;
+    return record_for(s, layer - 1, m).y;
+  };
+
+  for (const SchedOp& op : ops) {
+    const int l0 = op.stage * per_stage, l1 = l0 + per_stage, m = op.mb;
+    if (op.op == 0) {
+      for (int l = l0; l < l1; ++l) {
+        Record R = record_for(s, l, m);
+        void* out = R.y;
+        if (l == c.N_layers - 1) out = y ? (char*)y + (size_t)m * mb_bytes : scratch_out;
+        BF_TRY(layer_forward(s, l, S_mb, input_of(l, m), R, out, false, st));
+        ++live;
+      }
+    } else {
+      for (int l = l1 - 1; l >= l0; --l) {
+        Record R = record_for(s, l, m);
+        const void* xin = input_of(l, m);
+        if (c.ckpt_mode == BF_CKPT_LAYER) BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, st));
+        // gradient in: caller's dy for the last layer, the hand-off buffer at a stage top, else the ping-pong
+        const void* din;
+        if (l == c.N_layers - 1) din = (const char*)dy + (size_t)m * mb_bytes;
+        else if (l == l1 - 1) din = bhand + (size_t)m * s->Lo.y_bytes;
+        else din = tmp.ping[(l + 1) & 1];
+        void* dout;
+        if (l == 0) dout = dx ? (char*)dx + (size_t)m * mb_bytes : scratch_out + s->Lo.y_bytes;
+        else if (l == l0) dout = bhand + (size_t)m * s->Lo.y_bytes;
+        else dout = tmp.ping[l & 1];
+        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, st));
+        --live;
+      }
+    }
+    peak_live = live > peak_live ? live : peak_live;
+    s->trace.push_back(bf_event{op.op, op.stage, m, live});
+
+    if (op.op == 1 && m == N_mb - 1) {
+      // this stage's gradient is final (Sec. 4.2: breadth-first aggregates the steps by layer)
+      if (apply_optimizer) {
+        const size_t off = (size_t)l0 * s->D.layer_elems, n = (size_t)per_stage * s->D.layer_elems;
+        // breadth-first: the update runs beside the backward of the earlier stages; depth-first
+        // gets no such slot (every stage completes in the last micro-batch), so it stays in line
+        hipStream_t as = schedule == BF_SCHED_BF ? s->side : st;
+        if (as != st) {
+          BF_HIP_CHECK(hipEventRecord(s->ev_grad_ready, st));
+          BF_HIP_CHECK(hipStreamWaitEvent(as, s->ev_grad_ready, 0));
+        }
+        if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam], as));
+        BF_TRY(adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
+                         c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as));
+        if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam + 1], as));
+        ++n_adam;
+      }
+      s->trace.push_back(bf_event{2, op.stage, -1, live});
+    }
+    if (!s->queue_ev.empty()) {
+      // bounded launch queue (App. D.2): wait for the op issued queue_depth ops ago
+      hipEvent_t e = s->queue_ev[qi % s->queue_ev.size()];
+      if (qi >= s->queue_ev.size()) BF_HIP_CHECK(hipEventSynchronize(e));
+      BF_HIP_CHECK(hipEventRecord(e, st));
+      ++qi;
+    }
+  }
+  if (apply_optimizer && schedule == BF_SCHED_BF) {
+    BF_HIP_CHECK(hipEventRecord(s->ev_side_done, s->side));
+    BF_HIP_CHECK(hipStreamWaitEvent(st, s->ev_side_done, 0));
+  }
+  s->have_grads = true;
+
+  if (report) {
+    memset(report, 0, sizeof *report);
+    const double T = (double)S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
+    const double lin = 2.0 * T * (3 * h * h + h * h + 2 * h * f);
+    const double att = 4.0 * c.S_seq * T * h;  // full S_seq x S_seq scores
+    const double lm = (double)c.N_layers * N_mb;
+    report->flops_model = 3.0 * (lin + att) * lm;
+    report->flops_paper = 4.0 * (lin + att) * lm;
+    const double att_f = c.causal ? att / 2 : att;
+    // backward attention runs 7 score-sized products (dq pass: S, dP, dQ; dk/dv pass: S, dP, dK, dV) vs 2 forward
+    double exec = 3.0 * lin + att_f * (1.0 + 3.5);
+    if (c.ckpt_mode == BF_CKPT_LAYER) exec += (lin - 2.0 * T * h * f) + att_f;
+    report->flops_executed = exec * lm;
+    report->peak_ckpt_count = peak_live;
+    report->peak_ckpt_bytes = peak_live * (int64_t)mb_bytes;
+    RecSizes rs = rec_sizes(c);
+    (void)rs;
+    const double frac = (double)S_mb / c.S_mb_max;
+    const int64_t rec_live = (int64_t)((double)(s->Lo.rec_bytes) * frac) + (int64_t)mb_bytes;
+    report->peak_act_bytes = c.ckpt_mode == BF_CKPT_NONE ? peak_live * rec_live
+                                                         : peak_live * (int64_t)mb_bytes + (int64_t)((double)s->Lo.rec_bytes * frac);
+    report->state_bytes = (int64_t)s->Lo.P_total * (c.dtype == BF_BF16 ? 18 : 16);
+    report->n_events = (int32_t)s->trace.size();
+  }
+  if (timing) {
+    BF_HIP_CHECK(hipEventRecord(s->ev_t1, st));
+    BF_HIP_CHECK(hipEventSynchronize(s->ev_t1));
+    if (report) {
+      float ms = 0.f;
+      BF_HIP_CHECK(hipEventElapsedTime(&ms, s->ev_t0, s->ev_t1));
+      report->gpu_ms = ms;
+      double am = 0;
+      for (size_t i = 0; i < n_adam; ++i) {
+        BF_HIP_CHECK(hipEventSynchronize(s->adam_ev[2 * i + 1]));
+        BF_HIP_CHECK(hipEventElapsedTime(&ms, s->adam_ev[2 * i], s->adam_ev[2 * i + 1]));
+        am += ms;
+      }
+      report->adam_ms = am;
+      report->timed = 1;
+    }
+  }
+  return BF_OK;
+}
+
+}  // extern "C"

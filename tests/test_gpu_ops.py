@@ -1,0 +1,162 @@
+"""GPU parity of the single kernels against the CPU oracle, element by element.
+Tolerance: max|gpu - oracle| / max|oracle| <= 1e-5 in fp32 mode, 2e-2 in bf16 mode."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import bf_inputs
+import paper_2211_05953_amd as bf
+from oracle import layer as L
+from oracle import stack as K
+from util import TOL, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+MODES = [("fp32", bf.BF_FP32), ("bf16", bf.BF_BF16)]
+
+
+def _dt(bf16):
+    return torch.bfloat16 if bf16 else torch.float32
+
+
+@pytest.mark.parametrize("mode,dtype", MODES)
+@pytest.mark.parametrize("kernels", [bf.BF_KERNELS_PLAIN, bf.BF_KERNELS_AUTO])
+@pytest.mark.parametrize("M,N,K", [(128, 768, 256), (200, 136, 72), (256, 512, 384), (2048, 256, 512), (64, 64, 2048), (1, 1, 1)])
+def test_gemm_all_layouts_and_epilogues(mode, dtype, kernels, M, N, K):
+    b16 = dtype == bf.BF_BF16
+    A = bf_inputs.normal(1, 0, (M, K), bf16=b16)
+    B = bf_inputs.normal(1, 1, (K, N), 0.05, bf16=b16)
+    bias = bf_inputs.normal(1, 2, (N,), 0.5)
+    R = bf_inputs.normal(1, 3, (M, N), bf16=b16)
+    A64, B64, R64 = A.astype(np.float64), B.astype(np.float64), R.astype(np.float64)
+    acc = A64 @ B64
+    dA, dB, dR, dbias = to_dev(A, b16), to_dev(B, b16), to_dev(R, b16), to_dev(bias, False)
+    out = torch.empty(M, N, dtype=_dt(b16), device="cuda")
+    out2 = torch.empty_like(out)
+    # forward layouts
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NN, bf.BF_EPI_NONE, M, N, K, dA, dB, out)
+    assert rel_err(to_host(out), acc) <= TOL[mode]
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NN, bf.BF_EPI_BIAS, M, N, K, dA, dB, out, bias=dbias)
+    assert rel_err(to_host(out), acc + bias) <= TOL[mode]
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NN, bf.BF_EPI_BIAS_RES, M, N, K, dA, dB, out, bias=dbias, R=dR)
+    assert rel_err(to_host(out), acc + bias + R64) <= TOL[mode]
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NN, bf.BF_EPI_BIAS_GELU, M, N, K, dA, dB, out, bias=dbias, C2=out2)
+    assert rel_err(to_host(out), acc + bias) <= TOL[mode]
+    assert rel_err(to_host(out2), L.gelu(acc + bias)) <= TOL[mode]
+    # dgrad layout: B passed as [N, K]
+    dBt = to_dev(np.ascontiguousarray(B.T), b16)
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NT, bf.BF_EPI_NONE, M, N, K, dA, dBt, out)
+    assert rel_err(to_host(out), acc) <= TOL[mode]
+    bf.bf_op_gemm(dtype, kernels, bf.BF_NT, bf.BF_EPI_GELU_BWD, M, N, K, dA, dBt, out, R=dR)
+    assert rel_err(to_host(out), acc * L.gelu_grad(R64)) <= TOL[mode]
+    # wgrad layout: A passed as [K, M], fp32 output, overwrite then accumulate
+    dAt = to_dev(np.ascontiguousarray(A.T), b16)
+    G = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    bf.bf_op_gemm(dtype, kernels, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, K, dAt, dB, G, accumulate=0)
+    assert rel_err(to_host(G), acc) <= TOL["fp32"] * (1 if not b16 else 1)
+    bf.bf_op_gemm(dtype, kernels, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, K, dAt, dB, G, accumulate=1)
+    assert rel_err(to_host(G), 2 * acc) <= TOL["fp32"]
+
+
+@pytest.mark.parametrize("mode,dtype", MODES)
+@pytest.mark.parametrize("T,h", [(128, 256), (77, 100), (512, 2048), (3, 8200)])
+def test_layernorm_fwd_bwd_and_colsum(mode, dtype, T, h):
+    b16 = dtype == bf.BF_BF16
+    x = bf_inputs.normal(2, 0, (T, h), 2.0, bf16=b16) + np.float32(0.5)
+    if b16:
+        x = bf_inputs.round_bf16(x)
+    g = 1 + bf_inputs.normal(2, 1, (h,), 0.2)
+    b = bf_inputs.normal(2, 2, (h,), 0.2)
+    dy = bf_inputs.normal(2, 3, (T, h), bf16=b16)
+    dres = bf_inputs.normal(2, 4, (T, h), bf16=b16)
+    eps = 1e-5
+    y_ref, saved = L.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), eps)
+    dx_ref, dg_ref, db_ref = L.layernorm_bwd(dy.astype(np.float64), g.astype(np.float64), saved)
+    dX, dG, dB, dDY, dRES = to_dev(x, b16), to_dev(g, False), to_dev(b, False), to_dev(dy, b16), to_dev(dres, b16)
+    y = torch.empty(T, h, dtype=_dt(b16), device="cuda")
+    stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
+    bf.bf_op_layernorm_fwd(dtype, T, h, dX, dG, dB, eps, y, stats)
+    assert rel_err(to_host(y), y_ref) <= TOL[mode]
+    st = to_host(stats).astype(np.float64)
+    assert rel_err(st[:, 0], x.astype(np.float64).mean(-1)) <= 1e-5
+    assert rel_err(st[:, 1], saved[1][:, 0]) <= 1e-5
+    dx = torch.empty_like(y)
+    dg = torch.full((h,), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((h,), float("nan"), dtype=torch.float32, device="cuda")
+    bf.bf_op_layernorm_bwd(dtype, T, h, dDY, dX, dG, stats, dRES, dx, dg, db, 0)
+    assert rel_err(to_host(dx), dx_ref + dres) <= TOL[mode]
+    assert rel_err(to_host(dg), dg_ref) <= 1e-5 and rel_err(to_host(db), db_ref) <= 1e-5
+    bf.bf_op_layernorm_bwd(dtype, T, h, dDY, dX, dG, stats, None, dx, dg, db, 1)
+    assert rel_err(to_host(dx), dx_ref) <= TOL[mode]
+    assert rel_err(to_host(dg), 2 * dg_ref) <= 1e-5 and rel_err(to_host(db), 2 * db_ref) <= 1e-5
+    out = torch.full((h,), float("nan"), dtype=torch.float32, device="cuda")
+    bf.bf_op_colsum(dtype, T, h, dDY, out, 0)
+    assert rel_err(to_host(out), dy.astype(np.float64).sum(0)) <= 1e-5
+    bf.bf_op_colsum(dtype, T, h, dDY, out, 1)
+    assert rel_err(to_host(out), 2 * dy.astype(np.float64).sum(0)) <= 1e-5
+
+
+@pytest.mark.parametrize("mode,dtype", MODES)
+@pytest.mark.parametrize("kernels", [bf.BF_KERNELS_PLAIN, bf.BF_KERNELS_AUTO])
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("S_mb,S_seq,a,d", [(1, 128, 4, 64), (2, 256, 2, 128), (2, 100, 3, 40), (1, 1, 1, 8), (1, 384, 2, 128)])
+def test_attention_fwd_bwd(mode, dtype, kernels, causal, S_mb, S_seq, a, d):
+    b16 = dtype == bf.BF_BF16
+    h = a * d
+    qkv = bf_inputs.normal(3, 0, (S_mb, S_seq, 3 * h), bf16=b16)
+    dctx = bf_inputs.normal(3, 1, (S_mb, S_seq, h), bf16=b16)
+    ctx_ref, saved = L.attention_fwd(qkv.astype(np.float64), a, bool(causal))
+    dqkv_ref = L.attention_bwd(dctx.astype(np.float64), saved, a)
+    dQKV, dDC = to_dev(qkv, b16), to_dev(dctx, b16)
+    ctx = torch.empty(S_mb, S_seq, h, dtype=_dt(b16), device="cuda")
+    lse = torch.empty(S_mb, a, S_seq, dtype=torch.float32, device="cuda")
+    bf.bf_op_attention_fwd(dtype, kernels, S_mb, S_seq, a, d, causal, dQKV, ctx, lse)
+    assert rel_err(to_host(ctx), ctx_ref) <= TOL[mode]
+    # log-sum-exp of the scaled masked scores, from the definition
+    q, k, v, p = saved
+    s = np.matmul(q, k.transpose(0, 1, 3, 2)) / math.sqrt(d)
+    if causal:
+        s = np.where(np.tril(np.ones((S_seq, S_seq), dtype=bool)), s, -np.inf)
+    lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+    assert np.abs(to_host(lse) - lse_ref).max() <= (1e-4 if not b16 else 2e-2)
+    dqkv = torch.empty(S_mb, S_seq, 3 * h, dtype=_dt(b16), device="cuda")
+    delta = torch.empty(S_mb * a * S_seq, dtype=torch.float32, device="cuda")
+    bf.bf_op_attention_bwd(dtype, kernels, S_mb, S_seq, a, d, causal, dQKV, ctx, lse, dDC, dqkv, delta)
+    got = to_host(dqkv)
+    for i, name in enumerate(("dq", "dk", "dv")):
+        assert rel_err(got[..., i * h:(i + 1) * h], dqkv_ref[..., i * h:(i + 1) * h]) <= TOL[mode], name
+
+
+@pytest.mark.parametrize("n", [1, 1000, 4096 * 33 + 4])
+def test_adam_kernel(n):
+    rng = np.random.default_rng(4)
+    w = rng.standard_normal(n).astype(np.float32)
+    g = (rng.standard_normal(n) * 10.0 ** rng.integers(-4, 2, n)).astype(np.float32)
+    m0 = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    v0 = (rng.random(n) * 0.1).astype(np.float32)
+    dW, dM, dV, dGr = (torch.from_numpy(t).cuda() for t in (w, m0, v0, g))
+    wlp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    args = dict(lr=1e-2, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.01)
+    bf.bf_op_adam(n, dW, dM, dV, dGr, wlp, 3, **args)
+    w1, m1, v1 = K.adam_update(w.astype(np.float64), g.astype(np.float64), m0.astype(np.float64), v0.astype(np.float64),
+                               3, args["lr"], 0.9, 0.999, 1e-8, 0.01)
+    assert rel_err(to_host(dM), m1) <= 1e-6 and rel_err(to_host(dV), v1) <= 1e-6
+    assert rel_err(to_host(dW) - w, w1 - w) <= 1e-4          # the update itself
+    assert np.array_equal(to_host(wlp), bf_inputs.round_bf16(to_host(dW)))  # recast = RNE of the new master
+
+
+def test_op_argument_errors():
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_op_gemm(bf.BF_FP32, 0, bf.BF_NN, bf.BF_EPI_BIAS, 4, 4, 4, t, t, t)   # bias missing
+    assert e.value.status == bf.BF_EINVAL
+    with pytest.raises(bf.BfError):
+        bf.bf_op_gemm(bf.BF_FP32, 0, bf.BF_TN, bf.BF_EPI_NONE, 4, 4, 4, t, t, t)
+    with pytest.raises(bf.BfError):
+        bf.bf_op_gemm(9, 0, bf.BF_NN, bf.BF_EPI_NONE, 4, 4, 4, t, t, t)
+    with pytest.raises(bf.BfError):
+        bf.bf_op_layernorm_fwd(bf.BF_FP32, 0, 4, t, t, t, 1e-5, t, t)
+    with pytest.raises(bf.BfError):
+        bf.bf_op_attention_fwd(bf.BF_FP32, 0, 1, 5000, 1, 4, 1, t, t, t)

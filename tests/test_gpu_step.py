@@ -1,0 +1,145 @@
+"""GPU parity of the whole training step (bf_run_step) against the CPU oracle, in both
+orders, plus the order invariants: BF == DF bitwise, event trace and checkpoint counts
+equal to the oracle's and to Eq. mem_ckpt."""
+import numpy as np
+import pytest
+import torch
+
+import bf_inputs
+import paper_2211_05953_amd as bf
+from oracle import formulas as F
+from oracle import stack as K
+from util import TOL, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_gpu(cfg, params, x, dy, schedule, N_loop, N_mb, S_mb, apply_optimizer=0, steps=1):
+    b16 = cfg.dtype == bf.BF_BF16
+    st = bf.Stack(cfg)
+    for l, p in enumerate(params):
+        for name, tid in bf.TENSOR_IDS.items():
+            st.bf_set_params(l, tid, p[name].reshape(-1))
+    dX, dDY = to_dev(x, b16), to_dev(dy, b16)
+    y, dx = torch.empty_like(dX), torch.empty_like(dX)
+    for _ in range(steps):
+        rep = st.bf_run_step(schedule, N_loop, N_mb, S_mb, dX, dDY, y, dx, apply_optimizer=apply_optimizer)
+    torch.cuda.synchronize()
+    out = dict(y=to_host(y), dx=to_host(dx), report=rep, trace=st.bf_get_trace(),
+               grads=[{n: st.bf_get_grads(l, t) for n, t in bf.TENSOR_IDS.items()} for l in range(cfg.N_layers)],
+               params=[{n: st.bf_get_params(l, t) for n, t in bf.TENSOR_IDS.items()} for l in range(cfg.N_layers)],
+               m=[{n: st.bf_get_moments(l, t, 0) for n, t in bf.TENSOR_IDS.items()} for l in range(cfg.N_layers)],
+               v=[{n: st.bf_get_moments(l, t, 1) for n, t in bf.TENSOR_IDS.items()} for l in range(cfg.N_layers)])
+    st.close()
+    return out
+
+
+def _oracle(params, x, dy, schedule, N_loop, N_heads, causal=True, adam=None, steps=1):
+    p64 = [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
+    state = None
+    for t in range(1, steps + 1):
+        a = dict(adam, t=t) if adam else None
+        r = K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), schedule, N_loop, N_heads, causal=causal,
+                       adam=a, adam_state=state)
+        p64, state = r["new_params"], r["new_adam_state"]
+    return r
+
+
+def _compare(gpu, ref, tol, N_layers):
+    assert rel_err(gpu["y"], ref["y"]) <= tol
+    assert rel_err(gpu["dx"], ref["dx"]) <= tol
+    for l in range(N_layers):
+        for name in bf.TENSOR_IDS:
+            e = rel_err(gpu["grads"][l][name], ref["grads"][l][name].reshape(-1))
+            assert e <= tol, (l, name, e)
+
+
+CASES = [
+    # mode, dtype, ckpt, kernels, L, N_loop, h, a, f, S_seq, S_mb, N_mb
+    ("fp32", bf.BF_FP32, bf.BF_CKPT_NONE, bf.BF_KERNELS_AUTO, 4, 2, 256, 4, 1024, 128, 1, 4),    # configs[0]
+    ("fp32", bf.BF_FP32, bf.BF_CKPT_LAYER, bf.BF_KERNELS_AUTO, 4, 4, 256, 4, 1024, 128, 1, 4),
+    ("fp32", bf.BF_FP32, bf.BF_CKPT_NONE, bf.BF_KERNELS_AUTO, 2, 1, 72, 3, 200, 50, 2, 3),       # ragged everything
+    ("bf16", bf.BF_BF16, bf.BF_CKPT_NONE, bf.BF_KERNELS_PLAIN, 4, 2, 256, 4, 1024, 128, 1, 4),
+    ("bf16", bf.BF_BF16, bf.BF_CKPT_NONE, bf.BF_KERNELS_AUTO, 4, 2, 256, 2, 1024, 256, 1, 4),
+    ("bf16", bf.BF_BF16, bf.BF_CKPT_LAYER, bf.BF_KERNELS_AUTO, 2, 2, 512, 4, 2048, 256, 2, 2),
+]
+
+
+@pytest.mark.parametrize("mode,dtype,ckpt,kernels,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", CASES)
+def test_step_matches_oracle_in_both_orders(mode, dtype, ckpt, kernels, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(11, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(11, N_mb, S_mb, S_seq, h, bf16=b16)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, ckpt_mode=ckpt, kernels=kernels)
+    ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a)
+    g_bf = _run_gpu(cfg, params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    g_df = _run_gpu(cfg, params, x, dy, bf.BF_SCHED_DF, N_loop, N_mb, S_mb)
+    _compare(g_bf, ref, TOL[mode], Lyr)
+    _compare(g_df, ref, TOL[mode], Lyr)
+    # the two orders add the same numbers in the same sequence
+    assert np.array_equal(g_bf["y"], g_df["y"]) and np.array_equal(g_bf["dx"], g_df["dx"])
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            assert np.array_equal(g_bf["grads"][l][name], g_df["grads"][l][name]), (l, name)
+    # integer trace and checkpoint counts: the oracle's, and Eq. mem_ckpt at N_PP = 1
+    assert g_bf["trace"] == [tuple(e) for e in ref["trace"]]
+    assert g_bf["report"].peak_ckpt_count == F.ckpt_count("BF", N_mb, Lyr, 1) == ref["peak_ckpt"]
+    assert g_df["report"].peak_ckpt_count == F.ckpt_count("DF", N_mb, Lyr, 1)
+    assert [e[:3] for e in g_df["trace"]] == K.event_order(K.SCHED_DF, N_loop, N_mb)
+    assert g_bf["report"].peak_ckpt_bytes == int(F.ckpt_count("BF", N_mb, Lyr, 1) * S_mb * S_seq * h * (2 if b16 else 4))
+    if f == 4 * h:   # Eq. compute assumes S_mlp = 4 S_hidden
+        assert g_bf["report"].flops_paper == float(F.c_gpu(N_mb, S_mb, Lyr, h, S_seq))
+
+
+@pytest.mark.parametrize("mode,dtype", [("fp32", bf.BF_FP32), ("bf16", bf.BF_BF16)])
+@pytest.mark.parametrize("schedule", [bf.BF_SCHED_BF, bf.BF_SCHED_DF])
+def test_two_optimizer_steps(mode, dtype, schedule):
+    b16 = dtype == bf.BF_BF16
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 2, 2, 128, 2, 512, 64, 1, 3
+    params = bf_inputs.make_params(12, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(12, N_mb, S_mb, S_seq, h, bf16=b16)
+    adam = dict(lr=1e-3, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, lr=adam["lr"])
+    for steps in (1, 2):
+        gpu = _run_gpu(cfg, params, x, dy, schedule, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        ref = _oracle(params, x, dy, schedule, N_loop, a, adam=adam, steps=steps)
+        tol = TOL[mode] * (1 if steps == 1 else 20)   # step 2 sees weights moved by +-lr where a gradient sign is ambiguous
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                g_ref = ref["grads"][l][name].reshape(-1)
+                m_ref, v_ref = (t.reshape(-1) for t in ref["new_adam_state"][l][name])
+                assert rel_err(gpu["grads"][l][name], g_ref) <= tol, (steps, l, name)
+                assert rel_err(gpu["m"][l][name], m_ref) <= tol, (steps, l, name)
+                assert rel_err(gpu["v"][l][name], v_ref) <= 2 * tol, (steps, l, name)
+                if steps == 1:
+                    # where the gradient is well away from zero the first update is -lr * sign(g)
+                    big = np.abs(g_ref) > 1e-2 * np.abs(g_ref).max()
+                    upd = (gpu["params"][l][name].astype(np.float64) - params[l][name].reshape(-1))[big]
+                    upd_ref = (ref["new_params"][l][name].reshape(-1) - params[l][name].reshape(-1))[big]
+                    assert np.abs(upd - upd_ref).max() <= 1e-3 * adam["lr"] + 2e-7 * np.abs(params[l][name]).max()
+
+
+def test_run_step_argument_errors():
+    cfg = bf.make_config(64, 2, 256, 16, 4, 2, 1, dtype=bf.BF_FP32)
+    st = bf.Stack(cfg)
+    t = torch.zeros(2, 1, 16, 64, device="cuda")
+    with pytest.raises(bf.BfError) as e:
+        st.bf_get_grads(0, 2)
+    assert e.value.status == bf.BF_ESTATE
+    for kw in [dict(N_loop=3), dict(N_mb=3), dict(S_mb=2), dict(schedule=5), dict(x=None)]:
+        args = dict(schedule=0, N_loop=2, N_mb=2, S_mb=1, x=t, dy=t)
+        args.update(kw)
+        with pytest.raises(bf.BfError) as e:
+            st.bf_run_step(**args)
+        assert e.value.status == bf.BF_EINVAL
+    with pytest.raises(bf.BfError):
+        st.bf_set_params(9, 0, np.zeros(64, np.float32))
+    with pytest.raises(bf.BfError):
+        st.bf_set_params(0, 0, np.zeros(63, np.float32))
+    st.close()
+    # workspace too small
+    import ctypes as C
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p()
+    rc = bf.load().bf_create_stack(C.byref(cfg), small.data_ptr(), 1024, None, C.byref(h))
+    assert rc == bf.BF_ENOMEM

@@ -1,0 +1,84 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/*.h declares,
+validates arguments, and its integer schedule generator matches the oracle's simulator
+and the closed forms (Eq. bubble, Eq. bubble_looped, Eq. mem_ckpt)."""
+import os
+import re
+from fractions import Fraction
+
+import pytest
+
+import paper_2211_05953_amd as bf
+from oracle import formulas as F
+from oracle import schedule as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = bf.load()
+    declared = set()
+    for hdr in ("bf.h", "bf_ops.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared |= set(re.findall(r"\b(bf_[a-z_0-9]+)\s*\(", text))
+    assert len(declared) >= 20
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert set(bf.binding._SIGNATURES) == declared
+
+
+def test_config_validation_without_a_device():
+    good = bf.make_config(256, 4, 1024, 128, 4, 4, 1, dtype=bf.BF_FP32)
+    assert bf.bf_workspace_bytes(good) > 0
+    assert bf.bf_param_count(good) == F.n_params_exact(4, 256, 1024) == 3159040
+    bad = bf.make_config(256, 4, 1024, 128, 4, 4, 1)
+    bad.S_head = 60
+    assert bf.bf_workspace_bytes(bad) == 0 and "N_heads" in bf.binding.last_error()
+    bad = bf.make_config(256, 4, 1024, 128, 4, 0, 1)
+    assert bf.bf_workspace_bytes(bad) == 0
+    bad = bf.make_config(256, 4, 1024, 128, 4, 4, 1, dtype=7)
+    assert bf.bf_workspace_bytes(bad) == 0
+    # checkpointing shrinks the arena; bf16 shrinks activations
+    none = bf.make_config(512, 4, 2048, 256, 4, 8, 1, ckpt_mode=bf.BF_CKPT_NONE)
+    ck = bf.make_config(512, 4, 2048, 256, 4, 8, 1, ckpt_mode=bf.BF_CKPT_LAYER)
+    assert bf.bf_workspace_bytes(ck) < bf.bf_workspace_bytes(none)
+
+
+@pytest.mark.parametrize("kind,code", [("BF", bf.BF_SCHED_BF), ("DF", bf.BF_SCHED_DF)])
+def test_schedule_trace_matches_oracle_and_closed_forms(kind, code):
+    for N_PP in (1, 2, 4, 8):
+        for N_loop in (1, 2, 4):
+            for N_mb in (N_PP, 2 * N_PP, 4 * N_PP):
+                for t_fwd, t_bwd in ((1, 2), (1, 3)):
+                    ref = S.simulate(kind, N_PP, N_loop, N_mb, t_fwd, t_bwd)
+                    for rank in range(N_PP):
+                        ev, st = bf.bf_schedule_trace(code, N_PP, N_loop, N_mb, rank, t_fwd, t_bwd)
+                        assert [(o, j, m) for o, j, m, _ in ev] == S.device_order(kind, N_PP, N_loop, N_mb, rank)
+                        assert Fraction(st.bubble_num, st.bubble_den) == F.bubble(N_PP, N_mb, N_loop) == ref["bubble"]
+                        assert st.makespan == ref["makespan"] and st.busy == ref["busy"]
+                        assert st.peak_live == ref["peak_live"][rank]
+                        if kind == "BF":
+                            # Eq. mem_ckpt first factor with one layer per stage
+                            assert st.peak_live == F.ckpt_count("BF", N_mb, N_PP * N_loop, N_PP)
+                        assert ev[-1][3] == 0 and max(e[3] for e in ev) == st.peak_live
+
+
+def test_schedule_trace_fig4_and_errors():
+    _, st = bf.bf_schedule_trace(bf.BF_SCHED_BF, 4, 1, 8, 0)
+    assert (st.bubble_num, st.bubble_den) == (3, 8)
+    _, st = bf.bf_schedule_trace(bf.BF_SCHED_BF, 4, 4, 8, 0)
+    assert (st.bubble_num, st.bubble_den) == (3, 32)
+    for args in [(bf.BF_SCHED_BF, 4, 2, 3, 0), (bf.BF_SCHED_DF, 4, 2, 6, 0), (5, 1, 1, 1, 0), (0, 2, 1, 2, 2),
+                 (0, 0, 1, 1, 0)]:
+        with pytest.raises(bf.BfError) as e:
+            bf.bf_schedule_trace(*args)
+        assert e.value.status == bf.BF_EINVAL
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2211_05953_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, os.path.join(dirpath, f)
