@@ -200,7 +200,7 @@ template <int VEC>
 __global__ __launch_bounds__(256) void adam_kernel(size_t n, float* __restrict__ w, float* __restrict__ m,
                                                    float* __restrict__ v, const float* __restrict__ g,
                                                    bf16_t* __restrict__ w_lp, float lr, float beta1, float beta2,
-                                                   float eps, float wd, float c1, float c2) {
+                                                   float eps, float wd, float c1, float c2, float omb1, float omb2) {
   const size_t stride = (size_t)gridDim.x * blockDim.x * VEC;
   for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < n; i += stride) {
     float ww[VEC], mm[VEC], vv[VEC], gg[VEC];
@@ -210,8 +210,8 @@ __global__ __launch_bounds__(256) void adam_kernel(size_t n, float* __restrict__
     load_vec<float, VEC>(g + i, gg);
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
-      mm[j] = beta1 * mm[j] + (1.f - beta1) * gg[j];
-      vv[j] = beta2 * vv[j] + (1.f - beta2) * gg[j] * gg[j];
+      mm[j] = beta1 * mm[j] + omb1 * gg[j];
+      vv[j] = beta2 * vv[j] + omb2 * gg[j] * gg[j];
       const float mhat = mm[j] * c1, vhat = vv[j] * c2;
       ww[j] = ww[j] - lr * (mhat / (sqrtf(vhat) + eps) + wd * ww[j]);
     }
@@ -338,10 +338,11 @@ bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16
   // bias corrections in double on the host, applied as multipliers
   const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
   const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+  const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
   const bool vec = n % 4 == 0 && aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
                    (!w_lp || ((uintptr_t)w_lp & 7) == 0);
-  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2);
-  else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2);
+  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2);
+  else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2);
   BF_LAUNCH_CHECK();
   return BF_OK;
 }

@@ -140,8 +140,10 @@ def test_adam_kernel(n):
     wlp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     args = dict(lr=1e-2, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.01)
     bf.bf_op_adam(n, dW, dM, dV, dGr, wlp, 3, **args)
+    # the C ABI carries the constants as fp32: the oracle gets those exact values
+    f32 = {k: float(np.float32(v)) for k, v in args.items()}
     w1, m1, v1 = K.adam_update(w.astype(np.float64), g.astype(np.float64), m0.astype(np.float64), v0.astype(np.float64),
-                               3, args["lr"], 0.9, 0.999, 1e-8, 0.01)
+                               3, f32["lr"], f32["beta1"], f32["beta2"], f32["adam_eps"], f32["weight_decay"])
     assert rel_err(to_host(dM), m1) <= 1e-6 and rel_err(to_host(dV), v1) <= 1e-6
     assert rel_err(to_host(dW) - w, w1 - w) <= 1e-4          # the update itself
     assert np.array_equal(to_host(wlp), bf_inputs.round_bf16(to_host(dW)))  # recast = RNE of the new master

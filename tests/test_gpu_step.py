@@ -98,7 +98,8 @@ def test_two_optimizer_steps(mode, dtype, schedule):
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 2, 2, 128, 2, 512, 64, 1, 3
     params = bf_inputs.make_params(12, Lyr, h, f, bf16=b16)
     x, dy = bf_inputs.make_batch(12, N_mb, S_mb, S_seq, h, bf16=b16)
-    adam = dict(lr=1e-3, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0)
+    # the C ABI carries the constants as fp32: the oracle gets those exact values
+    adam = {k: float(np.float32(v)) for k, v in dict(lr=1e-3, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0).items()}
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, lr=adam["lr"])
     for steps in (1, 2):
         gpu = _run_gpu(cfg, params, x, dy, schedule, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
