@@ -1,8 +1,247 @@
-// bf16 MFMA GEMM for gfx950 (placeholder until the kernel lands: reports "not supported"
-// so that every caller takes the plain kernel).
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
+//
+// One workgroup computes a BM x BN tile of C, stepping BK = 64 along K.  Each step's A and
+// B tiles are copied global -> registers -> LDS (16-byte accesses, double-buffered LDS, the
+// next tile's global loads in flight during the current tile's MFMAs).  Operands whose
+// global layout is K-contiguous sit in LDS as [row][BK] with the 16-byte chunk index
+// XOR-swizzled by the row (conflict-free ds_read_b128 of MFMA fragments).  Operands whose
+// global layout has K as the slow dimension (B of the forward product, both operands of
+// the weight-gradient product) sit in LDS as [BK][cols + pad] and are read through the
+// LDS transpose load (ds_read_b64_tr_b16), which hands every lane four consecutive k of
+// its own column: no transposed copy of any tensor is ever made in HBM.
+//
+// Wave w of the workgroup owns a (BM / WM) x (BN / WN) sub-tile as MI x NI MFMA tiles of
+// 32 x 32.  Accumulator layout of one MFMA tile: lane l, register r holds
+// row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
 #include "common.h"
+#include "epilogue.h"
 
 namespace bf {
-bool gemm_mfma_supported(int, int, int, int, int) { return false; }
-bf_status gemm_mfma(int, int, const GemmArgs&, hipStream_t) { set_error("gemm_mfma: not built"); return BF_EINVAL; }
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+constexpr int BK = 64;
+constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
+
+template <int BM_, int BN_, int WM_, int WN_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int NT = WM * WN * 64;
+  static constexpr int TM = BM / WM, TN = BN / WN;
+  static constexpr int MI = TM / 32, NI = TN / 32;
+};
+
+// bytes of one LDS stage of an operand tile with R rows (m or n extent)
+template <bool KCONTIG, int R>
+constexpr int stage_elems() { return KCONTIG ? R * BK : BK * (R + TPAD); }
+
+// ---- global -> registers: the thread's 16-byte chunks of an operand tile
+template <bool KCONTIG, int R, int NT>
+struct Stager {
+  static constexpr int CHUNKS = R * BK / 8 / NT;
+  u32x4 v[CHUNKS];
+
+  // g: operand base; ld: its leading dimension (elements); r0: first row/col of the tile; k0: first k
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int r0, int k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = tid + i * NT;
+      const bf16_t* p;
+      if (KCONTIG) {
+        const int row = c >> 3, kc = c & 7;  // 8 chunks per row of BK = 64
+        p = g + (size_t)(r0 + row) * ld + k0 + kc * 8;
+      } else {
+        const int krow = c / (R / 8), rc = c % (R / 8);
+        p = g + (size_t)(k0 + krow) * ld + r0 + rc * 8;
+      }
+      v[i] = *reinterpret_cast<const u32x4*>(p);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = tid + i * NT;
+      int off;
+      if (KCONTIG) {
+        const int row = c >> 3, kc = c & 7;
+        off = row * BK + ((kc ^ (row & 7)) << 3);
+      } else {
+        const int krow = c / (R / 8), rc = c % (R / 8);
+        off = krow * (R + TPAD) + rc * 8;
+      }
+      *reinterpret_cast<u32x4*>(lds + off) = v[i];
+    }
+  }
+};
+
+// ---- LDS -> MFMA fragment: 8 consecutive k of row/column (r32 + lane % 32), k-step kk (16 wide)
+template <bool KCONTIG, int R>
+__device__ __forceinline__ bf16x8 load_frag(const bf16_t* lds, int r32, int kk, int lane) {
+  if (KCONTIG) {
+    const int row = r32 + (lane & 31);
+    const int kc = kk * 2 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(lds + row * BK + ((kc ^ (row & 7)) << 3));
+  } else {
+    const int t = lane & 15, blk = lane >> 4;
+    const int k = kk * 16 + 8 * (blk >> 1) + (t >> 2);
+    const int col = r32 + 16 * (blk & 1) + 4 * (t & 3);
+    const bf16_t* p = lds + k * (R + TPAD) + col;
+    typedef s16x4 __attribute__((address_space(3))) * lds_v4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * (R + TPAD)));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  }
+}
+
+// AK: A is K-contiguous in memory (forward, dgrad); BKC: B is K-contiguous (dgrad)
+template <typename TL, bool AK, bool BKC, int EPI, typename TO>
+__global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ B, TO* __restrict__ C,
+                                                           const float* __restrict__ bias, const TO* __restrict__ R,
+                                                           TO* __restrict__ C2, int accumulate, int tiles_m) {
+  constexpr int BM = TL::BM, BN = TL::BN, NT = TL::NT, MI = TL::MI, NI = TL::NI;
+  constexpr int A_ST = stage_elems<AK, BM>(), B_ST = stage_elems<BKC, BN>();
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* As[2] = {smem, smem + A_ST + B_ST};
+  bf16_t* Bs[2] = {smem + A_ST, smem + 2 * A_ST + B_ST};
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wm = w % TL::WM, wn = w / TL::WM;
+  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  const int m0 = bm * BM, n0 = bn * BN;
+  const size_t lda = AK ? (size_t)K : (size_t)M;   // A stored [M,K] or [K,M]
+  const size_t ldb = BKC ? (size_t)K : (size_t)N;  // B stored [N,K] or [K,N]
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Stager<AK, BM, NT> sa;
+  Stager<BKC, BN, NT> sb;
+  sa.load(A, lda, m0, 0, tid);
+  sb.load(B, ldb, n0, 0, tid);
+  sa.store(As[0], tid);
+  sb.store(Bs[0], tid);
+  __syncthreads();
+
+  const int nk = K / BK;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      sa.load(A, lda, m0, (kt + 1) * BK, tid);
+      sb.load(B, ldb, n0, (kt + 1) * BK, tid);
+    }
+    const bf16_t* as = As[cur];
+    const bf16_t* bs = Bs[cur];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 af[MI], bfr[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      sa.store(As[cur ^ 1], tid);
+      sb.store(Bs[cur ^ 1], tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const size_t row = m0 + wm * TL::TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const size_t col = n0 + wn * TL::TN + j * 32 + (lane & 31);
+        epilogue_store<EPI, TO>(acc[i][j][r], row, col, (size_t)N, C, bias, R, C2, accumulate);
+      }
+}
+
+typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave
+typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
+
+template <typename TL, bool AK, bool BKC>
+constexpr size_t lds_bytes() { return 2 * (size_t)(stage_elems<AK, TL::BM>() + stage_elems<BKC, TL::BN>()) * sizeof(bf16_t); }
+
+template <typename TL, bool AK, bool BKC, int EPI, typename TO>
+bf_status launch(const GemmArgs& a, hipStream_t st) {
+  auto kern = gemm_mfma_kernel<TL, AK, BKC, EPI, TO>;
+  constexpr size_t lds = lds_bytes<TL, AK, BKC>();
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) { set_error("gemm_mfma: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e)); return BF_EDEVICE; }
+    attr_set = true;
+  }
+  const int tiles_m = a.M / TL::BM, tiles_n = a.N / TL::BN;
+  kern<<<tiles_m * tiles_n, TL::NT, lds, st>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.B, (TO*)a.C, a.bias,
+                                                (const TO*)a.R, (TO*)a.C2, a.accumulate, tiles_m);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_error("gemm_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
+  return BF_OK;
+}
+
+template <typename TL, bool AK, bool BKC>
+bf_status by_epilogue(int epi, const GemmArgs& a, hipStream_t st) {
+  switch (epi) {
+    case E_NONE: return launch<TL, AK, BKC, E_NONE, bf16_t>(a, st);
+    case E_BIAS: return launch<TL, AK, BKC, E_BIAS, bf16_t>(a, st);
+    case E_BIAS_RES: return launch<TL, AK, BKC, E_BIAS_RES, bf16_t>(a, st);
+    case E_BIAS_GELU: return launch<TL, AK, BKC, E_BIAS_GELU, bf16_t>(a, st);
+    case E_GELU_BWD: return launch<TL, AK, BKC, E_GELU_BWD, bf16_t>(a, st);
+    default: break;
+  }
+  set_error("gemm_mfma: epilogue %d not available for this layout", epi);
+  return BF_EINVAL;
+}
+
+template <typename TL>
+bf_status by_layout(int layout, int epi, const GemmArgs& a, hipStream_t st) {
+  if (layout == L_NN) return by_epilogue<TL, true, false>(epi, a, st);
+  if (layout == L_NT) return by_epilogue<TL, true, true>(epi, a, st);
+  if (epi != E_ACCUM) { set_error("gemm_mfma: the weight-gradient layout stores fp32 with E_ACCUM only"); return BF_EINVAL; }
+  return launch<TL, false, false, E_ACCUM, float>(a, st);
+}
+
+inline bool big_fits(int M, int N) { return M % 256 == 0 && N % 256 == 0 && (long)(M / 256) * (N / 256) >= 128; }
+inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
+
+}  // namespace
+
+bool gemm_mfma_supported(int layout, int epi, int M, int N, int K) {
+  if (layout < L_NN || layout > L_TN) return false;
+  if ((layout == L_TN) != (epi == E_ACCUM)) return false;
+  if (epi < E_NONE || epi > E_ACCUM) return false;
+  if (M < 1 || N < 1 || K < BK || K % BK) return false;
+  return small_fits(M, N);
+}
+
+bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
+  if (!gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) { set_error("gemm_mfma: shape not supported"); return BF_EINVAL; }
+  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2;
+  if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
+  if (big_fits(a.M, a.N)) return by_layout<TileBig>(layout, epi, a, st);
+  return by_layout<TileSmall>(layout, epi, a, st);
+}
+
 }  // namespace bf

@@ -113,7 +113,8 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 }
 
 bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st) {
-  if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
+  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2;
+  if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
     bf_status s = gemm_check(layout, epi, a);
     if (s != BF_OK) return s;
     return gemm_mfma(layout, epi, a, st);

@@ -129,6 +129,31 @@ def test_attention_fwd_bwd(mode, dtype, kernels, causal, S_mb, S_seq, a, d):
         assert rel_err(got[..., i * h:(i + 1) * h], dqkv_ref[..., i * h:(i + 1) * h]) <= TOL[mode], name
 
 
+@pytest.mark.parametrize("M,N,K", [(2048, 4096, 512), (4096, 2048, 192), (512, 16384, 128)])
+def test_gemm_mfma_large_tile(M, N, K):
+    """Shapes that take the 256 x 256 workgroup tile of the MFMA kernel, all layouts."""
+    assert bf.bf_op_gemm_uses_mfma(bf.BF_NN, bf.BF_EPI_NONE, M, N, K)
+    A = bf_inputs.normal(5, 0, (M, K), bf16=True)
+    B = bf_inputs.normal(5, 1, (K, N), 0.05, bf16=True)
+    bias = bf_inputs.normal(5, 2, (N,), 0.5)
+    R = bf_inputs.normal(5, 3, (M, N), bf16=True)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    dA, dB, dR, dbias = to_dev(A, True), to_dev(B, True), to_dev(R, True), to_dev(bias, False)
+    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    out2 = torch.empty_like(out)
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NN, bf.BF_EPI_BIAS_RES, M, N, K, dA, dB, out, bias=dbias, R=dR)
+    assert rel_err(to_host(out), acc + bias + R) <= TOL["bf16"]
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NN, bf.BF_EPI_BIAS_GELU, M, N, K, dA, dB, out, bias=dbias, C2=out2)
+    assert rel_err(to_host(out2), L.gelu(acc + bias)) <= TOL["bf16"]
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NT, bf.BF_EPI_GELU_BWD, M, N, K, dA, to_dev(np.ascontiguousarray(B.T), True), out, R=dR)
+    assert rel_err(to_host(out), acc * L.gelu_grad(R.astype(np.float64))) <= TOL["bf16"]
+    G = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    dAt = to_dev(np.ascontiguousarray(A.T), True)
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, K, dAt, dB, G, accumulate=0)
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, K, dAt, dB, G, accumulate=1)
+    assert rel_err(to_host(G), 2 * acc) <= 1e-5   # bf16 products are exact in fp32; only the summation order differs
+
+
 @pytest.mark.parametrize("n", [1, 1000, 4096 * 33 + 4])
 def test_adam_kernel(n):
     rng = np.random.default_rng(4)
