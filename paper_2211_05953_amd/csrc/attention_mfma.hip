@@ -1,8 +1,421 @@
-// bf16 MFMA attention for gfx950 (placeholder until the kernel lands).
+// Fused attention on the gfx950 matrix cores: softmax(Q K^T / sqrt(S_head) [+ causal mask]) V
+// forward, and its backward as two deterministic passes (dQ pass over key blocks, dK/dV pass
+// over query blocks) that recompute the probabilities from the saved log-sum-exp.  No
+// S_seq x S_seq tensor ever reaches HBM and nothing is accumulated with atomics, so the
+// result does not depend on scheduling.
+//
+// Every score tile is computed TRANSPOSED where that keeps "one lane = one softmax row":
+//   forward / dQ pass:  S^T = K Q^T   (MFMA rows = keys,    columns = the wave's 32 queries)
+//   dK/dV pass:         S   = Q K^T   (MFMA rows = queries, columns = the wave's 32 keys)
+// In the accumulator layout of v_mfma_f32_32x32x16_bf16 (lane l, register r holds
+// row (r/4)*8 + (l/32)*4 + r%4, column l%32) a lane then owns one column and 16 rows, so a
+// row statistic of the softmax is a per-lane scalar (forward) and the 8 registers
+// 8kk..8kk+7 of a lane, rounded to bf16, are directly the B operand of the next product
+// for the contraction rows 16kk + 8(e/4) + 4(l/32) + e%4.  The matching A operand is read
+// from LDS with the transpose load (ds_read_b64_tr_b16) using that same row order.
+//
+// LDS tiles are [row][S_head] with the 16-byte chunk index XOR-swizzled by row & 7; the
+// layout serves both the K-contiguous 16-byte fragment reads and the transpose loads.
 #include "common.h"
 
 namespace bf {
-bool attention_mfma_supported(int, int) { return false; }
-bf_status attention_fwd_mfma(int, int, int, int, int, const void*, void*, float*, hipStream_t) { set_error("attention_mfma: not built"); return BF_EINVAL; }
-bf_status attention_bwd_mfma(int, int, int, int, int, const void*, const void*, const float*, const void*, void*, float*, hipStream_t) { set_error("attention_mfma: not built"); return BF_EINVAL; }
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+constexpr int NTHR = 256;   // 4 waves; wave w owns rows 32w..32w+31 of the workgroup's 128-row block
+constexpr int WG_ROWS = 128;
+constexpr int BLK = 64;     // rows of the streamed tiles (keys in forward/dQ, queries in dK/dV)
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+template <int D>
+__device__ __forceinline__ int swz(int row, int col) {
+  return row * D + ((((col >> 3) ^ (row & 7)) << 3) | (col & 7));
+}
+
+// thread's 16-byte chunks of a [ROWS][D] tile
+template <int ROWS, int D>
+struct TileRegs {
+  static constexpr int CH = ROWS * D / 8 / NTHR;
+  u32x4 v[CH];
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int tid) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NTHR, row = c / (D / 8), ch = c % (D / 8);
+      v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + ch * 8);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NTHR, row = c / (D / 8), ch = c % (D / 8);
+      *reinterpret_cast<u32x4*>(lds + row * D + ((ch ^ (row & 7)) << 3)) = v[i];
+    }
+  }
+};
+
+// A operand, contraction along the tile's columns: lane holds tile[row0 + l%32][16kk + 8(l/32) .. +7]
+template <int D>
+__device__ __forceinline__ bf16x8 frag_k(const bf16_t* tile, int row0, int kk, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + swz<D>(row0 + (lane & 31), kk * 16 + 8 * (lane >> 5)));
+}
+
+// A operand, contraction along the tile's rows in the accumulator order: lane holds
+// tile[rowbase + 8(e/4) + 4(l/32) + e%4][col0 + l%32] for e = 0..7
+template <int D>
+__device__ __forceinline__ bf16x8 frag_t(const bf16_t* tile, int rowbase, int col0, int lane) {
+  const int t = lane & 15, blk = lane >> 4;
+  const int row = rowbase + 4 * (blk >> 1) + (t >> 2);
+  const int col = col0 + 16 * (blk & 1) + 4 * (t & 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_v4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + swz<D>(row, col)));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + swz<D>(row + 8, col)));
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// registers 8kk..8kk+7 of an accumulator tile as a bf16 B operand
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int kk) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)a[8 * kk + e];
+  return o;
+}
+
+// B operand straight from global memory: lane holds row[16kk + 8(l/32) .. +7] of its own token row
+template <int D>
+__device__ __forceinline__ void load_rowfrags(const bf16_t* __restrict__ row, int lane, bf16x8 (&f)[D / 16]) {
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) f[kk] = *reinterpret_cast<const bf16x8*>(row + kk * 16 + 8 * (lane >> 5));
+}
+
+__device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+
+// store a transposed accumulator set acc[dt] (rows = head dims, column = this lane's token) as a token row
+template <int D>
+__device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], bf16_t* __restrict__ row, int lane, float mul) {
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[dt][q4 * 4 + e] * mul);
+      *reinterpret_cast<bf16x4*>(row + dt * 32 + q4 * 8 + (lane >> 5) * 4) = o;
+    }
+}
+
+// ------------------------------------------------------------------------------ forward
+template <int D>
+__global__ __launch_bounds__(NTHR) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+                                                        float* __restrict__ lse, int S_seq, int N_heads, int causal,
+                                                        float scale) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[BLK * D];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[BLK * D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int qblk = gridDim.x - 1 - blockIdx.x;  // longest rows first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int h = N_heads * D;
+  const size_t ld = 3 * (size_t)h;
+  const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
+  const int q0 = qblk * WG_ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
+
+  bf16x8 qf[D / 16];
+  load_rowfrags<D>(base + (size_t)q * ld, lane, qf);
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) o[dt] = zero16();
+  float m = -INFINITY, l = 0.f;
+  const float c2 = scale * LOG2E;
+
+  const int nblk = causal ? (q0 + WG_ROWS) / BLK : S_seq / BLK;
+  TileRegs<BLK, D> kr, vr;
+  kr.load(base + h, ld, tid);
+  vr.load(base + 2 * h, ld, tid);
+  for (int j = 0; j < nblk; ++j) {
+    __syncthreads();  // previous block's readers are done
+    kr.store(Ks, tid);
+    vr.store(Vs, tid);
+    __syncthreads();
+    if (j + 1 < nblk) {
+      kr.load(base + (size_t)(j + 1) * BLK * ld + h, ld, tid);
+      vr.load(base + (size_t)(j + 1) * BLK * ld + 2 * h, ld, tid);
+    }
+    const int kb = j * BLK;
+    if (causal && kb > qw + 31) continue;  // the whole tile is above this wave's diagonal
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      s[t] = zero16();
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s[t], 0, 0, 0);
+    }
+    float mx = m;
+    const bool diag = causal && kb + BLK - 1 > qw;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = s[t][r] * c2;
+        if (diag && kb + 32 * t + acc_row(r, lane) > q) v = -INFINITY;
+        s[t][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float alpha = exp2f(m - mx);
+    m = mx;
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[t][r] - mx);
+        s[t][r] = p;
+        sum += p;
+      }
+    l = l * alpha + sum;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        const bf16x8 pb = pack8(s[t], k2);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Vs, 32 * t + 16 * k2, 32 * dt, lane), pb, o[dt], 0, 0, 0);
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  store_rows<D>(o, ctx + ((size_t)b * S_seq + q) * h + head * D, lane, 1.0f / l);
+  if (lane < 32) lse[((size_t)b * N_heads + head) * S_seq + q] = m * LN2 + logf(l);
+}
+
+// delta[b, head, i] = sum_c dctx[i, c] * ctx[i, c]: one wave per (token, head)
+template <int D>
+__global__ __launch_bounds__(NTHR) void attn_delta_kernel(const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx,
+                                                          float* __restrict__ delta, int S_seq, int N_heads) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int i = blockIdx.x * 4 + w, head = blockIdx.y, b = blockIdx.z;
+  const size_t off = ((size_t)b * S_seq + i) * (N_heads * D) + head * D;
+  float s = 0.f;
+  for (int c = lane; c < D; c += 64) s = fmaf((float)dctx[off + c], (float)ctx[off + c], s);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) delta[((size_t)b * N_heads + head) * S_seq + i] = s;
+}
+
+// ------------------------------------------------------------------- backward, dQ pass
+template <int D>
+__global__ __launch_bounds__(NTHR) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
+                                                           float scale) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[BLK * D];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[BLK * D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int h = N_heads * D;
+  const size_t ld = 3 * (size_t)h;
+  const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
+  const int q0 = qblk * WG_ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  load_rowfrags<D>(base + (size_t)q * ld, lane, qf);
+  load_rowfrags<D>(dctx + ((size_t)b * S_seq + q) * h + head * D, lane, dof);
+  const size_t st = ((size_t)b * N_heads + head) * S_seq + q;
+  const float lse2 = lse[st] * LOG2E, dl = delta[st], c2 = scale * LOG2E;
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
+
+  const int nblk = causal ? (q0 + WG_ROWS) / BLK : S_seq / BLK;
+  TileRegs<BLK, D> kr, vr;
+  kr.load(base + h, ld, tid);
+  vr.load(base + 2 * h, ld, tid);
+  for (int j = 0; j < nblk; ++j) {
+    __syncthreads();
+    kr.store(Ks, tid);
+    vr.store(Vs, tid);
+    __syncthreads();
+    if (j + 1 < nblk) {
+      kr.load(base + (size_t)(j + 1) * BLK * ld + h, ld, tid);
+      vr.load(base + (size_t)(j + 1) * BLK * ld + 2 * h, ld, tid);
+    }
+    const int kb = j * BLK;
+    if (causal && kb > qw + 31) continue;
+    const bool diag = causal && kb + BLK - 1 > qw;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Vs, 32 * t, kk, lane), dof[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = exp2f(s[r] * c2 - lse2);
+        if (diag && kb + 32 * t + acc_row(r, lane) > q) p = 0.f;
+        s[r] = p * (dp[r] - dl) * scale;
+      }
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        const bf16x8 dsb = pack8(s, k2);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Ks, 32 * t + 16 * k2, 32 * dt, lane), dsb, dq[dt], 0, 0, 0);
+      }
+    }
+  }
+  store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, 1.0f);
+}
+
+// ----------------------------------------------------------------- backward, dK/dV pass
+template <int D>
+__global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                            const float* __restrict__ lse, const float* __restrict__ delta,
+                                                            bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
+                                                            float scale) {
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[BLK * D];
+  __shared__ __attribute__((aligned(16))) bf16_t dOs[BLK * D];
+  __shared__ float lse_s[BLK], delta_s[BLK];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int kblk = blockIdx.x;  // earliest keys see the most queries: they go first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int h = N_heads * D;
+  const size_t ld = 3 * (size_t)h;
+  const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
+  const bf16_t* dob = dctx + (size_t)b * S_seq * h + head * D;
+  const float* lrow = lse + ((size_t)b * N_heads + head) * S_seq;
+  const float* drow = delta + ((size_t)b * N_heads + head) * S_seq;
+  const int k0 = kblk * WG_ROWS, kw = k0 + 32 * w, key = kw + (lane & 31);
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  load_rowfrags<D>(base + (size_t)key * ld + h, lane, kf);
+  load_rowfrags<D>(base + (size_t)key * ld + 2 * h, lane, vf);
+  const float c2 = scale * LOG2E;
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
+
+  const int jbeg = causal ? k0 / BLK : 0, nblk = S_seq / BLK;
+  TileRegs<BLK, D> qr, dor;
+  qr.load(base + (size_t)jbeg * BLK * ld, ld, tid);
+  dor.load(dob + (size_t)jbeg * BLK * h, h, tid);
+  float lnext = 0.f, dnext = 0.f;
+  if (tid < BLK) { lnext = lrow[jbeg * BLK + tid] * LOG2E; dnext = drow[jbeg * BLK + tid]; }
+  for (int j = jbeg; j < nblk; ++j) {
+    __syncthreads();
+    qr.store(Qs, tid);
+    dor.store(dOs, tid);
+    if (tid < BLK) { lse_s[tid] = lnext; delta_s[tid] = dnext; }
+    __syncthreads();
+    if (j + 1 < nblk) {
+      qr.load(base + (size_t)(j + 1) * BLK * ld, ld, tid);
+      dor.load(dob + (size_t)(j + 1) * BLK * h, h, tid);
+      if (tid < BLK) { lnext = lrow[(j + 1) * BLK + tid] * LOG2E; dnext = drow[(j + 1) * BLK + tid]; }
+    }
+    const int qb = j * BLK;
+    if (causal && qb + BLK - 1 < kw) continue;  // every query of the tile is before this wave's keys
+    const bool diag = causal && qb < kw + 31;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Qs, 32 * t, kk, lane), kf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(dOs, 32 * t, kk, lane), vf[kk], dp, 0, 0, 0);
+      }
+      f32x16 pr;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int ql = 32 * t + acc_row(r, lane);
+        float p = exp2f(s[r] * c2 - lse_s[ql]);
+        if (diag && key > qb + ql) p = 0.f;
+        pr[r] = p;
+        s[r] = p * (dp[r] - delta_s[ql]) * scale;
+      }
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        const bf16x8 pb = pack8(pr, k2), dsb = pack8(s, k2);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(dOs, 32 * t + 16 * k2, 32 * dt, lane), pb, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Qs, 32 * t + 16 * k2, 32 * dt, lane), dsb, dk[dt], 0, 0, 0);
+        }
+      }
+    }
+  }
+  bf16_t* out = dqkv + ((size_t)b * S_seq + key) * ld + head * D;
+  store_rows<D>(dk, out + h, lane, 1.0f);
+  store_rows<D>(dv, out + 2 * h, lane, 1.0f);
+}
+
+template <int D>
+bf_status fwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, void* ctx, float* lse, hipStream_t st) {
+  dim3 grid(S_seq / WG_ROWS, N_heads, S_mb);
+  attn_fwd_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, causal, 1.0f / sqrtf((float)D));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_error("attention_fwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
+  return BF_OK;
+}
+
+template <int D>
+bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, const void* ctx, const float* lse,
+                const void* dctx, void* dqkv, float* delta, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)D);
+  attn_delta_kernel<D><<<dim3(S_seq / 4, N_heads, S_mb), NTHR, 0, st>>>((const bf16_t*)ctx, (const bf16_t*)dctx, delta, S_seq, N_heads);
+  dim3 grid(S_seq / WG_ROWS, N_heads, S_mb);
+  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
+  attn_bwd_dkv_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
+  return BF_OK;
+}
+
+bool args_ok(int S_mb, int S_seq, int N_heads, int S_head, const void* a, const void* b2) {
+  if (!attention_mfma_supported(S_seq, S_head)) { set_error("attention_mfma: needs S_head 64 or 128 and S_seq a multiple of 128"); return false; }
+  if (S_mb < 1 || N_heads < 1 || S_mb > 65535 || N_heads > 65535) { set_error("attention_mfma: bad S_mb / N_heads"); return false; }
+  if (((uintptr_t)a | (uintptr_t)b2) & 15) { set_error("attention_mfma: tensors must be 16-byte aligned"); return false; }
+  return true;
+}
+
+}  // namespace
+
+bool attention_mfma_supported(int S_seq, int S_head) {
+  return (S_head == 64 || S_head == 128) && S_seq >= WG_ROWS && S_seq % WG_ROWS == 0;
+}
+
+bf_status attention_fwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal, const void* qkv, void* ctx,
+                             float* lse, hipStream_t st) {
+  if (!args_ok(S_mb, S_seq, N_heads, S_head, qkv, ctx)) return BF_EINVAL;
+  if (S_head == 128) return fwd_d<128>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, st);
+  return fwd_d<64>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, st);
+}
+
+bf_status attention_bwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal, const void* qkv, const void* ctx,
+                             const float* lse, const void* dctx, void* dqkv, float* delta, hipStream_t st) {
+  if (!args_ok(S_mb, S_seq, N_heads, S_head, qkv, dqkv) || !args_ok(S_mb, S_seq, N_heads, S_head, ctx, dctx)) return BF_EINVAL;
+  if (S_head == 128) return bwd_d<128>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+  return bwd_d<64>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+}
+
 }  // namespace bf
