@@ -1,0 +1,177 @@
+"""Benchmark of the breadth-first training-step path on one MI355X.
+
+A "step" is one pass of the whole hot path: forward and backward of the rank's N_loop stages
+over N_mb micro-batches in breadth-first order, fp32 main-grad accumulation and the fused Adam
+step per stage (bf_run_step with apply_optimizer = 1).  The default workload is the
+52B-shaped rank share at S_mb = 1 (8 layers as 4 stages of 2, S_hidden 8192, 64 heads,
+S_mlp 32768, S_seq 2048, N_mb 16, bf16 with fp32 main-grads), seeded synthetic inputs
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+PEAK_HBM_GBS = 8000.0
+
+# name: (N_layers, N_loop, S_hidden, N_heads, S_mlp, S_seq, S_mb, N_mb, dtype, ckpt)
+WORKLOADS = {
+    "c1": (4, 2, 256, 4, 1024, 128, 1, 4, "fp32", "none"),
+    "c2": (6, 3, 2048, 16, 8192, 2048, 1, 8, "bf16", "none"),
+    "c3": (8, 4, 8192, 64, 32768, 2048, 1, 16, "bf16", "none"),
+    "c4": (8, 4, 8192, 64, 32768, 2048, 4, 4, "bf16", "none"),
+    "c5": (16, 16, 6144, 48, 24576, 2048, 1, 32, "bf16", "layer"),
+}
+WORKLOAD_TEXT = {
+    "c1": "tiny GPT stack fp32 (parity case)",
+    "c2": "1.3B-shaped stack",
+    "c3": "52B-shaped rank share, S_mb=1, N_mb=16",
+    "c4": "52B-shaped rank share, S_mb=4, N_mb=4",
+    "c5": "deep-loop stress case, N_loop=16, N_mb=32, per-layer checkpoints",
+}
+
+
+def time_steps(st, bf, schedule, N_loop, N_mb, S_mb, x, dy, y, dx, steps, warmup, timing):
+    import torch
+    for _ in range(warmup):
+        st.bf_run_step(schedule, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer=1, timing=0)
+    torch.cuda.synchronize()
+    reports = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        reports.append(st.bf_run_step(schedule, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer=1, timing=timing))
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps, reports
+
+
+def cpu_baseline(w, budget_note=True):
+    """The CPU oracle, as it stands, on one layer and one micro-batch of the same workload
+    (forward + backward), timed on the host cores."""
+    import numpy as np
+
+    import bf_inputs
+    from oracle import formulas as F
+    from oracle import stack as K
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, _ = w
+    params = bf_inputs.make_params(1, 1, h, f, bf16=dtype == "bf16")
+    p64 = [{k: v.astype(np.float64) for k, v in params[0].items()}]
+    del params
+    x, dy = bf_inputs.make_batch(1, 1, S_mb, S_seq, h, bf16=dtype == "bf16")
+    t0 = time.perf_counter()
+    K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), K.SCHED_BF, 1, a)
+    dt = time.perf_counter() - t0
+    flops = 3.0 * float(F.fwd_flops_layer_mb(h, S_seq, S_mb)) if f == 4 * h else None
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": flops / dt / 1e12, "unit": "model TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 layer x 1 micro-batch of %d (same S_hidden/S_seq/S_mb), forward+backward, %.1f s; "
+                      "fp64 numpy" % (Lyr * N_mb, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-df", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one pipeline rank's share of the step); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2211_05953_amd as bf
+    bf.load()   # no fallback: a missing library is an error
+    w = WORKLOADS[args.workload]
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, ckpt = w
+    b16 = dtype == "bf16"
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
+                         ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0)
+    torch.cuda.set_device(0)
+    st = bf.Stack(cfg, device="cuda:0")
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x221105953)
+    td = torch.bfloat16 if b16 else torch.float32
+    shape = (N_mb, S_mb, S_seq, h)
+    x = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+    dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+
+    sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 2)
+    r = rep_bf[-1]
+    out_df = None
+    if not args.no_df:
+        sec_df, rep_df = time_steps(st, bf, bf.BF_SCHED_DF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, 1, 1)
+        rd = rep_df[-1]
+        out_df = {"ms_per_step": sec_df * 1e3, "model_tflops": rd.flops_model / sec_df / 1e12,
+                  "peak_ckpt_count": rd.peak_ckpt_count, "peak_ckpt_bytes": rd.peak_ckpt_bytes,
+                  "peak_act_bytes": rd.peak_act_bytes}
+    # one plain-timed BF step to show what the per-launch events cost
+    sec_plain, _ = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 1, 0, 1)
+
+    # per-kernel-class figures, averaged over the timed BF steps
+    kern = {}
+    for i, name in enumerate(bf.binding.KERNEL_CLASSES):
+        ms = sum(rp.kernel_ms[i] for rp in rep_bf) / len(rep_bf)
+        n = sum(rp.kernel_launches[i] for rp in rep_bf) / len(rep_bf)
+        fl = sum(rp.kernel_flops[i] for rp in rep_bf) / len(rep_bf)
+        by = sum(rp.kernel_bytes[i] for rp in rep_bf) / len(rep_bf)
+        if n:
+            kern[name] = {"ms_per_step": ms, "launches": n, "avg_launch_ms": ms / n,
+                          "tflops": fl / ms / 1e9 if fl else None, "gbs": by / ms / 1e6 if by else None}
+    dom = max((k for k in kern if k.startswith("gemm")), key=lambda k: kern[k]["ms_per_step"])
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": kern[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                "flops_per_launch": kern[dom]["tflops"] * 1e9 * kern[dom]["avg_launch_ms"],
+                "avg_launch_ms": kern[dom]["avg_launch_ms"]}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        t = json.load(open(traffic_file)).get(args.workload, {}).get(dom)
+        if t:
+            roofline["traffic"] = t
+
+    value = r.flops_model / sec_bf / 1e12
+    line = {
+        "metric": "model TFLOP/s per training step at S_mb=1, BF order (3x forward flops, full attention)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_bf * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "N_layers": Lyr, "N_loop": N_loop,
+                   "S_hidden": h, "N_heads": a, "S_mlp": f, "S_seq": S_seq, "S_mb": S_mb, "N_mb": N_mb,
+                   "schedule": "BF", "ckpt": ckpt, "tokens_per_step": N_mb * S_mb * S_seq},
+        "frac_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
+        "paper_eq_tflops": r.flops_paper / sec_bf / 1e12,
+        "executed_tflops": r.flops_executed / sec_bf / 1e12,
+        "tokens_per_s": N_mb * S_mb * S_seq / sec_bf,
+        "bf": {"peak_ckpt_count": r.peak_ckpt_count, "peak_ckpt_bytes": r.peak_ckpt_bytes,
+               "peak_act_bytes": r.peak_act_bytes, "state_bytes": r.state_bytes, "adam_ms": r.adam_ms,
+               "ms_per_step_without_launch_events": sec_plain * 1e3},
+        "df": out_df,
+        "kernels": kern,
+        "roofline": roofline,
+    }
+    st.close()
+    del x, dy, y, dx
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

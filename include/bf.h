@@ -79,6 +79,16 @@ typedef struct {
  * event, the count of Eq. mem_ckpt. */
 typedef struct { int32_t op, stage, mb, live_ckpt; } bf_event;
 
+/* Kernel classes of the per-launch timing (bf_run_step with timing == 2). */
+typedef enum {
+  BF_K_GEMM_FWD = 0,   /* Y = X W           (QKV, out-proj, FC1, FC2) */
+  BF_K_GEMM_DGRAD = 1, /* dX = dY W^T */
+  BF_K_GEMM_WGRAD = 2, /* G += X^T dY into the fp32 main-grad */
+  BF_K_ATTN_FWD = 3, BF_K_ATTN_BWD = 4,
+  BF_K_LN_FWD = 5, BF_K_LN_BWD = 6, BF_K_COLSUM = 7, BF_K_ADAM = 8,
+  BF_N_KERNEL_CLASSES = 9
+} bf_kernel_class;
+
 typedef struct {
   double gpu_ms;            /* whole step on the device (events on the caller's stream) */
   double adam_ms;           /* sum of the fused Adam launches (side stream in BF) */
@@ -91,6 +101,14 @@ typedef struct {
   int64_t state_bytes;      /* weights, Adam moments, main-grads, low-precision weights */
   int32_t n_events;
   int32_t timed;            /* 1 if gpu_ms / adam_ms are valid (bf_run_step ... timing != 0) */
+  /* timing == 2 only: per kernel class, summed over the step's launches: device time between
+   * events recorded around each launch on its stream, launch count, algorithmic flops
+   * (2 M N K per product; attention with the causal half; backward attention 2.5 x forward) and
+   * algorithmic HBM bytes (every operand read once, every result written once). */
+  double kernel_ms[BF_N_KERNEL_CLASSES];
+  double kernel_flops[BF_N_KERNEL_CLASSES];
+  double kernel_bytes[BF_N_KERNEL_CLASSES];
+  int64_t kernel_launches[BF_N_KERNEL_CLASSES];
 } bf_step_report;
 
 typedef struct {
@@ -135,7 +153,8 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *   dy           device, same shape/dtype: gradient of the loss w.r.t. the last stage's output
  *   y, dx        device outputs, same shape/dtype; either may be NULL
  *   apply_optimizer  0: gradients only; 1: fused Adam per stage when its gradient is final
- *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end)
+ *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end);
+ *                2: as 1, plus an event pair around every kernel launch -> report->kernel_*
  *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
  *                on it (unless timing != 0); the library's side stream joins it before returning
  *                control of the stream to later work.

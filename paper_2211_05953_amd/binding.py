@@ -32,7 +32,12 @@ class bf_event(C.Structure):
 class bf_step_report(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("gpu_ms", "adam_ms", "flops_model", "flops_paper", "flops_executed")] + \
                [(n, C.c_int64) for n in ("peak_ckpt_count", "peak_ckpt_bytes", "peak_act_bytes", "state_bytes")] + \
-               [("n_events", C.c_int32), ("timed", C.c_int32)]
+               [("n_events", C.c_int32), ("timed", C.c_int32)] + \
+               [("kernel_ms", C.c_double * 9), ("kernel_flops", C.c_double * 9), ("kernel_bytes", C.c_double * 9),
+                ("kernel_launches", C.c_int64 * 9)]
+
+
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam")
 
 
 class bf_sched_stats(C.Structure):

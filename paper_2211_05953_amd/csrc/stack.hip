@@ -173,6 +173,11 @@ struct bf_stack {
   std::vector<hipEvent_t> adam_ev;   // pairs of events per stage for timing
   std::vector<hipEvent_t> queue_ev;  // ring for the bounded launch queue
   std::vector<bf_event> trace;
+  // per-kernel-class timing (timing == 2): event pairs around every launch of a step
+  bool prof_on;
+  std::vector<hipEvent_t> prof_ev;
+  struct ProfRec { int cls; double flops, bytes; };
+  std::vector<ProfRec> prof_rec;
   int step;               // optimizer step counter
   bool have_grads;
   int device;
@@ -227,11 +232,69 @@ Tmp tmp_of(bf_stack* s) {
   return T;
 }
 
+// Runs one kernel launcher; with profiling on, brackets it with a pair of events on its stream.
+template <typename F>
+bf_status timed(bf_stack* s, int cls, double flops, double bytes, hipStream_t st, F&& call) {
+  if (!s->prof_on) return call();
+  const size_t i = s->prof_rec.size();
+  while (s->prof_ev.size() < 2 * (i + 1)) {
+    hipEvent_t e;
+    BF_HIP_CHECK(hipEventCreate(&e));
+    s->prof_ev.push_back(e);
+  }
+  BF_HIP_CHECK(hipEventRecord(s->prof_ev[2 * i], st));
+  bf_status r = call();
+  if (r != BF_OK) return r;
+  BF_HIP_CHECK(hipEventRecord(s->prof_ev[2 * i + 1], st));
+  s->prof_rec.push_back({cls, flops, bytes});
+  return BF_OK;
+}
+
 #define BF_TRY(expr)            \
   do {                          \
     bf_status s__ = (expr);     \
     if (s__ != BF_OK) return s__; \
   } while (0)
+
+// ---- launchers with per-class accounting: algorithmic flops (MFMA-bound classes) and
+// algorithmic HBM bytes (bandwidth-bound classes) of each launch
+bf_status p_gemm(bf_stack* s, int layout, int epi, const GemmArgs& g, hipStream_t st) {
+  const int cls = layout == L_NN ? BF_K_GEMM_FWD : layout == L_NT ? BF_K_GEMM_DGRAD : BF_K_GEMM_WGRAD;
+  const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
+  double bytes = es * ((double)g.M * g.K + (double)g.K * g.N) + (layout == L_TN ? (g.accumulate ? 8.0 : 4.0) : es) * g.M * g.N;
+  return timed(s, cls, 2.0 * g.M * g.N * g.K, bytes, st, [&] { return gemm(s->cfg.dtype, s->cfg.kernels, layout, epi, g, st); });
+}
+bf_status p_ln_fwd(bf_stack* s, int T, int h, const void* x, const float* g, const float* b, float eps, void* y, float* stats,
+                   hipStream_t st) {
+  const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
+  return timed(s, BF_K_LN_FWD, 0.0, 2.0 * es * T * h, st, [&] { return layernorm_fwd(s->cfg.dtype, T, h, x, g, b, eps, y, stats, st); });
+}
+bf_status p_ln_bwd(bf_stack* s, int T, int h, const void* dy, const void* x, const float* g, const float* stats, const void* dres,
+                   void* dx, float* dg, float* db, int acc, hipStream_t st) {
+  const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
+  return timed(s, BF_K_LN_BWD, 0.0, 4.0 * es * T * h, st,
+               [&] { return layernorm_bwd(s->cfg.dtype, T, h, dy, x, g, stats, dres, dx, dg, db, acc, st); });
+}
+bf_status p_colsum(bf_stack* s, int T, int N, const void* dY, float* out, int acc, hipStream_t st) {
+  const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
+  return timed(s, BF_K_COLSUM, 0.0, es * T * N, st, [&] { return colsum(s->cfg.dtype, T, N, dY, out, acc, st); });
+}
+bf_status p_attn_fwd(bf_stack* s, int S_mb, const void* qkv, void* ctx, float* lse, hipStream_t st) {
+  const bf_config& c = s->cfg;
+  const double full = 4.0 * c.S_seq * (double)S_mb * c.S_seq * c.S_hidden;
+  return timed(s, BF_K_ATTN_FWD, c.causal ? full / 2 : full, 0.0, st, [&] {
+    return attention_fwd(c.dtype, c.kernels, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, qkv, ctx, lse, st);
+  });
+}
+bf_status p_attn_bwd(bf_stack* s, int S_mb, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                     float* delta, hipStream_t st) {
+  const bf_config& c = s->cfg;
+  const double full = 4.0 * c.S_seq * (double)S_mb * c.S_seq * c.S_hidden;
+  // algorithmic backward = 2.5 x forward (five score-sized products); the two-pass kernels run seven
+  return timed(s, BF_K_ATTN_BWD, 2.5 * (c.causal ? full / 2 : full), 0.0, st, [&] {
+    return attention_bwd(c.dtype, c.kernels, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+  });
+}
 
 // Forward of one layer on T tokens.  x: layer input; R: where the activations go; y: output.
 // skip_fc2: recomputation before a backward does not need the layer output.
@@ -240,19 +303,19 @@ bf_status layer_forward(bf_stack* s, int layer, int S_mb, const void* x, const R
   const bf_config& c = s->cfg;
   const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp, dt = c.dtype, kn = c.kernels;
   auto P = [&](int tid) { return param_ptr(s, s->w32, layer, tid); };
-  BF_TRY(layernorm_fwd(dt, T, h, x, P(BF_LN1_G), P(BF_LN1_B), c.ln_eps, R.a, R.ln1, st));
+  BF_TRY(p_ln_fwd(s, T, h, x, P(BF_LN1_G), P(BF_LN1_B), c.ln_eps, R.a, R.ln1, st));
   GemmArgs g{};
   g = GemmArgs{T, 3 * h, h, R.a, weight_ptr(s, layer, BF_W_QKV), R.qkv, P(BF_B_QKV), nullptr, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NN, E_BIAS, g, st));
-  BF_TRY(attention_fwd(dt, kn, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, R.qkv, R.ctx, R.lse, st));
+  BF_TRY(p_gemm(s, L_NN, E_BIAS, g, st));
+  BF_TRY(p_attn_fwd(s, S_mb, R.qkv, R.ctx, R.lse, st));
   g = GemmArgs{T, h, h, R.ctx, weight_ptr(s, layer, BF_W_O), R.x1, P(BF_B_O), x, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NN, E_BIAS_RES, g, st));
-  BF_TRY(layernorm_fwd(dt, T, h, R.x1, P(BF_LN2_G), P(BF_LN2_B), c.ln_eps, R.c, R.ln2, st));
+  BF_TRY(p_gemm(s, L_NN, E_BIAS_RES, g, st));
+  BF_TRY(p_ln_fwd(s, T, h, R.x1, P(BF_LN2_G), P(BF_LN2_B), c.ln_eps, R.c, R.ln2, st));
   g = GemmArgs{T, f, h, R.c, weight_ptr(s, layer, BF_W_FC1), R.u, P(BF_B_FC1), nullptr, R.g, 0};
-  BF_TRY(gemm(dt, kn, L_NN, E_BIAS_GELU, g, st));
+  BF_TRY(p_gemm(s, L_NN, E_BIAS_GELU, g, st));
   if (!skip_fc2) {
     g = GemmArgs{T, h, f, R.g, weight_ptr(s, layer, BF_W_FC2), y, P(BF_B_FC2), R.x1, nullptr, 0};
-    BF_TRY(gemm(dt, kn, L_NN, E_BIAS_RES, g, st));
+    BF_TRY(p_gemm(s, L_NN, E_BIAS_RES, g, st));
   }
   return BF_OK;
 }
@@ -269,34 +332,34 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
   GemmArgs g{};
   // y = x1 + gelu(u) W_fc2 + b_fc2
   g = GemmArgs{f, h, T, R.g, dy, G(BF_W_FC2), nullptr, nullptr, nullptr, acc};
-  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
-  BF_TRY(colsum(dt, T, h, dy, G(BF_B_FC2), acc, st));
+  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  BF_TRY(p_colsum(s, T, h, dy, G(BF_B_FC2), acc, st));
   g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), t.du, nullptr, R.u, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NT, E_GELU_BWD, g, st));
+  BF_TRY(p_gemm(s, L_NT, E_GELU_BWD, g, st));
   // u = c W_fc1 + b_fc1
   g = GemmArgs{h, f, T, R.c, t.du, G(BF_W_FC1), nullptr, nullptr, nullptr, acc};
-  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
-  BF_TRY(colsum(dt, T, f, t.du, G(BF_B_FC1), acc, st));
+  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  BF_TRY(p_colsum(s, T, f, t.du, G(BF_B_FC1), acc, st));
   g = GemmArgs{T, h, f, t.du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
+  BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // c = LN2(x1); dx1 = dy + LN2'(dc)
-  BF_TRY(layernorm_bwd(dt, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, t.dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, t.dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
   // x1 = x + ctx W_o + b_o
   g = GemmArgs{h, h, T, R.ctx, t.dx1, G(BF_W_O), nullptr, nullptr, nullptr, acc};
-  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
-  BF_TRY(colsum(dt, T, h, t.dx1, G(BF_B_O), acc, st));
+  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  BF_TRY(p_colsum(s, T, h, t.dx1, G(BF_B_O), acc, st));
   g = GemmArgs{T, h, h, t.dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
-  BF_TRY(attention_bwd(dt, kn, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, R.qkv, R.ctx, R.lse, t.dctx, t.dqkv,
+  BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
+  BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, t.dqkv,
                        t.delta, st));
   // qkv = a W_qkv + b_qkv
   g = GemmArgs{h, 3 * h, T, R.a, t.dqkv, G(BF_W_QKV), nullptr, nullptr, nullptr, acc};
-  BF_TRY(gemm(dt, kn, L_TN, E_ACCUM, g, st));
-  BF_TRY(colsum(dt, T, 3 * h, t.dqkv, G(BF_B_QKV), acc, st));
+  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  BF_TRY(p_colsum(s, T, 3 * h, t.dqkv, G(BF_B_QKV), acc, st));
   g = GemmArgs{T, h, 3 * h, t.dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
-  BF_TRY(gemm(dt, kn, L_NT, E_NONE, g, st));
+  BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // a = LN1(x); dx = dx1 + LN1'(da)
-  BF_TRY(layernorm_bwd(dt, T, h, t.dc, x, P(BF_LN1_G), R.ln1, t.dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, x, P(BF_LN1_G), R.ln1, t.dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
   return BF_OK;
 }
 
@@ -348,6 +411,7 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->wlp = cfg->dtype == BF_BF16 ? (bf16_t*)(s->ws + s->Lo.off_wlp) : nullptr;
   s->step = 0;
   s->have_grads = false;
+  s->prof_on = false;
   s->side = nullptr;
   s->ev_grad_ready = s->ev_side_done = s->ev_t0 = s->ev_t1 = nullptr;
   hipStream_t st = (hipStream_t)stream;
@@ -400,6 +464,7 @@ bf_status bf_destroy_stack(bf_stack* s) {
   for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : s->adam_ev) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : s->queue_ev) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : s->prof_ev) if (e) (void)hipEventDestroy(e);
   delete s;
   return BF_OK;
 }
@@ -520,6 +585,8 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
 
   s->trace.clear();
   s->have_grads = false;
+  s->prof_on = timing == 2;
+  s->prof_rec.clear();
   if (apply_optimizer) s->step += 1;
   int live = 0;
   int64_t peak_live = 0;
@@ -575,8 +642,10 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
           BF_HIP_CHECK(hipStreamWaitEvent(as, s->ev_grad_ready, 0));
         }
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam], as));
-        BF_TRY(adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
-                         c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as));
+        BF_TRY(timed(s, BF_K_ADAM, 0.0, (double)n * (s->wlp ? 30.0 : 28.0), as, [&] {
+          return adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
+                           c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as);
+        }));
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam + 1], as));
         ++n_adam;
       }
@@ -635,6 +704,15 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
       }
       report->adam_ms = am;
       report->timed = 1;
+      if (s->prof_on) BF_HIP_CHECK(hipStreamSynchronize(s->side));
+      for (size_t i = 0; i < s->prof_rec.size(); ++i) {
+        BF_HIP_CHECK(hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]));
+        const int k = s->prof_rec[i].cls;
+        report->kernel_ms[k] += ms;
+        report->kernel_launches[k] += 1;
+        report->kernel_flops[k] += s->prof_rec[i].flops;
+        report->kernel_bytes[k] += s->prof_rec[i].bytes;
+      }
     }
   }
   return BF_OK;
