@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-df", action="store_true")
+    ap.add_argument("--no-fuse-wgrad", action="store_true",
+                    help="accumulate weight gradients per micro-batch in BF order too (default: one product per stage)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one pipeline rank's share of the step); "
@@ -101,7 +103,8 @@ def main():
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, ckpt = w
     b16 = dtype == "bf16"
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
-                         ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0)
+                         ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
+                         fuse_wgrad=0 if args.no_fuse_wgrad else 1)
     torch.cuda.set_device(0)
     st = bf.Stack(cfg, device="cuda:0")
     gen = torch.Generator(device="cuda:0")
@@ -153,7 +156,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "N_layers": Lyr, "N_loop": N_loop,
                    "S_hidden": h, "N_heads": a, "S_mlp": f, "S_seq": S_seq, "S_mb": S_mb, "N_mb": N_mb,
-                   "schedule": "BF", "ckpt": ckpt, "tokens_per_step": N_mb * S_mb * S_seq},
+                   "schedule": "BF", "ckpt": ckpt, "fuse_wgrad": not args.no_fuse_wgrad, "tokens_per_step": N_mb * S_mb * S_seq},
         "frac_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
         "paper_eq_tflops": r.flops_paper / sec_bf / 1e12,
         "executed_tflops": r.flops_executed / sec_bf / 1e12,

@@ -68,6 +68,13 @@ typedef struct {
   int32_t kernels;                                 /* bf_kernels */
   int32_t queue_depth;  /* > 0: the host never runs more than this many stage-level ops ahead of
                            the device (App. D.2, bounded kernel queue); 0: unbounded */
+  int32_t fuse_wgrad;   /* 1: in breadth-first order (and without checkpointing) the weight-matrix gradients
+                           of a stage are taken once per stage, as one product over all its micro-batches,
+                           after the stage's last backward ("aggregates the steps by layer", Sec. 4.2): the
+                           fp32 main-grad is written once instead of read-modified-written N_mb times.
+                           The sum over micro-batches is then one long fp32 contraction, so BF and DF
+                           gradients agree to rounding, not bitwise.  0: accumulate per micro-batch. */
+  int32_t reserved_;    /* keeps seed 8-byte aligned; must be 0 */
   uint64_t seed;        /* device-side initialisation: weights ~ N(0, init_std), biases 0, LN gain 1 */
   float init_std;
   float ln_eps;

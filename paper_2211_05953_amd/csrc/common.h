@@ -35,6 +35,11 @@ struct GemmArgs {
   const void* R;      // [M,N] in the activation dtype or null
   void* C2;           // second output of E_BIAS_GELU
   int accumulate;     // E_ACCUM only
+  // Weight-gradient layout only: the contraction runs over n_seg segments of K rows each, segment i
+  // reading A + i * seg_stride_a and B + i * seg_stride_b (elements): one product over all the
+  // micro-batches of a stage.  n_seg <= 1 means a single segment.
+  int n_seg = 1;
+  size_t seg_stride_a = 0, seg_stride_b = 0;
 };
 
 void set_error(const char* fmt, ...);

@@ -13,6 +13,8 @@
 // Wave w of the workgroup owns a (BM / WM) x (BN / WN) sub-tile as MI x NI MFMA tiles of
 // 32 x 32.  Accumulator layout of one MFMA tile: lane l, register r holds
 // row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
+#include <cstdlib>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -24,14 +26,15 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int BK = 64;
 constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
 
-template <int BM_, int BN_, int WM_, int WN_>
+template <int BM_, int BN_, int WM_, int WN_, int PIPE_ = 0>
 struct Tile {
-  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, PIPE = PIPE_;
   static constexpr int NT = WM * WN * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;
   static constexpr int MI = TM / 32, NI = TN / 32;
@@ -106,17 +109,35 @@ template <typename TL, bool AK, bool BKC, int EPI, typename TO>
 __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ B, TO* __restrict__ C,
                                                            const float* __restrict__ bias, const TO* __restrict__ R,
-                                                           TO* __restrict__ C2, int accumulate, int tiles_m) {
+                                                           TO* __restrict__ C2, int accumulate, int tiles_m, int remap,
+                                                           int n_seg, size_t seg_a, size_t seg_b) {
   constexpr int BM = TL::BM, BN = TL::BN, NT = TL::NT, MI = TL::MI, NI = TL::NI;
   constexpr int A_ST = stage_elems<AK, BM>(), B_ST = stage_elems<BKC, BN>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  bf16_t* As[2] = {smem, smem + A_ST + B_ST};
-  bf16_t* Bs[2] = {smem + A_ST, smem + 2 * A_ST + B_ST};
+  constexpr int STAGE = A_ST + B_ST;  // stage s: A tile at smem + s * STAGE, B tile right after it
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wm = w % TL::WM, wn = w / TL::WM;
-  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  // Workgroups go to the 8 XCDs round-robin and each XCD has its own L2: give XCD x a contiguous
+  // range of the tile order, and walk that order in groups of 8 row-tiles so that the ~32
+  // workgroups an XCD runs at a time form an 8 x 4 block sharing A row-panels and B column-panels.
+  int lin = blockIdx.x;
+  if (remap) {
+    const int per_xcd = gridDim.x >> 3;
+    lin = (lin & 7) * per_xcd + (lin >> 3);
+  }
+  const int tiles_n = gridDim.x / tiles_m;
+  const int in_group = 8 * tiles_n;
+  int bm, bn;
+  if (remap && tiles_m % 8 == 0) {
+    const int gi = lin / in_group, rem = lin % in_group;
+    bm = gi * 8 + (rem & 7);
+    bn = rem >> 3;
+  } else {
+    bm = lin % tiles_m;
+    bn = lin / tiles_m;
+  }
   const int m0 = bm * BM, n0 = bn * BN;
   const size_t lda = AK ? (size_t)K : (size_t)M;   // A stored [M,K] or [K,M]
   const size_t ldb = BKC ? (size_t)K : (size_t)N;  // B stored [N,K] or [K,N]
@@ -131,54 +152,167 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 
   Stager<AK, BM, NT> sa;
   Stager<BKC, BN, NT> sb;
-  sa.load(A, lda, m0, 0, tid);
-  sb.load(B, ldb, n0, 0, tid);
-  sa.store(As[0], tid);
-  sb.store(Bs[0], tid);
-  __syncthreads();
-
-  const int nk = K / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      sa.load(A, lda, m0, (kt + 1) * BK, tid);
-      sb.load(B, ldb, n0, (kt + 1) * BK, tid);
+  const int nk_seg = K / BK, nk = nk_seg * n_seg;
+  // k-tile kt lives in segment kt / nk_seg (one segment unless this is a multi-micro-batch weight gradient)
+  auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
+  auto seg_b_of = [&](int kt) { return B + (size_t)(kt / nk_seg) * seg_b; };
+  auto k0_of = [&](int kt) { return (kt % nk_seg) * BK; };
+  if (TL::PIPE == 0) {
+    sa.load(A, lda, m0, 0, tid);
+    sb.load(B, ldb, n0, 0, tid);
+    sa.store(smem, tid);
+    sb.store(smem + A_ST, tid);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) {
+        sa.load(seg_a_of(kt + 1), lda, m0, k0_of(kt + 1), tid);
+        sb.load(seg_b_of(kt + 1), ldb, n0, k0_of(kt + 1), tid);
+      }
+      const bf16_t* as = smem + cur * STAGE;
+      const bf16_t* bs = as + A_ST;
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8 af[MI], bfr[NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+      if (kt + 1 < nk) {
+        sa.store(smem + (cur ^ 1) * STAGE, tid);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+      }
+      __syncthreads();
     }
-    const bf16_t* as = As[cur];
-    const bf16_t* bs = Bs[cur];
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MI], bfr[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      sa.store(As[cur ^ 1], tid);
-      sb.store(Bs[cur ^ 1], tid);
+  } else {
+    // Tile kt+1 sits in registers when iteration kt starts (loaded one iteration earlier): it goes to
+    // the idle LDS stage first, the loads of tile kt+2 follow, and the fragments of k-step kk+1
+    // are requested before the MFMAs of k-step kk.
+    sa.load(A, lda, m0, 0, tid);
+    sb.load(B, ldb, n0, 0, tid);
+    sa.store(smem, tid);
+    sb.store(smem + A_ST, tid);
+    if (nk > 1) {
+      sa.load(seg_a_of(1), lda, m0, k0_of(1), tid);
+      sb.load(seg_b_of(1), ldb, n0, k0_of(1), tid);
     }
     __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      const bf16_t* as = smem + cur * STAGE;
+      const bf16_t* bs = as + A_ST;
+      bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[0][i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, 0, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[0][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, 0, lane);
+      if (kt + 1 < nk) {
+        sa.store(smem + (cur ^ 1) * STAGE, tid);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+      }
+      if (kt + 2 < nk) {
+        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2), tid);
+        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2), tid);
+      }
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const int cb = kk & 1, nb = cb ^ 1;
+        if (kk + 1 < BK / 16) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i) af[nb][i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk + 1, lane);
+#pragma unroll
+          for (int j = 0; j < NI; ++j) bfr[nb][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk + 1, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
+      }
+      __syncthreads();
+    }
   }
 
+  if constexpr (EPI == E_ACCUM) {
+    // fp32 main-grad: a lane's 32 columns are 128 contiguous bytes per row, stored directly
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
+      for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const size_t row = m0 + wm * TL::TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const size_t col = n0 + wn * TL::TN + j * 32 + (lane & 31);
-        epilogue_store<EPI, TO>(acc[i][j][r], row, col, (size_t)N, C, bias, R, C2, accumulate);
+        for (int r = 0; r < 16; ++r) {
+          const size_t row = m0 + wm * TL::TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          const size_t col = n0 + wn * TL::TN + j * 32 + (lane & 31);
+          epilogue_store<EPI, TO>(acc[i][j][r], row, col, (size_t)N, C, bias, R, C2, accumulate);
+        }
+  } else {
+    // bf16 outputs: the fp32 accumulators pass through LDS, 64 tile rows at a time, so that every
+    // thread finishes 8 adjacent columns (bias, residual, GeLU in fp32, one rounding) and the
+    // global accesses of C, C2 and R are 16 bytes per lane over whole 512-byte row segments.
+    constexpr int PR = 64, LDC = BN + 4;
+    float* cs = reinterpret_cast<float*>(smem_raw);
+    static_assert((size_t)PR * LDC * 4 <= 2 * (size_t)STAGE * sizeof(bf16_t), "epilogue staging does not fit");
+#pragma unroll
+    for (int p = 0; p < BM / PR; ++p) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int r0 = wm * TL::TM + i * 32;
+        if (r0 / PR != p) continue;
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            cs[(r0 % PR + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + wn * TL::TN + j * 32 + (lane & 31)] = acc[i][j][r];
       }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PR * BN / 8 / NT; ++q) {
+        const int c = tid + q * NT, lr = c / (BN / 8), lc = (c % (BN / 8)) * 8;
+        const size_t row = m0 + p * PR + lr, col = n0 + lc, idx = row * (size_t)N + col;
+        float v[8];
+        *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(cs + lr * LDC + lc);
+        *reinterpret_cast<f32x4*>(v + 4) = *reinterpret_cast<const f32x4*>(cs + lr * LDC + lc + 4);
+        if constexpr (EPI == E_BIAS || EPI == E_BIAS_RES || EPI == E_BIAS_GELU) {
+          const f32x4 b0 = *reinterpret_cast<const f32x4*>(bias + col), b1 = *reinterpret_cast<const f32x4*>(bias + col + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { v[e] += b0[e]; v[4 + e] += b1[e]; }
+        }
+        bf16x8 o;
+        if constexpr (EPI == E_BIAS_RES) {
+          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + idx);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (__bf16)(v[e] + (float)rr[e]);
+        } else if constexpr (EPI == E_GELU_BWD) {
+          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + idx);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (__bf16)(v[e] * gelu_grad_f((float)rr[e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+        }
+        *reinterpret_cast<bf16x8*>(C + idx) = o;
+        if constexpr (EPI == E_BIAS_GELU) {
+          bf16x8 g2;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g2[e] = (__bf16)gelu_f((float)o[e]);
+          *reinterpret_cast<bf16x8*>(C2 + idx) = g2;
+        }
+      }
+      __syncthreads();
+    }
+  }
 }
 
-typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave
-typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
+int g_variant = 0;  // experiment switch (BF_GEMM_VARIANT): low bits pick the big tile, bit 4 turns the XCD remap off
+typedef Tile<256, 256, 2, 4, 1> TileBig;  // 8 waves, 128 x 64 per wave, pipelined
+typedef Tile<256, 256, 2, 2, 1> TileBig4;   // 4 waves, 128 x 128 per wave, pipelined
+typedef Tile<256, 256, 2, 4, 0> TileBigP;   // 8 waves, 128 x 64 per wave, plain loop
+typedef Tile<128, 128, 2, 2, 1> TileSmall;  // 4 waves, 64 x 64 per wave
 
 template <typename TL, bool AK, bool BKC>
 constexpr size_t lds_bytes() { return 2 * (size_t)(stage_elems<AK, TL::BM>() + stage_elems<BKC, TL::BN>()) * sizeof(bf16_t); }
@@ -194,8 +328,10 @@ bf_status launch(const GemmArgs& a, hipStream_t st) {
     attr_set = true;
   }
   const int tiles_m = a.M / TL::BM, tiles_n = a.N / TL::BN;
+  const int remap = ((tiles_m * tiles_n) % 8 == 0 && !(g_variant & 16)) ? 1 : 0;
   kern<<<tiles_m * tiles_n, TL::NT, lds, st>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.B, (TO*)a.C, a.bias,
-                                                (const TO*)a.R, (TO*)a.C2, a.accumulate, tiles_m);
+                                                (const TO*)a.R, (TO*)a.C2, a.accumulate, tiles_m, remap, a.n_seg > 1 ? a.n_seg : 1,
+                                                a.seg_stride_a, a.seg_stride_b);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("gemm_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
@@ -238,9 +374,19 @@ bool gemm_mfma_supported(int layout, int epi, int M, int N, int K) {
 
 bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   if (!gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) { set_error("gemm_mfma: shape not supported"); return BF_EINVAL; }
-  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2;
+  if (a.n_seg > 1 && (layout != L_TN || ((a.seg_stride_a | a.seg_stride_b) & 7))) {
+    set_error("gemm_mfma: segments go with the weight-gradient layout and 16-byte aligned strides");
+    return BF_EINVAL;
+  }
+  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
-  if (big_fits(a.M, a.N)) return by_layout<TileBig>(layout, epi, a, st);
+  static bool read_env = false;
+  if (!read_env) { const char* e = getenv("BF_GEMM_VARIANT"); g_variant = e ? atoi(e) : 0; read_env = true; }
+  if (big_fits(a.M, a.N)) {
+    if ((g_variant & 15) == 1) return by_layout<TileBig4>(layout, epi, a, st);
+    if ((g_variant & 15) == 3) return by_layout<TileBigP>(layout, epi, a, st);
+    return by_layout<TileBig>(layout, epi, a, st);
+  }
   return by_layout<TileSmall>(layout, epi, a, st);
 }
 

@@ -106,6 +106,19 @@ bf_status gemm_check(int layout, int epi, const GemmArgs& a) {
 bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStream_t st) {
   bf_status s = gemm_check(layout, epi, a);
   if (s != BF_OK) return s;
+  if (a.n_seg > 1) {
+    if (layout != L_TN) { set_error("gemm: segments go with the weight-gradient layout"); return BF_EINVAL; }
+    const size_t es = dtype == BF_BF16 ? 2 : 4;
+    for (int i = 0; i < a.n_seg; ++i) {
+      GemmArgs b = a;
+      b.n_seg = 1;
+      b.A = (const char*)a.A + (size_t)i * a.seg_stride_a * es;
+      b.B = (const char*)a.B + (size_t)i * a.seg_stride_b * es;
+      b.accumulate = i > 0 ? 1 : a.accumulate;
+      if ((s = gemm_plain(dtype, layout, epi, b, st)) != BF_OK) return s;
+    }
+    return BF_OK;
+  }
   if (dtype == BF_BF16) return dispatch<bf16_t>(layout, epi, a, st);
   if (dtype == BF_FP32) return dispatch<float>(layout, epi, a, st);
   set_error("gemm: unknown dtype %d", dtype);
@@ -113,7 +126,7 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 }
 
 bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st) {
-  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2;
+  const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
     bf_status s = gemm_check(layout, epi, a);
     if (s != BF_OK) return s;

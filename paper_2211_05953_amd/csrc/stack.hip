@@ -66,6 +66,7 @@ bool valid_config(const bf_config* c) {
   if (c->kernels != BF_KERNELS_AUTO && c->kernels != BF_KERNELS_PLAIN) { set_error("config: unknown kernels"); return false; }
   if (c->causal != 0 && c->causal != 1) { set_error("config: causal must be 0 or 1"); return false; }
   if (c->queue_depth < 0) { set_error("config: queue_depth < 0"); return false; }
+  if (c->fuse_wgrad != 0 && c->fuse_wgrad != 1) { set_error("config: fuse_wgrad must be 0 or 1"); return false; }
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
   if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
   return true;
@@ -95,7 +96,9 @@ struct WsLayout {
   size_t n_full_records;
   size_t off_ckpt;         // LAYER: L * N_mb_max [T, h] tensors (outputs of each layer)
   size_t off_tmp;          // backward temporaries
-  size_t off_bhand;        // N_mb_max [T, h]
+  size_t off_grec;         // fused weight gradient: L * N_mb_max records {dy, du, dx1, dqkv}
+  size_t grec_bytes;
+  size_t off_bhand;        // 2 x N_mb_max [T, h] (two sets, alternating by stage)
   size_t off_scratch_out;  // [T, h] x 2: discarded outputs / ping-pong
   size_t total;
 };
@@ -125,6 +128,10 @@ TmpSizes tmp_sizes(const bf_config& c) {
   return t;
 }
 
+// The weight gradients of a stage can be taken as one product over all its micro-batches only
+// when every micro-batch's activations are still stored (no checkpointing).
+bool fuse_wgrad_possible(const bf_config& c) { return c.fuse_wgrad != 0 && c.ckpt_mode == BF_CKPT_NONE; }
+
 void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
   const size_t T = (size_t)c.S_mb_max * c.S_seq;
@@ -151,7 +158,13 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
     off += slots * Lo->y_bytes;
   }
   Lo->off_tmp = off; off += tmp_sizes(c).total;
-  Lo->off_bhand = off; off += (size_t)c.N_mb_max * Lo->y_bytes;
+  {
+    TmpSizes t = tmp_sizes(c);
+    Lo->grec_bytes = t.ping + t.du + t.dx1 + t.dqkv;
+    Lo->off_grec = off;
+    if (fuse_wgrad_possible(c)) off += slots * Lo->grec_bytes;
+  }
+  Lo->off_bhand = off; off += 2 * (size_t)c.N_mb_max * Lo->y_bytes;
   Lo->off_scratch_out = off; off += 2 * Lo->y_bytes;
   Lo->total = off;
 }
@@ -223,6 +236,17 @@ Record record_for(bf_stack* s, int layer, int mb) {
 
 struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float* delta; };
 
+// Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
+struct GradRec { char *dy, *du, *dx1, *dqkv; };
+
+GradRec grad_rec(bf_stack* s, int layer, int mb) {
+  TmpSizes t = tmp_sizes(s->cfg);
+  char* p = s->ws + s->Lo.off_grec + ((size_t)layer * s->cfg.N_mb_max + mb) * s->Lo.grec_bytes;
+  GradRec g;
+  g.dy = p; p += t.ping; g.du = p; p += t.du; g.dx1 = p; p += t.dx1; g.dqkv = p;
+  return g;
+}
+
 Tmp tmp_of(bf_stack* s) {
   TmpSizes t = tmp_sizes(s->cfg);
   Tmp T;
@@ -262,7 +286,9 @@ bf_status p_gemm(bf_stack* s, int layout, int epi, const GemmArgs& g, hipStream_
   const int cls = layout == L_NN ? BF_K_GEMM_FWD : layout == L_NT ? BF_K_GEMM_DGRAD : BF_K_GEMM_WGRAD;
   const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
   double bytes = es * ((double)g.M * g.K + (double)g.K * g.N) + (layout == L_TN ? (g.accumulate ? 8.0 : 4.0) : es) * g.M * g.N;
-  return timed(s, cls, 2.0 * g.M * g.N * g.K, bytes, st, [&] { return gemm(s->cfg.dtype, s->cfg.kernels, layout, epi, g, st); });
+  const double nseg = g.n_seg > 1 ? g.n_seg : 1;
+  if (nseg > 1) bytes = es * nseg * ((double)g.M * g.K + (double)g.K * g.N) + 4.0 * g.M * g.N;
+  return timed(s, cls, 2.0 * g.M * g.N * g.K * nseg, bytes, st, [&] { return gemm(s->cfg.dtype, s->cfg.kernels, layout, epi, g, st); });
 }
 bf_status p_ln_fwd(bf_stack* s, int T, int h, const void* x, const float* g, const float* b, float eps, void* y, float* stats,
                    hipStream_t st) {
@@ -322,44 +348,85 @@ bf_status layer_forward(bf_stack* s, int layer, int S_mb, const void* x, const R
 
 // Backward of one layer.  dy: gradient w.r.t. the layer output; dx: gradient w.r.t. its input.
 // acc: 0 for the first micro-batch of the step (main-grads are overwritten), 1 afterwards.
+// keep: null, or where du / dx1 / dqkv are kept for a later weight-gradient product over all the
+// micro-batches of the stage (then no weight-matrix gradient is taken here).
 bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const Record& R, const void* dy, void* dx,
-                         int acc, hipStream_t st) {
+                         int acc, const GradRec* keep, hipStream_t st) {
   const bf_config& c = s->cfg;
-  const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp, dt = c.dtype, kn = c.kernels;
+  const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
   Tmp t = tmp_of(s);
+  char* du = keep ? keep->du : t.du;
+  char* dx1 = keep ? keep->dx1 : t.dx1;
+  char* dqkv = keep ? keep->dqkv : t.dqkv;
   auto P = [&](int tid) { return param_ptr(s, s->w32, layer, tid); };
   auto G = [&](int tid) { return param_ptr(s, s->g32, layer, tid); };
   GemmArgs g{};
   // y = x1 + gelu(u) W_fc2 + b_fc2
-  g = GemmArgs{f, h, T, R.g, dy, G(BF_W_FC2), nullptr, nullptr, nullptr, acc};
-  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  if (!keep) {
+    g = GemmArgs{f, h, T, R.g, dy, G(BF_W_FC2), nullptr, nullptr, nullptr, acc};
+    BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  }
   BF_TRY(p_colsum(s, T, h, dy, G(BF_B_FC2), acc, st));
-  g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), t.du, nullptr, R.u, nullptr, 0};
+  g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), du, nullptr, R.u, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_GELU_BWD, g, st));
   // u = c W_fc1 + b_fc1
-  g = GemmArgs{h, f, T, R.c, t.du, G(BF_W_FC1), nullptr, nullptr, nullptr, acc};
-  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
-  BF_TRY(p_colsum(s, T, f, t.du, G(BF_B_FC1), acc, st));
-  g = GemmArgs{T, h, f, t.du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
+  if (!keep) {
+    g = GemmArgs{h, f, T, R.c, du, G(BF_W_FC1), nullptr, nullptr, nullptr, acc};
+    BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  }
+  BF_TRY(p_colsum(s, T, f, du, G(BF_B_FC1), acc, st));
+  g = GemmArgs{T, h, f, du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // c = LN2(x1); dx1 = dy + LN2'(dc)
-  BF_TRY(p_ln_bwd(s, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, t.dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
   // x1 = x + ctx W_o + b_o
-  g = GemmArgs{h, h, T, R.ctx, t.dx1, G(BF_W_O), nullptr, nullptr, nullptr, acc};
-  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
-  BF_TRY(p_colsum(s, T, h, t.dx1, G(BF_B_O), acc, st));
-  g = GemmArgs{T, h, h, t.dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
+  if (!keep) {
+    g = GemmArgs{h, h, T, R.ctx, dx1, G(BF_W_O), nullptr, nullptr, nullptr, acc};
+    BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  }
+  BF_TRY(p_colsum(s, T, h, dx1, G(BF_B_O), acc, st));
+  g = GemmArgs{T, h, h, dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
-  BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, t.dqkv,
-                       t.delta, st));
+  BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, dqkv, t.delta, st));
   // qkv = a W_qkv + b_qkv
-  g = GemmArgs{h, 3 * h, T, R.a, t.dqkv, G(BF_W_QKV), nullptr, nullptr, nullptr, acc};
-  BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
-  BF_TRY(p_colsum(s, T, 3 * h, t.dqkv, G(BF_B_QKV), acc, st));
-  g = GemmArgs{T, h, 3 * h, t.dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
+  if (!keep) {
+    g = GemmArgs{h, 3 * h, T, R.a, dqkv, G(BF_W_QKV), nullptr, nullptr, nullptr, acc};
+    BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+  }
+  BF_TRY(p_colsum(s, T, 3 * h, dqkv, G(BF_B_QKV), acc, st));
+  g = GemmArgs{T, h, 3 * h, dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // a = LN1(x); dx = dx1 + LN1'(da)
-  BF_TRY(p_ln_bwd(s, T, h, t.dc, x, P(BF_LN1_G), R.ln1, t.dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, x, P(BF_LN1_G), R.ln1, dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
+  return BF_OK;
+}
+
+// The four weight-matrix gradients of one layer as products over all N_mb micro-batches at once
+// (breadth-first only: every micro-batch of the stage has been through its backward, Sec. 4.2).
+// G = sum_m X_m^T dY_m is one long contraction, written once: no read-modify-write of the fp32
+// main-grad per micro-batch.  dy0 / dy_stride: the layer's incoming gradients, micro-batch 0 and
+// the distance (elements) between micro-batches.
+bf_status layer_wgrad_fused(bf_stack* s, int layer, int S_mb, int N_mb, const void* dy0, size_t dy_stride, hipStream_t st) {
+  const bf_config& c = s->cfg;
+  const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
+  const size_t es = 2;  // bf16 or fp32 handled through element strides below
+  (void)es;
+  const size_t esz = c.dtype == BF_BF16 ? 2 : 4;
+  const Record R0 = record_for(s, layer, 0);
+  const GradRec K0 = grad_rec(s, layer, 0);
+  const size_t rec_stride = (s->Lo.rec_bytes + s->Lo.y_bytes) / esz, grec_stride = s->Lo.grec_bytes / esz;
+  auto G = [&](int tid) { return param_ptr(s, s->g32, layer, tid); };
+  auto run = [&](int M, int N, const void* A, const void* B, size_t sb, float* out) {
+    GemmArgs g{M, N, T, A, B, out, nullptr, nullptr, nullptr, 0};
+    g.n_seg = N_mb;
+    g.seg_stride_a = rec_stride;
+    g.seg_stride_b = sb;
+    return p_gemm(s, L_TN, E_ACCUM, g, st);
+  };
+  BF_TRY(run(f, h, R0.g, dy0, dy_stride, G(BF_W_FC2)));
+  BF_TRY(run(h, f, R0.c, K0.du, grec_stride, G(BF_W_FC1)));
+  BF_TRY(run(h, h, R0.ctx, K0.dx1, grec_stride, G(BF_W_O)));
+  BF_TRY(run(h, 3 * h, R0.a, K0.dqkv, grec_stride, G(BF_W_QKV)));
   return BF_OK;
 }
 
@@ -576,8 +643,11 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
   const int per_stage = c.N_layers / N_loop;
   const size_t mb_bytes = (size_t)S_mb * c.S_seq * c.S_hidden * es;
   Tmp tmp = tmp_of(s);
-  char* bhand = s->ws + s->Lo.off_bhand;
+  // gradient hand-off between stages: stage j reads set j & 1 and writes set (j - 1) & 1, so the
+  // gradients a stage received stay intact until its fused weight-gradient products have run
+  auto bhand = [&](int stage, int m) { return s->ws + s->Lo.off_bhand + ((size_t)(stage & 1) * c.N_mb_max + m) * s->Lo.y_bytes; };
   char* scratch_out = s->ws + s->Lo.off_scratch_out;
+  const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c);
 
   std::vector<SchedOp> ops;
   std::string why;
@@ -615,16 +685,30 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
         const void* xin = input_of(l, m);
         if (c.ckpt_mode == BF_CKPT_LAYER) BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, st));
         // gradient in: caller's dy for the last layer, the hand-off buffer at a stage top, else the ping-pong
+        // (with the fused weight gradient every layer's incoming gradient is kept per micro-batch instead)
         const void* din;
         if (l == c.N_layers - 1) din = (const char*)dy + (size_t)m * mb_bytes;
-        else if (l == l1 - 1) din = bhand + (size_t)m * s->Lo.y_bytes;
-        else din = tmp.ping[(l + 1) & 1];
+        else if (l == l1 - 1) din = bhand(op.stage, m);
+        else din = fuse ? grad_rec(s, l, m).dy : tmp.ping[(l + 1) & 1];
         void* dout;
         if (l == 0) dout = dx ? (char*)dx + (size_t)m * mb_bytes : scratch_out + s->Lo.y_bytes;
-        else if (l == l0) dout = bhand + (size_t)m * s->Lo.y_bytes;
-        else dout = tmp.ping[l & 1];
-        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, st));
+        else if (l == l0) dout = bhand(op.stage - 1, m);
+        else dout = fuse ? grad_rec(s, l - 1, m).dy : tmp.ping[l & 1];
+        GradRec keep{};
+        if (fuse) keep = grad_rec(s, l, m);
+        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, st));
         --live;
+      }
+      if (fuse && m == N_mb - 1) {
+        // every micro-batch of the stage is through: one weight-gradient product per matrix
+        for (int l = l1 - 1; l >= l0; --l) {
+          const void* dy0;
+          size_t stride;
+          if (l == c.N_layers - 1) { dy0 = dy; stride = mb_bytes / es; }
+          else if (l == l1 - 1) { dy0 = bhand(op.stage, 0); stride = s->Lo.y_bytes / es; }
+          else { dy0 = grad_rec(s, l, 0).dy; stride = s->Lo.grec_bytes / es; }
+          BF_TRY(layer_wgrad_fused(s, l, S_mb, N_mb, dy0, stride, st));
+        }
       }
     }
     peak_live = live > peak_live ? live : peak_live;

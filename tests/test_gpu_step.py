@@ -91,6 +91,34 @@ def test_step_matches_oracle_in_both_orders(mode, dtype, ckpt, kernels, Lyr, N_l
         assert g_bf["report"].flops_paper == float(F.c_gpu(N_mb, S_mb, Lyr, h, S_seq))
 
 
+@pytest.mark.parametrize("mode,dtype,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", [
+    ("fp32", bf.BF_FP32, 4, 2, 256, 4, 1024, 128, 1, 4),
+    ("fp32", bf.BF_FP32, 3, 1, 72, 3, 200, 50, 2, 3),
+    ("bf16", bf.BF_BF16, 4, 2, 256, 2, 1024, 256, 1, 4),
+    ("bf16", bf.BF_BF16, 4, 4, 512, 4, 2048, 128, 2, 3),
+])
+def test_fused_weight_gradient_in_breadth_first_order(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+    """fuse_wgrad = 1: one weight-gradient product per stage over all micro-batches (BF only).
+    Same sum, one long contraction: equal to the oracle within the tolerance, equal to the
+    per-micro-batch accumulation up to fp32 rounding; DF ignores the flag."""
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(13, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(13, N_mb, S_mb, S_seq, h, bf16=b16)
+    fused = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1)
+    plain = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=0)
+    ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a)
+    g_f = _run_gpu(fused, params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    g_p = _run_gpu(plain, params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    g_df = _run_gpu(fused, params, x, dy, bf.BF_SCHED_DF, N_loop, N_mb, S_mb)
+    _compare(g_f, ref, TOL[mode], Lyr)
+    assert np.array_equal(g_f["y"], g_p["y"]) and np.array_equal(g_f["dx"], g_p["dx"])
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            assert rel_err(g_f["grads"][l][name], g_p["grads"][l][name]) <= 2e-6, (l, name)
+            assert np.array_equal(g_df["grads"][l][name], g_p["grads"][l][name]), (l, name)
+    assert g_f["trace"] == g_p["trace"]
+
+
 @pytest.mark.parametrize("mode,dtype", [("fp32", bf.BF_FP32), ("bf16", bf.BF_BF16)])
 @pytest.mark.parametrize("schedule", [bf.BF_SCHED_BF, bf.BF_SCHED_DF])
 def test_two_optimizer_steps(mode, dtype, schedule):
