@@ -120,7 +120,7 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], bf16_t* 
 
 // ------------------------------------------------------------------------------ forward
 template <int D>
-__global__ __launch_bounds__(NTHR) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+__global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                         float* __restrict__ lse, int S_seq, int N_heads, int causal,
                                                         float scale) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BLK * D];
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(NTHR) void attn_delta_kernel(const bf16_t* __restri
 
 // ------------------------------------------------------------------- backward, dQ pass
 template <int D>
-__global__ __launch_bounds__(NTHR) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+__global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
                                                            float scale) {

@@ -141,22 +141,26 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_kernel(const T* __restr
 }
 
 // ---------------------------------------------------- column reductions (fixed order)
-// Workgroup = 32 column groups x 8 row groups; thread (cx, ry) owns VEC adjacent columns
-// and rows ry, ry+8, ...  Partial sums meet in LDS and are added in ascending ry.
+// Workgroup = CG column groups x RG row groups (CG * RG = 256); thread (cx, ry) owns VEC adjacent
+// columns and rows ry, ry + RG, ...  Partial sums meet in LDS and are added in ascending ry.
+// A workgroup covers CG * VEC columns: narrow enough that the few thousand columns of a bias
+// or LayerNorm gradient still spread over all compute units, wide enough (>= 128 bytes per
+// row) to keep the row reads in whole cache lines.
 // MODE 0: out[c] = sum_t dY[t,c]
 // MODE 1: dg[c] = sum_t dY[t,c] * xhat[t,c],  db[c] = sum_t dY[t,c]
-template <typename T, int VEC, int MODE>
+template <typename T, int VEC, int MODE, int CG>
 __global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ dY, const T* __restrict__ x,
                                                          const float* __restrict__ stats, float* __restrict__ out0,
                                                          float* __restrict__ out1, int T_rows, int N, int accumulate) {
-  __shared__ float part[2][8][32 * VEC];
-  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
-  const int c0 = (blockIdx.x * 32 + cx) * VEC;
+  constexpr int RG = 256 / CG;
+  __shared__ float part[MODE == 1 ? 2 : 1][RG][CG * VEC + 1];
+  const int cx = threadIdx.x % CG, ry = threadIdx.x / CG;
+  const int c0 = (blockIdx.x * CG + cx) * VEC;
   float a0[VEC], a1[VEC];
 #pragma unroll
   for (int j = 0; j < VEC; ++j) a0[j] = a1[j] = 0.f;
   if (c0 < N) {
-    for (int t = ry; t < T_rows; t += 8) {
+    for (int t = ry; t < T_rows; t += RG) {
       float d[VEC];
       load_vec<T, VEC>(dY + (size_t)t * N + c0, d);
       if (MODE == 1) {
@@ -177,21 +181,29 @@ __global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ d
 #pragma unroll
   for (int j = 0; j < VEC; ++j) {
     part[0][ry][cx * VEC + j] = a0[j];
-    if (MODE == 1) part[1][ry][cx * VEC + j] = a1[j];
+    if (MODE == 1) part[MODE == 1 ? 1 : 0][ry][cx * VEC + j] = a1[j];
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < 32 * VEC; c += 256) {
-    const int col = blockIdx.x * 32 * VEC + c;
+  for (int c = threadIdx.x; c < CG * VEC; c += 256) {
+    const int col = blockIdx.x * CG * VEC + c;
     if (col >= N) continue;
     float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
+#pragma unroll 8
+    for (int r = 0; r < RG; ++r) {
       s0 += part[0][r][c];
-      if (MODE == 1) s1 += part[1][r][c];
+      if (MODE == 1) s1 += part[MODE == 1 ? 1 : 0][r][c];
     }
     out0[col] = accumulate ? out0[col] + s0 : s0;
     if (MODE == 1) out1[col] = accumulate ? out1[col] + s1 : s1;
   }
+}
+
+template <typename T, int VEC, int MODE>
+void launch_col_reduce(const void* dY, const void* x, const float* stats, float* out0, float* out1, int T_rows, int N,
+                       int accumulate, hipStream_t st) {
+  constexpr int CG = 8;  // 8 x VEC columns per workgroup, 32 row groups
+  const int blocks = (N + CG * VEC - 1) / (CG * VEC);
+  col_reduce_kernel<T, VEC, MODE, CG><<<blocks, 256, 0, st>>>((const T*)dY, (const T*)x, stats, out0, out1, T_rows, N, accumulate);
 }
 
 // ------------------------------------------------------------------------- fused Adam
@@ -295,8 +307,7 @@ template <typename T, int VEC>
 static void launch_ln_bwd(int T_rows, int h, const void* dy, const void* x, const float* g, const float* stats,
                           const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st) {
   ln_bwd_dx_kernel<T, VEC><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
-  const int blocks = (h + 32 * VEC - 1) / (32 * VEC);
-  col_reduce_kernel<T, VEC, 1><<<blocks, 256, 0, st>>>((const T*)dy, (const T*)x, stats, dg, db, T_rows, h, accumulate);
+  launch_col_reduce<T, VEC, 1>(dy, x, stats, dg, db, T_rows, h, accumulate, st);
 }
 
 bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g, const float* stats,
@@ -317,15 +328,11 @@ bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, 
 bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, hipStream_t st) {
   if (T < 1 || N < 1 || !dY || !out) { set_error("colsum: bad argument"); return BF_EINVAL; }
   if (dtype == BF_BF16) {
-    if (aligned16(dY) && N % 8 == 0)
-      col_reduce_kernel<bf16_t, 8, 0><<<(N + 255) / 256, 256, 0, st>>>((const bf16_t*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
-    else
-      col_reduce_kernel<bf16_t, 1, 0><<<(N + 31) / 32, 256, 0, st>>>((const bf16_t*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+    if (aligned16(dY) && N % 8 == 0) launch_col_reduce<bf16_t, 8, 0>(dY, nullptr, nullptr, out, nullptr, T, N, accumulate, st);
+    else launch_col_reduce<bf16_t, 1, 0>(dY, nullptr, nullptr, out, nullptr, T, N, accumulate, st);
   } else {
-    if (aligned16(dY) && N % 4 == 0)
-      col_reduce_kernel<float, 4, 0><<<(N + 127) / 128, 256, 0, st>>>((const float*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
-    else
-      col_reduce_kernel<float, 1, 0><<<(N + 31) / 32, 256, 0, st>>>((const float*)dY, nullptr, nullptr, out, nullptr, T, N, accumulate);
+    if (aligned16(dY) && N % 4 == 0) launch_col_reduce<float, 4, 0>(dY, nullptr, nullptr, out, nullptr, T, N, accumulate, st);
+    else launch_col_reduce<float, 1, 0>(dY, nullptr, nullptr, out, nullptr, T, N, accumulate, st);
   }
   BF_LAUNCH_CHECK();
   return BF_OK;

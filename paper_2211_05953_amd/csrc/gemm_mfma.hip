@@ -14,6 +14,7 @@
 // 32 x 32.  Accumulator layout of one MFMA tile: lane l, register r holds
 // row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 #include "epilogue.h"
@@ -157,7 +158,92 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
   auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
   auto seg_b_of = [&](int kt) { return B + (size_t)(kt / nk_seg) * seg_b; };
   auto k0_of = [&](int kt) { return (kt % nk_seg) * BK; };
-  if (TL::PIPE == 0) {
+  if constexpr (TL::PIPE == 2) {
+    // One barrier per k-tile, placed between k-steps 2 and 3.  By then every wave holds its
+    // k-step-3 fragments of the current stage in registers and has written tile kt+1 into the other
+    // stage, so after the barrier k-step 3's MFMAs run while the k-step-0 fragments of the NEXT
+    // stage are fetched: no LDS latency is exposed behind the barrier.  Within a k-step the
+    // scheduler is told to alternate one MFMA with one LDS/global access.
+    constexpr int NREAD = (AK ? MI : 2 * MI) + (BKC ? NI : 2 * NI);  // LDS reads of one k-step
+    constexpr int NMMA = MI * NI;
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto ldf = [&](int buf, const bf16_t* as, const bf16_t* bs, int kk) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[buf][i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[buf][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk, lane);
+    };
+    auto mma = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // mask: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 global read
+    auto interleave = [&](auto extra_mask, auto n_extra) {
+#pragma unroll
+      for (int i = 0; i < NMMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMMA - 1) / NMMA, 0);
+        if (decltype(n_extra)::value > 0 && i < decltype(n_extra)::value)
+          __builtin_amdgcn_sched_group_barrier(decltype(extra_mask)::value, 1, 0);
+      }
+    };
+    constexpr int NCH = Stager<AK, BM, NT>::CHUNKS + Stager<BKC, BN, NT>::CHUNKS;
+    typedef std::integral_constant<int, 0x200> MW;
+    typedef std::integral_constant<int, 0x020> MG;
+    typedef std::integral_constant<int, NCH> NC;
+    typedef std::integral_constant<int, 0> N0;
+
+    sa.load(A, lda, m0, 0, tid);
+    sb.load(B, ldb, n0, 0, tid);
+    sa.store(smem, tid);
+    sb.store(smem + A_ST, tid);
+    if (nk > 1) {
+      sa.load(seg_a_of(1), lda, m0, k0_of(1), tid);
+      sb.load(seg_b_of(1), ldb, n0, k0_of(1), tid);
+    }
+    __syncthreads();
+    ldf(0, smem, smem + A_ST, 0);
+    auto iter = [&](int kt, auto do_store, auto do_load) {
+      const int cur = kt & 1;
+      const bf16_t* as = smem + cur * STAGE;
+      const bf16_t* bs = as + A_ST;
+      const bf16_t* an = smem + (cur ^ 1) * STAGE;
+      const bf16_t* bn2 = an + A_ST;
+      // k-step 0: tile kt+1 (in registers since the previous iteration) goes to the other stage
+      ldf(1, as, bs, 1);
+      if constexpr (decltype(do_store)::value) {
+        sa.store(smem + (cur ^ 1) * STAGE, tid);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+      }
+      mma(0);
+      if constexpr (decltype(do_store)::value) interleave(MW{}, NC{}); else interleave(MW{}, N0{});
+      // k-step 1: the loads of tile kt+2 start
+      ldf(0, as, bs, 2);
+      if constexpr (decltype(do_load)::value) {
+        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2), tid);
+        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2), tid);
+      }
+      mma(1);
+      if constexpr (decltype(do_load)::value) interleave(MG{}, NC{}); else interleave(MG{}, N0{});
+      // k-step 2
+      ldf(1, as, bs, 3);
+      mma(0);
+      interleave(MW{}, N0{});
+      __syncthreads();
+      // k-step 3, overlapped with the fetch of the next stage's first fragments
+      ldf(0, an, bn2, 0);
+      mma(1);
+      interleave(MW{}, N0{});
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) iter(kt, std::true_type{}, std::true_type{});
+    if (kt + 1 < nk) { iter(kt, std::true_type{}, std::false_type{}); ++kt; }
+    iter(kt, std::false_type{}, std::false_type{});
+    __syncthreads();
+  } else if (TL::PIPE == 0) {
     sa.load(A, lda, m0, 0, tid);
     sb.load(B, ldb, n0, 0, tid);
     sa.store(smem, tid);
@@ -309,10 +395,10 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 }
 
 int g_variant = 0;  // experiment switch (BF_GEMM_VARIANT): low bits pick the big tile, bit 4 turns the XCD remap off
-typedef Tile<256, 256, 2, 4, 1> TileBig;  // 8 waves, 128 x 64 per wave, pipelined
+typedef Tile<256, 256, 2, 4, 2> TileBig;  // 8 waves, 128 x 64 per wave, mid-tile barrier + pinned interleave
 typedef Tile<256, 256, 2, 2, 1> TileBig4;   // 4 waves, 128 x 128 per wave, pipelined
-typedef Tile<256, 256, 2, 4, 0> TileBigP;   // 8 waves, 128 x 64 per wave, plain loop
-typedef Tile<128, 128, 2, 2, 1> TileSmall;  // 4 waves, 64 x 64 per wave
+typedef Tile<256, 256, 2, 4, 1> TileBigP;   // 8 waves, 128 x 64 per wave, barrier at the end of the tile
+typedef Tile<128, 128, 2, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
 
 template <typename TL, bool AK, bool BKC>
 constexpr size_t lds_bytes() { return 2 * (size_t)(stage_elems<AK, TL::BM>() + stage_elems<BKC, TL::BN>()) * sizeof(bf16_t); }
