@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--no-df", action="store_true")
     ap.add_argument("--no-fuse-wgrad", action="store_true",
                     help="accumulate weight gradients per micro-batch in BF order too (default: one product per stage)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="first run a 1 GiB device copy (known HBM traffic) so that FETCH_SIZE / WRITE_SIZE "
+                         "readings of a rocprofv3 --pmc run of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one pipeline rank's share of the step); "
@@ -106,6 +109,14 @@ def main():
                          ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
                          fuse_wgrad=0 if args.no_fuse_wgrad else 1)
     torch.cuda.set_device(0)
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     st = bf.Stack(cfg, device="cuda:0")
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x221105953)
