@@ -14,8 +14,9 @@
 // for the contraction rows 16kk + 8(e/4) + 4(l/32) + e%4.  The matching A operand is read
 // from LDS with the transpose load (ds_read_b64_tr_b16) using that same row order.
 //
-// LDS tiles are [row][S_head] with the 16-byte chunk index XOR-swizzled by row & 7; the
-// layout serves both the K-contiguous 16-byte fragment reads and the transpose loads.
+// LDS tiles are [row][S_head] with the 16-byte chunk index XOR-swizzled by row bits; the
+// layout serves both the K-contiguous 16-byte fragment reads and the transpose loads without
+// bank conflicts.
 #include "common.h"
 
 namespace bf {
@@ -35,9 +36,20 @@ constexpr int BLK = 64;     // rows of the streamed tiles (keys in forward/dQ, q
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
+// XOR key of a tile row.  The LDS has 64 banks of 4 bytes; a 16-byte-per-lane read is served 16
+// lanes (16 rows, one logical chunk) at a time and a transpose load 32 lanes (4 rows x 4
+// adjacent chunks) at a time.  Both sets land in 16 distinct 16-byte slots of the 256-byte bank
+// line when the key sends row bits 0-1 to chunk bits 2-3 and row bits 2-3 to chunk bits 0-1
+// (S_head 128: 16 chunks per 256-byte row), or row bit 1 to chunk bit 2 and row bits 2-3 to chunk
+// bits 0-1 with the row parity choosing the half line (S_head 64: 8 chunks per 128-byte row).
+template <int D>
+__device__ __forceinline__ int row_key(int row) {
+  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
 template <int D>
 __device__ __forceinline__ int swz(int row, int col) {
-  return row * D + ((((col >> 3) ^ (row & 7)) << 3) | (col & 7));
+  return row * D + ((((col >> 3) ^ row_key<D>(row)) << 3) | (col & 7));
 }
 
 // thread's 16-byte chunks of a [ROWS][D] tile
@@ -56,7 +68,7 @@ struct TileRegs {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int c = tid + i * NTHR, row = c / (D / 8), ch = c % (D / 8);
-      *reinterpret_cast<u32x4*>(lds + row * D + ((ch ^ (row & 7)) << 3)) = v[i];
+      *reinterpret_cast<u32x4*>(lds + row * D + ((ch ^ row_key<D>(row)) << 3)) = v[i];
     }
   }
 };

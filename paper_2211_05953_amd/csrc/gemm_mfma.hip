@@ -4,7 +4,7 @@
 // B tiles are copied global -> registers -> LDS (16-byte accesses, double-buffered LDS, the
 // next tile's global loads in flight during the current tile's MFMAs).  Operands whose
 // global layout is K-contiguous sit in LDS as [row][BK] with the 16-byte chunk index
-// XOR-swizzled by the row (conflict-free ds_read_b128 of MFMA fragments).  Operands whose
+// XOR-swizzled by row bits (conflict-free ds_read_b128 of MFMA fragments on the 64-bank LDS).  Operands whose
 // global layout has K as the slow dimension (B of the forward product, both operands of
 // the weight-gradient product) sit in LDS as [BK][cols + pad] and are read through the
 // LDS transpose load (ds_read_b64_tr_b16), which hands every lane four consecutive k of
@@ -41,46 +41,54 @@ struct Tile {
   static constexpr int MI = TM / 32, NI = TN / 32;
 };
 
+// XOR key of a K-contiguous LDS row (128 bytes = 8 chunks of 16 bytes).  The LDS has 64 banks of 4
+// bytes and serves a 16-byte-per-lane read 16 lanes at a time: the 16 rows r..r+15 that those
+// lanes read at one logical chunk must land in 16 different (row parity, chunk) slots, which any
+// bijection of the bits of row >> 1 gives.
+__device__ __forceinline__ int kswz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
 // bytes of one LDS stage of an operand tile with R rows (m or n extent)
 template <bool KCONTIG, int R>
 constexpr int stage_elems() { return KCONTIG ? R * BK : BK * (R + TPAD); }
 
-// ---- global -> registers: the thread's 16-byte chunks of an operand tile
+// ---- global -> registers: the thread's 16-byte chunks of an operand tile.  Chunk i of a thread
+// sits a fixed number of tile rows below chunk 0, so one per-thread byte offset (global) and one
+// per-thread element offset (LDS) serve all chunks: every load is "wave-uniform base (scalar
+// registers, moved per k-tile and per chunk) + 32-bit lane offset", every LDS store "lane offset
+// + immediate".
 template <bool KCONTIG, int R, int NT>
 struct Stager {
   static constexpr int CHUNKS = R * BK / 8 / NT;
+  static constexpr int ROWSTEP = KCONTIG ? NT / 8 : NT / (R / 8);  // tile rows between a thread's chunks
+  static_assert(!KCONTIG || ROWSTEP % 16 == 0, "the swizzle key must repeat from chunk to chunk");
   u32x4 v[CHUNKS];
+  uint32_t goff;  // byte offset of chunk 0 from the tile's first element
+  int loff;       // element offset of chunk 0 inside the LDS tile
 
-  // g: operand base; ld: its leading dimension (elements); r0: first row/col of the tile; k0: first k
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int r0, int k0, int tid) {
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int c = tid + i * NT;
-      const bf16_t* p;
-      if (KCONTIG) {
-        const int row = c >> 3, kc = c & 7;  // 8 chunks per row of BK = 64
-        p = g + (size_t)(r0 + row) * ld + k0 + kc * 8;
-      } else {
-        const int krow = c / (R / 8), rc = c % (R / 8);
-        p = g + (size_t)(k0 + krow) * ld + r0 + rc * 8;
-      }
-      v[i] = *reinterpret_cast<const u32x4*>(p);
+  __device__ __forceinline__ void init(size_t ld, int tid) {
+    if (KCONTIG) {
+      const int row = tid >> 3, kc = tid & 7;  // 8 chunks per row of BK = 64
+      goff = (uint32_t)(((size_t)row * ld + kc * 8) * sizeof(bf16_t));
+      loff = row * BK + ((kc ^ kswz(row)) << 3);
+    } else {
+      const int krow = tid / (R / 8), rc = tid % (R / 8);
+      goff = (uint32_t)(((size_t)krow * ld + rc * 8) * sizeof(bf16_t));
+      loff = krow * (R + TPAD) + rc * 8;
     }
   }
-  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+  // g: operand base (uniform); r0: first row/col of the tile; k0: first k.  Buffer loads: the
+  // descriptor carries the tile's base address, the lane offset is a VGPR, the chunk step an SGPR.
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int r0, int k0) {
+    const bf16_t* base = KCONTIG ? g + (size_t)r0 * ld + k0 : g + (size_t)k0 * ld + r0;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+    const int step = (int)((size_t)ROWSTEP * ld * sizeof(bf16_t));
 #pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int c = tid + i * NT;
-      int off;
-      if (KCONTIG) {
-        const int row = c >> 3, kc = c & 7;
-        off = row * BK + ((kc ^ (row & 7)) << 3);
-      } else {
-        const int krow = c / (R / 8), rc = c % (R / 8);
-        off = krow * (R + TPAD) + rc * 8;
-      }
-      *reinterpret_cast<u32x4*>(lds + off) = v[i];
-    }
+    for (int i = 0; i < CHUNKS; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff, i * step, 0);
+  }
+  __device__ __forceinline__ void store(bf16_t* lds) const {
+    constexpr int LSTEP = KCONTIG ? ROWSTEP * BK : ROWSTEP * (R + TPAD);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) *reinterpret_cast<u32x4*>(lds + loff + i * LSTEP) = v[i];
   }
 };
 
@@ -90,7 +98,7 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16_t* lds, int r32, int kk, 
   if (KCONTIG) {
     const int row = r32 + (lane & 31);
     const int kc = kk * 2 + (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(lds + row * BK + ((kc ^ (row & 7)) << 3));
+    return *reinterpret_cast<const bf16x8*>(lds + row * BK + ((kc ^ kswz(row)) << 3));
   } else {
     const int t = lane & 15, blk = lane >> 4;
     const int k = kk * 16 + 8 * (blk >> 1) + (t >> 2);
@@ -153,6 +161,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 
   Stager<AK, BM, NT> sa;
   Stager<BKC, BN, NT> sb;
+  sa.init(lda, tid);
+  sb.init(ldb, tid);
   const int nk_seg = K / BK, nk = nk_seg * n_seg;
   // k-tile kt lives in segment kt / nk_seg (one segment unless this is a multi-micro-batch weight gradient)
   auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
@@ -189,6 +199,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         if (decltype(n_extra)::value > 0 && i < decltype(n_extra)::value)
           __builtin_amdgcn_sched_group_barrier(decltype(extra_mask)::value, 1, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);  // nothing moves across the end of a k-step
     };
     constexpr int NCH = Stager<AK, BM, NT>::CHUNKS + Stager<BKC, BN, NT>::CHUNKS;
     typedef std::integral_constant<int, 0x200> MW;
@@ -196,13 +207,13 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     typedef std::integral_constant<int, NCH> NC;
     typedef std::integral_constant<int, 0> N0;
 
-    sa.load(A, lda, m0, 0, tid);
-    sb.load(B, ldb, n0, 0, tid);
-    sa.store(smem, tid);
-    sb.store(smem + A_ST, tid);
+    sa.load(A, lda, m0, 0);
+    sb.load(B, ldb, n0, 0);
+    sa.store(smem);
+    sb.store(smem + A_ST);
     if (nk > 1) {
-      sa.load(seg_a_of(1), lda, m0, k0_of(1), tid);
-      sb.load(seg_b_of(1), ldb, n0, k0_of(1), tid);
+      sa.load(seg_a_of(1), lda, m0, k0_of(1));
+      sb.load(seg_b_of(1), ldb, n0, k0_of(1));
     }
     __syncthreads();
     ldf(0, smem, smem + A_ST, 0);
@@ -215,16 +226,16 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
       // k-step 0: tile kt+1 (in registers since the previous iteration) goes to the other stage
       ldf(1, as, bs, 1);
       if constexpr (decltype(do_store)::value) {
-        sa.store(smem + (cur ^ 1) * STAGE, tid);
-        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+        sa.store(smem + (cur ^ 1) * STAGE);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST);
       }
       mma(0);
       if constexpr (decltype(do_store)::value) interleave(MW{}, NC{}); else interleave(MW{}, N0{});
       // k-step 1: the loads of tile kt+2 start
       ldf(0, as, bs, 2);
       if constexpr (decltype(do_load)::value) {
-        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2), tid);
-        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2), tid);
+        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
+        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2));
       }
       mma(1);
       if constexpr (decltype(do_load)::value) interleave(MG{}, NC{}); else interleave(MG{}, N0{});
@@ -244,16 +255,16 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     iter(kt, std::false_type{}, std::false_type{});
     __syncthreads();
   } else if (TL::PIPE == 0) {
-    sa.load(A, lda, m0, 0, tid);
-    sb.load(B, ldb, n0, 0, tid);
-    sa.store(smem, tid);
-    sb.store(smem + A_ST, tid);
+    sa.load(A, lda, m0, 0);
+    sb.load(B, ldb, n0, 0);
+    sa.store(smem);
+    sb.store(smem + A_ST);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
       const int cur = kt & 1;
       if (kt + 1 < nk) {
-        sa.load(seg_a_of(kt + 1), lda, m0, k0_of(kt + 1), tid);
-        sb.load(seg_b_of(kt + 1), ldb, n0, k0_of(kt + 1), tid);
+        sa.load(seg_a_of(kt + 1), lda, m0, k0_of(kt + 1));
+        sb.load(seg_b_of(kt + 1), ldb, n0, k0_of(kt + 1));
       }
       const bf16_t* as = smem + cur * STAGE;
       const bf16_t* bs = as + A_ST;
@@ -270,8 +281,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
           for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       }
       if (kt + 1 < nk) {
-        sa.store(smem + (cur ^ 1) * STAGE, tid);
-        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+        sa.store(smem + (cur ^ 1) * STAGE);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST);
       }
       __syncthreads();
     }
@@ -279,13 +290,13 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     // Tile kt+1 sits in registers when iteration kt starts (loaded one iteration earlier): it goes to
     // the idle LDS stage first, the loads of tile kt+2 follow, and the fragments of k-step kk+1
     // are requested before the MFMAs of k-step kk.
-    sa.load(A, lda, m0, 0, tid);
-    sb.load(B, ldb, n0, 0, tid);
-    sa.store(smem, tid);
-    sb.store(smem + A_ST, tid);
+    sa.load(A, lda, m0, 0);
+    sb.load(B, ldb, n0, 0);
+    sa.store(smem);
+    sb.store(smem + A_ST);
     if (nk > 1) {
-      sa.load(seg_a_of(1), lda, m0, k0_of(1), tid);
-      sb.load(seg_b_of(1), ldb, n0, k0_of(1), tid);
+      sa.load(seg_a_of(1), lda, m0, k0_of(1));
+      sb.load(seg_b_of(1), ldb, n0, k0_of(1));
     }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
@@ -298,12 +309,12 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 #pragma unroll
       for (int j = 0; j < NI; ++j) bfr[0][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, 0, lane);
       if (kt + 1 < nk) {
-        sa.store(smem + (cur ^ 1) * STAGE, tid);
-        sb.store(smem + (cur ^ 1) * STAGE + A_ST, tid);
+        sa.store(smem + (cur ^ 1) * STAGE);
+        sb.store(smem + (cur ^ 1) * STAGE + A_ST);
       }
       if (kt + 2 < nk) {
-        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2), tid);
-        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2), tid);
+        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
+        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2));
       }
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
