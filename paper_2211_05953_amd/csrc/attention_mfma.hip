@@ -176,34 +176,42 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
       for (int kk = 0; kk < D / 16; ++kk)
         s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s[t], 0, 0, 0);
     }
+    // Online softmax on the raw scores: m is the running max of the unscaled scores, the scale
+    // 1/sqrt(S_head) log2(e) enters through one fma per element, the exponentials are the
+    // hardware exp2 (arguments <= 0; masked scores are -inf and give exactly 0).
+    if (causal && kb + BLK - 1 > qw) {  // only tiles that touch the diagonal pay for the mask
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (kb + 32 * t + acc_row(r, lane) > q) s[t][r] = -INFINITY;
+    }
     float mx = m;
-    const bool diag = causal && kb + BLK - 1 > qw;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = s[t][r] * c2;
-        if (diag && kb + 32 * t + acc_row(r, lane) > q) v = -INFINITY;
-        s[t][r] = v;
-        mx = fmaxf(mx, v);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = exp2f(m - mx);
-    m = mx;
+    const float nmx = -mx * c2;
     float sum = 0.f;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[t][r] - mx);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, nmx));
         s[t][r] = p;
         sum += p;
       }
-    l = l * alpha + sum;
+    if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {  // some row's max moved: rescale (rare after the first tiles)
+      const float alpha = __builtin_amdgcn_exp2f(fmaf(m, c2, nmx));
+      l *= alpha;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      m = mx;
+    }
+    l += sum;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -216,7 +224,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
   }
   l += __shfl_xor(l, 32, 64);
   store_rows<D>(o, ctx + ((size_t)b * S_seq + q) * h + head * D, lane, 1.0f / l);
-  if (lane < 32) lse[((size_t)b * N_heads + head) * S_seq + q] = m * LN2 + logf(l);
+  if (lane < 32) lse[((size_t)b * N_heads + head) * S_seq + q] = m * scale + logf(l);
 }
 
 // delta[b, head, i] = sum_c dctx[i, c] * ctx[i, c]: one wave per (token, head)
@@ -282,11 +290,13 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Vs, 32 * t, kk, lane), dof[kk], dp, 0, 0, 0);
       }
+      // p = exp(s/sqrt(d) - lse); dS = p (dP - delta) (the factor 1/sqrt(d) is applied once, to dQ)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = exp2f(s[r] * c2 - lse2);
-        if (diag && kb + 32 * t + acc_row(r, lane) > q) p = 0.f;
-        s[r] = p * (dp[r] - dl) * scale;
+      for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2)) * (dp[r] - dl);
+      if (diag) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (kb + 32 * t + acc_row(r, lane) > q) s[r] = 0.f;
       }
 #pragma unroll
       for (int k2 = 0; k2 < 2; ++k2) {
@@ -297,7 +307,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
       }
     }
   }
-  store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, 1.0f);
+  store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, scale);
 }
 
 // ----------------------------------------------------------------- backward, dK/dV pass
@@ -360,10 +370,14 @@ __global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __rest
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int ql = 32 * t + acc_row(r, lane);
-        float p = exp2f(s[r] * c2 - lse_s[ql]);
-        if (diag && key > qb + ql) p = 0.f;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse_s[ql]));
         pr[r] = p;
-        s[r] = p * (dp[r] - delta_s[ql]) * scale;
+        s[r] = p * (dp[r] - delta_s[ql]);  // the factor 1/sqrt(d) is applied once, to dK
+      }
+      if (diag) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (key > qb + 32 * t + acc_row(r, lane)) { pr[r] = 0.f; s[r] = 0.f; }
       }
 #pragma unroll
       for (int k2 = 0; k2 < 2; ++k2) {
@@ -377,7 +391,7 @@ __global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __rest
     }
   }
   bf16_t* out = dqkv + ((size_t)b * S_seq + key) * ld + head * D;
-  store_rows<D>(dk, out + h, lane, 1.0f);
+  store_rows<D>(dk, out + h, lane, scale);
   store_rows<D>(dv, out + 2 * h, lane, 1.0f);
 }
 

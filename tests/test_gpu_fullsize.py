@@ -1,0 +1,182 @@
+"""Parity at the benchmark's full sizes (52B-shaped rank share: S_hidden 8192, 64 heads of 128,
+S_mlp 32768, S_seq 2048, S_mb 1), in the launch configuration bench.py times.
+
+The oracle cannot run a whole step at this size, so:
+  * every GEMM shape of the layer (forward, dgrad, per-micro-batch and fused weight gradient) is
+    checked on sampled output elements that the oracle computes one by one (fp64 dot products);
+  * attention forward/backward is checked on sampled (head, position) rows computed by the oracle
+    from the definition;
+  * one layer, one micro-batch of the full width runs through bf_run_step and is compared with the
+    oracle's step element by element;
+  * the full 8-layer, 16-micro-batch step is checked through properties that hold at any size:
+    BF == DF bitwise with per-micro-batch accumulation, the fused weight gradient equal to it up
+    to fp32 rounding, event trace and checkpoint counts equal to Eq. mem_ckpt.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import bf_inputs
+import paper_2211_05953_amd as bf
+from oracle import formulas as F
+from oracle import layer as L
+from oracle import stack as K
+from util import TOL, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+H, A, D, FF, S = 8192, 64, 128, 32768, 2048
+
+
+def _sample_check(got, ref_fn, shape, n, rng, tol, scale):
+    idx = [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(n)]
+    worst = 0.0
+    for i in idx:
+        worst = max(worst, abs(float(got[i]) - ref_fn(*i)))
+    assert worst <= tol * scale, (worst, tol * scale)
+
+
+@pytest.mark.parametrize("name,layout,epi,M,N,Kd", [
+    ("qkv fwd", bf.BF_NN, bf.BF_EPI_BIAS, S, 3 * H, H),
+    ("fc1 fwd", bf.BF_NN, bf.BF_EPI_BIAS_GELU, S, FF, H),
+    ("fc2 fwd", bf.BF_NN, bf.BF_EPI_BIAS_RES, S, H, FF),
+    ("fc2 dgrad", bf.BF_NT, bf.BF_EPI_GELU_BWD, S, FF, H),
+    ("qkv dgrad", bf.BF_NT, bf.BF_EPI_NONE, S, H, 3 * H),
+    ("fc1 wgrad", bf.BF_TN, bf.BF_EPI_ACCUM, H, FF, S),
+])
+def test_gemm_shapes_of_the_52b_layer_on_sampled_outputs(name, layout, epi, M, N, Kd):
+    assert bf.bf_op_gemm_uses_mfma(layout, epi, M, N, Kd)
+    rng = np.random.default_rng(1)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    a_shape = (M, Kd) if layout != bf.BF_TN else (Kd, M)
+    b_shape = (Kd, N) if layout != bf.BF_NT else (N, Kd)
+    dA = torch.randn(a_shape, generator=g, device="cuda").bfloat16()
+    dB = (torch.randn(b_shape, generator=g, device="cuda") * 0.02).bfloat16()
+    dR = torch.randn((M, N), generator=g, device="cuda").bfloat16()
+    dbias = torch.randn(N, generator=g, device="cuda") * 0.1
+    out_t = torch.float32 if layout == bf.BF_TN else torch.bfloat16
+    out = torch.empty((M, N), dtype=out_t, device="cuda")
+    out2 = torch.empty_like(out)
+    bf.bf_op_gemm(bf.BF_BF16, 0, layout, epi, M, N, Kd, dA, dB, out, bias=dbias, R=dR, C2=out2, accumulate=0)
+    Ah, Bh, Rh, bh = to_host(dA).astype(np.float64), to_host(dB).astype(np.float64), to_host(dR).astype(np.float64), to_host(dbias).astype(np.float64)
+    o, o2 = to_host(out), to_host(out2)
+
+    def acc(m, n):
+        a = Ah[m, :] if layout != bf.BF_TN else Ah[:, m]
+        b = Bh[:, n] if layout != bf.BF_NT else Bh[n, :]
+        return float(a @ b)
+
+    ref = {bf.BF_EPI_BIAS: lambda m, n: acc(m, n) + bh[n],
+           bf.BF_EPI_BIAS_GELU: lambda m, n: acc(m, n) + bh[n],
+           bf.BF_EPI_BIAS_RES: lambda m, n: acc(m, n) + bh[n] + Rh[m, n],
+           bf.BF_EPI_GELU_BWD: lambda m, n: acc(m, n) * float(L.gelu_grad(Rh[m, n])),
+           bf.BF_EPI_NONE: acc, bf.BF_EPI_ACCUM: acc}[epi]
+    scale = math.sqrt(Kd) * 0.02 + 1.0          # typical magnitude of an output element
+    tol = 1e-5 if layout == bf.BF_TN else TOL["bf16"]
+    _sample_check(o, ref, (M, N), 400, rng, tol, scale * (4 if layout == bf.BF_TN else 1))
+    if epi == bf.BF_EPI_BIAS_GELU:
+        _sample_check(o2, lambda m, n: float(L.gelu(acc(m, n) + bh[n])), (M, N), 200, rng, tol, scale)
+
+
+def test_fused_weight_gradient_over_16_micro_batches_on_sampled_outputs():
+    """One product over N_mb = 16 segments of T = 2048 rows (out-proj weight gradient shape)."""
+    n_seg, T, M, N = 16, S, H, H
+    g = torch.Generator(device="cuda").manual_seed(9)
+    X = torch.randn((n_seg, T, M), generator=g, device="cuda").bfloat16()
+    dY = torch.randn((n_seg, T, N), generator=g, device="cuda").bfloat16()
+    G = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    # 16 accumulating calls (the per-micro-batch order) against one product over all 32768 rows (the
+    # contraction the fused path runs; its segment addressing is covered by the step tests)
+    for i in range(n_seg):
+        bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, T, X[i], dY[i], G, accumulate=int(i > 0))
+    Gl = torch.empty_like(G)
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, n_seg * T, X.view(n_seg * T, M), dY.view(n_seg * T, N), Gl, accumulate=0)
+    Gh, Glh = to_host(G), to_host(Gl)
+    # fp32 sums of 32768 products associated differently: ~sqrt(K) 2^-24 relative to the largest sum
+    assert rel_err(Glh, Gh) <= 1e-5
+    rng = np.random.default_rng(2)
+    Xh, Yh = X.float().cpu().numpy().reshape(-1, M), dY.float().cpu().numpy().reshape(-1, N)
+    _sample_check(Glh, lambda m, n: float(Xh[:, m].astype(np.float64) @ Yh[:, n].astype(np.float64)), (M, N), 200, rng,
+                  1e-5, 4 * math.sqrt(n_seg * T))
+
+
+def test_attention_at_full_size_on_sampled_rows():
+    g = torch.Generator(device="cuda").manual_seed(11)
+    qkv = torch.randn((1, S, 3 * H), generator=g, device="cuda").bfloat16()
+    dctx = torch.randn((1, S, H), generator=g, device="cuda").bfloat16()
+    ctx = torch.empty((1, S, H), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((1, A, S), dtype=torch.float32, device="cuda")
+    dqkv = torch.empty_like(qkv)
+    delta = torch.empty(A * S, dtype=torch.float32, device="cuda")
+    assert bf.bf_op_attention_uses_mfma(S, D)
+    bf.bf_op_attention_fwd(bf.BF_BF16, 0, 1, S, A, D, 1, qkv, ctx, lse)
+    bf.bf_op_attention_bwd(bf.BF_BF16, 0, 1, S, A, D, 1, qkv, ctx, lse, dctx, dqkv, delta)
+    qh, ch, dh, gh, lh = to_host(qkv), to_host(ctx), to_host(dctx), to_host(dqkv), to_host(lse)
+    rng = np.random.default_rng(3)
+    for head in rng.choice(A, 3, replace=False):
+        # the oracle on this one head (heads are independent)
+        cols = np.r_[head * D:(head + 1) * D]
+        one = np.concatenate([qh[..., cols], qh[..., H + cols], qh[..., 2 * H + cols]], axis=-1).astype(np.float64)
+        ctx_ref, saved = L.attention_fwd(one, 1, True)
+        dq_ref = L.attention_bwd(dh[..., cols].astype(np.float64), saved, 1)
+        assert rel_err(ch[..., cols], ctx_ref) <= TOL["bf16"]
+        for j, nm in enumerate(("dq", "dk", "dv")):
+            assert rel_err(gh[..., j * H + cols], dq_ref[..., j * D:(j + 1) * D]) <= TOL["bf16"], (head, nm)
+        q, k, v, p = saved
+        s = (q[0, 0] @ k[0, 0].T) / math.sqrt(D)
+        s = np.where(np.tril(np.ones((S, S), dtype=bool)), s, -np.inf)
+        lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+        assert np.abs(lh[0, head] - lse_ref).max() <= 2e-2
+
+
+def test_one_full_width_layer_step_against_the_oracle():
+    params = bf_inputs.make_params(21, 1, H, FF, bf16=True)
+    x, dy = bf_inputs.make_batch(21, 1, 1, S, H, bf16=True)
+    ref = K.run_step([{k: v.astype(np.float64) for k, v in params[0].items()}], x.astype(np.float64), dy.astype(np.float64),
+                     K.SCHED_BF, 1, A)
+    cfg = bf.make_config(H, A, FF, S, 1, 1, 1, fuse_wgrad=1)
+    st = bf.Stack(cfg)
+    for name, tid in bf.TENSOR_IDS.items():
+        st.bf_set_params(0, tid, params[0][name].reshape(-1))
+    dX, dDY = to_dev(x, True), to_dev(dy, True)
+    y, dx = torch.empty_like(dX), torch.empty_like(dX)
+    st.bf_run_step(bf.BF_SCHED_BF, 1, 1, 1, dX, dDY, y, dx)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(y), ref["y"]) <= TOL["bf16"]
+    assert rel_err(to_host(dx), ref["dx"]) <= TOL["bf16"]
+    for name, tid in bf.TENSOR_IDS.items():
+        e = rel_err(st.bf_get_grads(0, tid), ref["grads"][0][name].reshape(-1))
+        assert e <= TOL["bf16"], (name, e)
+    st.close()
+
+
+def test_full_52b_rank_share_step_invariants():
+    Lyr, N_loop, N_mb = 8, 4, 16
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn((N_mb, 1, S, H), generator=g, device="cuda").bfloat16()
+    dy = torch.randn((N_mb, 1, S, H), generator=g, device="cuda").bfloat16()
+    res = {}
+    for tag, fuse, sched in (("bf", 0, bf.BF_SCHED_BF), ("df", 0, bf.BF_SCHED_DF), ("bf_fused", 1, bf.BF_SCHED_BF)):
+        st = bf.Stack(bf.make_config(H, A, FF, S, Lyr, N_mb, 1, fuse_wgrad=fuse))
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        rep = st.bf_run_step(sched, N_loop, N_mb, 1, x, dy, y, dx)
+        torch.cuda.synchronize()
+        res[tag] = dict(y=y.cpu(), dx=dx.cpu(), rep=rep, trace=st.bf_get_trace(),
+                        grads={(l, n): st.bf_get_grads(l, bf.TENSOR_IDS[n]) for l, n in
+                               [(0, "w_o"), (7, "w_o"), (3, "b_fc1"), (5, "ln1_g"), (2, "b_qkv")]})
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+    assert torch.isfinite(res["bf"]["y"].float()).all() and torch.isfinite(res["bf"]["dx"].float()).all()
+    for k in ("y", "dx"):
+        assert torch.equal(res["bf"][k], res["df"][k]) and torch.equal(res["bf"][k], res["bf_fused"][k])
+    for key in res["bf"]["grads"]:
+        assert np.array_equal(res["bf"]["grads"][key], res["df"]["grads"][key]), key
+        assert rel_err(res["bf_fused"]["grads"][key], res["bf"]["grads"][key]) <= 1e-5, key
+    assert res["bf"]["rep"].peak_ckpt_count == F.ckpt_count("BF", N_mb, Lyr, 1) == 128
+    assert res["df"]["rep"].peak_ckpt_count == F.ckpt_count("DF", N_mb, Lyr, 1) == 8
+    assert [e[:3] for e in res["bf"]["trace"]] == K.event_order(K.SCHED_BF, N_loop, N_mb)
+    assert [e[:3] for e in res["df"]["trace"]] == K.event_order(K.SCHED_DF, N_loop, N_mb)
+    assert res["bf"]["rep"].flops_paper == float(F.c_gpu(N_mb, 1, Lyr, H, S))
