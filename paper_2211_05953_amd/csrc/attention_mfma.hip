@@ -53,21 +53,21 @@ __device__ __forceinline__ int swz(int row, int col) {
 }
 
 // thread's 16-byte chunks of a [ROWS][D] tile
-template <int ROWS, int D>
+template <int ROWS, int D, int NT = 256>
 struct TileRegs {
-  static constexpr int CH = ROWS * D / 8 / NTHR;
+  static constexpr int CH = ROWS * D / 8 / NT;
   u32x4 v[CH];
   __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int tid) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-      const int c = tid + i * NTHR, row = c / (D / 8), ch = c % (D / 8);
+      const int c = tid + i * NT, row = c / (D / 8), ch = c % (D / 8);
       v[i] = *reinterpret_cast<const u32x4*>(g + (size_t)row * ld + ch * 8);
     }
   }
   __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-      const int c = tid + i * NTHR, row = c / (D / 8), ch = c % (D / 8);
+      const int c = tid + i * NT, row = c / (D / 8), ch = c % (D / 8);
       *reinterpret_cast<u32x4*>(lds + row * D + ((ch ^ row_key<D>(row)) << 3)) = v[i];
     }
   }
@@ -311,15 +311,25 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
 }
 
 // ----------------------------------------------------------------- backward, dK/dV pass
+// 8 waves per 128-key block.  Waves 0-3 (one per 32 keys) accumulate dV = P^T dO, waves 4-7 the
+// matching dK = dS^T Q: each role keeps one 32 x S_head accumulator set plus its K (and V) rows in
+// registers, which fits 256 registers per lane, so two waves share a SIMD and one role's
+// exponentials overlap the other's MFMAs.  Both roles recompute S = Q K^T (8 of 24 / 16 MFMAs per
+// 32 x 32 tile).
+constexpr int NTHR_DKV = 512;
+
 template <int D>
-__global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                            bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
-                                                            float scale) {
+__global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                                const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
+                                                                float scale) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[BLK * D];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[BLK * D];
-  __shared__ float lse_s[BLK], delta_s[BLK];
+  __shared__ __attribute__((aligned(16))) float lse_s[BLK];
+  __shared__ __attribute__((aligned(16))) float delta_s[BLK];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int kg = w & 3;
+  const bool dk_role = w >= 4;  // wave-uniform
   const int kblk = blockIdx.x;  // earliest keys see the most queries: they go first
   const int head = blockIdx.y, b = blockIdx.z;
   const int h = N_heads * D;
@@ -328,18 +338,18 @@ __global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __rest
   const bf16_t* dob = dctx + (size_t)b * S_seq * h + head * D;
   const float* lrow = lse + ((size_t)b * N_heads + head) * S_seq;
   const float* drow = delta + ((size_t)b * N_heads + head) * S_seq;
-  const int k0 = kblk * WG_ROWS, kw = k0 + 32 * w, key = kw + (lane & 31);
+  const int k0 = kblk * WG_ROWS, kw = k0 + 32 * kg, key = kw + (lane & 31);
 
   bf16x8 kf[D / 16], vf[D / 16];
   load_rowfrags<D>(base + (size_t)key * ld + h, lane, kf);
-  load_rowfrags<D>(base + (size_t)key * ld + 2 * h, lane, vf);
+  if (dk_role) load_rowfrags<D>(base + (size_t)key * ld + 2 * h, lane, vf);
   const float c2 = scale * LOG2E;
-  f32x16 dk[D / 32], dv[D / 32];
+  f32x16 acc[D / 32];  // dV (waves 0-3) or dK (waves 4-7), transposed: rows = head dims, column = key
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
+  for (int dt = 0; dt < D / 32; ++dt) acc[dt] = zero16();
 
   const int jbeg = causal ? k0 / BLK : 0, nblk = S_seq / BLK;
-  TileRegs<BLK, D> qr, dor;
+  TileRegs<BLK, D, NTHR_DKV> qr, dor;
   qr.load(base + (size_t)jbeg * BLK * ld, ld, tid);
   dor.load(dob + (size_t)jbeg * BLK * h, h, tid);
   float lnext = 0.f, dnext = 0.f;
@@ -360,39 +370,55 @@ __global__ __launch_bounds__(NTHR) void attn_bwd_dkv_kernel(const bf16_t* __rest
     const bool diag = causal && qb < kw + 31;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      f32x16 s = zero16(), dp = zero16();
+      f32x16 s = zero16();
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
+      for (int kk = 0; kk < D / 16; ++kk)
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Qs, 32 * t, kk, lane), kf[kk], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(dOs, 32 * t, kk, lane), vf[kk], dp, 0, 0, 0);
-      }
-      f32x16 pr;
+      if (!dk_role) {
+        // P = exp(S / sqrt(d) - lse);  dV += dO^T P
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int ql = 32 * t + acc_row(r, lane);
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse_s[ql]));
-        pr[r] = p;
-        s[r] = p * (dp[r] - delta_s[ql]);  // the factor 1/sqrt(d) is applied once, to dK
-      }
-      if (diag) {
+        for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse_s[32 * t + acc_row(r, lane)]));
+        if (diag) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (key > qb + 32 * t + acc_row(r, lane)) { pr[r] = 0.f; s[r] = 0.f; }
-      }
+          for (int r = 0; r < 16; ++r)
+            if (key > qb + 32 * t + acc_row(r, lane)) s[r] = 0.f;
+        }
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        const bf16x8 pb = pack8(pr, k2), dsb = pack8(s, k2);
+        for (int k2 = 0; k2 < 2; ++k2) {
+          const bf16x8 pb = pack8(s, k2);
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(dOs, 32 * t + 16 * k2, 32 * dt, lane), pb, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Qs, 32 * t + 16 * k2, 32 * dt, lane), dsb, dk[dt], 0, 0, 0);
+          for (int dt = 0; dt < D / 32; ++dt)
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(dOs, 32 * t + 16 * k2, 32 * dt, lane), pb, acc[dt], 0, 0, 0);
+        }
+      } else {
+        // dP = dO V^T;  dS = P (dP - delta) (the factor 1/sqrt(d) is applied once, to dK);  dK += Q^T dS
+        f32x16 dp = zero16();
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(dOs, 32 * t, kk, lane), vf[kk], dp, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ql = 32 * t + acc_row(r, lane);
+          s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse_s[ql])) * (dp[r] - delta_s[ql]);
+        }
+        if (diag) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (key > qb + 32 * t + acc_row(r, lane)) s[r] = 0.f;
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          const bf16x8 dsb = pack8(s, k2);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt)
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Qs, 32 * t + 16 * k2, 32 * dt, lane), dsb, acc[dt], 0, 0, 0);
         }
       }
     }
   }
   bf16_t* out = dqkv + ((size_t)b * S_seq + key) * ld + head * D;
-  store_rows<D>(dk, out + h, lane, scale);
-  store_rows<D>(dv, out + 2 * h, lane, 1.0f);
+  if (dk_role) store_rows<D>(acc, out + h, lane, scale);
+  else store_rows<D>(acc, out + 2 * h, lane, 1.0f);
 }
 
 template <int D>
@@ -411,7 +437,7 @@ bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, c
   attn_delta_kernel<D><<<dim3(S_seq / 4, N_heads, S_mb), NTHR, 0, st>>>((const bf16_t*)ctx, (const bf16_t*)dctx, delta, S_seq, N_heads);
   dim3 grid(S_seq / WG_ROWS, N_heads, S_mb);
   attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
-  attn_bwd_dkv_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
+  attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
