@@ -107,7 +107,7 @@ def main():
     b16 = dtype == "bf16"
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
                          ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
-                         fuse_wgrad=0 if args.no_fuse_wgrad else 1)
+                         fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop)
     torch.cuda.set_device(0)
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy

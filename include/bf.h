@@ -68,13 +68,16 @@ typedef struct {
   int32_t kernels;                                 /* bf_kernels */
   int32_t queue_depth;  /* > 0: the host never runs more than this many stage-level ops ahead of
                            the device (App. D.2, bounded kernel queue); 0: unbounded */
-  int32_t fuse_wgrad;   /* 1: in breadth-first order (and without checkpointing) the weight-matrix gradients
-                           of a stage are taken once per stage, as one product over all its micro-batches,
-                           after the stage's last backward ("aggregates the steps by layer", Sec. 4.2): the
-                           fp32 main-grad is written once instead of read-modified-written N_mb times.
-                           The sum over micro-batches is then one long fp32 contraction, so BF and DF
-                           gradients agree to rounding, not bitwise.  0: accumulate per micro-batch. */
-  int32_t reserved_;    /* keeps seed 8-byte aligned; must be 0 */
+  int32_t fuse_wgrad;   /* 1: in breadth-first order the weight-matrix gradients of a stage are taken once per
+                           stage, as one product over all its micro-batches, after the stage's last backward
+                           ("aggregates the steps by layer", Sec. 4.2): the fp32 main-grad is written once
+                           instead of read-modified-written N_mb times.  The sum over micro-batches is then
+                           one long fp32 contraction, so BF and DF gradients agree to rounding, not bitwise.
+                           The per-micro-batch operands of one stage are kept until then (with
+                           BF_CKPT_LAYER: the recomputed ones).  0: accumulate per micro-batch. */
+  int32_t N_loop_min;   /* smallest N_loop bf_run_step will be called with (0 or 1: any).  Sizes the per-stage
+                           buffers of fuse_wgrad for ceil(N_layers / N_loop_min) layers; a step whose stages
+                           are larger than that accumulates per micro-batch instead. */
   uint64_t seed;        /* device-side initialisation: weights ~ N(0, init_std), biases 0, LN gain 1 */
   float init_std;
   float ln_eps;

@@ -351,9 +351,21 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     // bf16 outputs: the fp32 accumulators pass through LDS, 64 tile rows at a time, so that every
     // thread finishes 8 adjacent columns (bias, residual, GeLU in fp32, one rounding) and the
     // global accesses of C, C2 and R are 16 bytes per lane over whole 512-byte row segments.
-    constexpr int PR = 64, LDC = BN + 4;
+    constexpr int PR = 64, LDC = BN + 4, NQ = PR * BN / 8 / NT;
     float* cs = reinterpret_cast<float*>(smem_raw);
     static_assert((size_t)PR * LDC * 4 <= 2 * (size_t)STAGE * sizeof(bf16_t), "epilogue staging does not fit");
+    // the residual / pre-activation values of all passes are requested up front: their latency hides
+    // behind the LDS round trips instead of being paid once per pass
+    bf16x8 rpre[BM / PR][NQ];
+    if constexpr (EPI == E_BIAS_RES || EPI == E_GELU_BWD) {
+#pragma unroll
+      for (int p = 0; p < BM / PR; ++p)
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int c = tid + q * NT, lr = c / (BN / 8), lc = (c % (BN / 8)) * 8;
+          rpre[p][q] = *reinterpret_cast<const bf16x8*>(R + (size_t)(m0 + p * PR + lr) * N + n0 + lc);
+        }
+    }
 #pragma unroll
     for (int p = 0; p < BM / PR; ++p) {
 #pragma unroll
@@ -368,7 +380,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
       }
       __syncthreads();
 #pragma unroll
-      for (int q = 0; q < PR * BN / 8 / NT; ++q) {
+      for (int q = 0; q < NQ; ++q) {
         const int c = tid + q * NT, lr = c / (BN / 8), lc = (c % (BN / 8)) * 8;
         const size_t row = m0 + p * PR + lr, col = n0 + lc, idx = row * (size_t)N + col;
         float v[8];
@@ -381,11 +393,11 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         }
         bf16x8 o;
         if constexpr (EPI == E_BIAS_RES) {
-          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + idx);
+          const bf16x8 rr = rpre[p][q];
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = (__bf16)(v[e] + (float)rr[e]);
         } else if constexpr (EPI == E_GELU_BWD) {
-          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + idx);
+          const bf16x8 rr = rpre[p][q];
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = (__bf16)(v[e] * gelu_grad_f((float)rr[e]));
         } else {
@@ -456,7 +468,12 @@ bf_status by_layout(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   return launch<TL, false, false, E_ACCUM, float>(a, st);
 }
 
-inline bool big_fits(int M, int N) { return M % 256 == 0 && N % 256 == 0 && (long)(M / 256) * (N / 256) >= 128; }
+// The 256 x 256 tile needs enough tiles that the last round over the 256 compute units is mostly full.
+inline bool big_fits(int M, int N) {
+  if (M % 256 || N % 256) return false;
+  const long tiles = (long)(M / 256) * (N / 256), rounds = (tiles + 255) / 256;
+  return tiles * 10 >= rounds * 256 * 8;
+}
 inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
 
 }  // namespace

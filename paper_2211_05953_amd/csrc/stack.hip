@@ -67,6 +67,7 @@ bool valid_config(const bf_config* c) {
   if (c->causal != 0 && c->causal != 1) { set_error("config: causal must be 0 or 1"); return false; }
   if (c->queue_depth < 0) { set_error("config: queue_depth < 0"); return false; }
   if (c->fuse_wgrad != 0 && c->fuse_wgrad != 1) { set_error("config: fuse_wgrad must be 0 or 1"); return false; }
+  if (c->N_loop_min < 0 || c->N_loop_min > c->N_layers) { set_error("config: N_loop_min outside 0..N_layers"); return false; }
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
   if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
   return true;
@@ -96,8 +97,10 @@ struct WsLayout {
   size_t n_full_records;
   size_t off_ckpt;         // LAYER: L * N_mb_max [T, h] tensors (outputs of each layer)
   size_t off_tmp;          // backward temporaries
-  size_t off_grec;         // fused weight gradient: L * N_mb_max records {dy, du, dx1, dqkv}
+  size_t off_grec;         // fused weight gradient: (layers per stage) * N_mb_max records {dy, du, dx1, dqkv}
   size_t grec_bytes;
+  size_t off_wrec;         // with checkpointing: as many records {a, ctx, c, g}, the recomputed wgrad operands
+  size_t wrec_bytes;
   size_t off_bhand;        // 2 x N_mb_max [T, h] (two sets, alternating by stage)
   size_t off_scratch_out;  // [T, h] x 2: discarded outputs / ping-pong
   size_t total;
@@ -130,7 +133,13 @@ TmpSizes tmp_sizes(const bf_config& c) {
 
 // The weight gradients of a stage can be taken as one product over all its micro-batches only
 // when every micro-batch's activations are still stored (no checkpointing).
-bool fuse_wgrad_possible(const bf_config& c) { return c.fuse_wgrad != 0 && c.ckpt_mode == BF_CKPT_NONE; }
+bool fuse_wgrad_possible(const bf_config& c) { return c.fuse_wgrad != 0; }
+
+// Most layers a stage can have (sizes the per-stage buffers of the fused weight gradient).
+int lps_max(const bf_config& c) {
+  const int nl = c.N_loop_min > 0 ? c.N_loop_min : 1;
+  return (c.N_layers + nl - 1) / nl;
+}
 
 void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
@@ -160,9 +169,14 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   Lo->off_tmp = off; off += tmp_sizes(c).total;
   {
     TmpSizes t = tmp_sizes(c);
+    RecSizes r = rec_sizes(c);
+    const size_t stage_slots = (size_t)lps_max(c) * c.N_mb_max;
     Lo->grec_bytes = t.ping + t.du + t.dx1 + t.dqkv;
     Lo->off_grec = off;
-    if (fuse_wgrad_possible(c)) off += slots * Lo->grec_bytes;
+    if (fuse_wgrad_possible(c)) off += stage_slots * Lo->grec_bytes;
+    Lo->wrec_bytes = r.a + r.ctx + r.c + r.g;
+    Lo->off_wrec = off;
+    if (fuse_wgrad_possible(c) && c.ckpt_mode == BF_CKPT_LAYER) off += stage_slots * Lo->wrec_bytes;
   }
   Lo->off_bhand = off; off += 2 * (size_t)c.N_mb_max * Lo->y_bytes;
   Lo->off_scratch_out = off; off += 2 * Lo->y_bytes;
@@ -239,12 +253,21 @@ struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float* delta; };
 // Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
 struct GradRec { char *dy, *du, *dx1, *dqkv; };
 
-GradRec grad_rec(bf_stack* s, int layer, int mb) {
+// ls: index of the layer inside its stage
+GradRec grad_rec(bf_stack* s, int ls, int mb) {
   TmpSizes t = tmp_sizes(s->cfg);
-  char* p = s->ws + s->Lo.off_grec + ((size_t)layer * s->cfg.N_mb_max + mb) * s->Lo.grec_bytes;
+  char* p = s->ws + s->Lo.off_grec + ((size_t)ls * s->cfg.N_mb_max + mb) * s->Lo.grec_bytes;
   GradRec g;
   g.dy = p; p += t.ping; g.du = p; p += t.du; g.dx1 = p; p += t.dx1; g.dqkv = p;
   return g;
+}
+
+// With checkpointing the recomputed a / ctx / c / g of (layer in stage ls, micro-batch mb) are written
+// here instead of the scratch record, so that they survive until the stage's weight-gradient products.
+void redirect_wgrad_operands(bf_stack* s, int ls, int mb, Record* R) {
+  RecSizes r = rec_sizes(s->cfg);
+  char* p = s->ws + s->Lo.off_wrec + ((size_t)ls * s->cfg.N_mb_max + mb) * s->Lo.wrec_bytes;
+  R->a = p; p += r.a; R->ctx = p; p += r.ctx; R->c = p; p += r.c; R->g = p;
 }
 
 Tmp tmp_of(bf_stack* s) {
@@ -406,15 +429,19 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
 // G = sum_m X_m^T dY_m is one long contraction, written once: no read-modify-write of the fp32
 // main-grad per micro-batch.  dy0 / dy_stride: the layer's incoming gradients, micro-batch 0 and
 // the distance (elements) between micro-batches.
-bf_status layer_wgrad_fused(bf_stack* s, int layer, int S_mb, int N_mb, const void* dy0, size_t dy_stride, hipStream_t st) {
+bf_status layer_wgrad_fused(bf_stack* s, int layer, int ls, int S_mb, int N_mb, const void* dy0, size_t dy_stride,
+                            hipStream_t st) {
   const bf_config& c = s->cfg;
   const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
-  const size_t es = 2;  // bf16 or fp32 handled through element strides below
-  (void)es;
   const size_t esz = c.dtype == BF_BF16 ? 2 : 4;
-  const Record R0 = record_for(s, layer, 0);
-  const GradRec K0 = grad_rec(s, layer, 0);
-  const size_t rec_stride = (s->Lo.rec_bytes + s->Lo.y_bytes) / esz, grec_stride = s->Lo.grec_bytes / esz;
+  Record R0 = record_for(s, layer, 0);
+  size_t rec_stride = (s->Lo.rec_bytes + s->Lo.y_bytes) / esz;
+  if (c.ckpt_mode == BF_CKPT_LAYER) {
+    redirect_wgrad_operands(s, ls, 0, &R0);
+    rec_stride = s->Lo.wrec_bytes / esz;
+  }
+  const GradRec K0 = grad_rec(s, ls, 0);
+  const size_t grec_stride = s->Lo.grec_bytes / esz;
   auto G = [&](int tid) { return param_ptr(s, s->g32, layer, tid); };
   auto run = [&](int M, int N, const void* A, const void* B, size_t sb, float* out) {
     GemmArgs g{M, N, T, A, B, out, nullptr, nullptr, nullptr, 0};
@@ -647,7 +674,7 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
   // gradients a stage received stay intact until its fused weight-gradient products have run
   auto bhand = [&](int stage, int m) { return s->ws + s->Lo.off_bhand + ((size_t)(stage & 1) * c.N_mb_max + m) * s->Lo.y_bytes; };
   char* scratch_out = s->ws + s->Lo.off_scratch_out;
-  const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c);
+  const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c) && per_stage <= lps_max(c);
 
   std::vector<SchedOp> ops;
   std::string why;
@@ -683,19 +710,22 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
       for (int l = l1 - 1; l >= l0; --l) {
         Record R = record_for(s, l, m);
         const void* xin = input_of(l, m);
-        if (c.ckpt_mode == BF_CKPT_LAYER) BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, st));
+        if (c.ckpt_mode == BF_CKPT_LAYER) {
+          if (fuse) redirect_wgrad_operands(s, l - l0, m, &R);
+          BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, st));
+        }
         // gradient in: caller's dy for the last layer, the hand-off buffer at a stage top, else the ping-pong
         // (with the fused weight gradient every layer's incoming gradient is kept per micro-batch instead)
         const void* din;
         if (l == c.N_layers - 1) din = (const char*)dy + (size_t)m * mb_bytes;
         else if (l == l1 - 1) din = bhand(op.stage, m);
-        else din = fuse ? grad_rec(s, l, m).dy : tmp.ping[(l + 1) & 1];
+        else din = fuse ? grad_rec(s, l - l0, m).dy : tmp.ping[(l + 1) & 1];
         void* dout;
         if (l == 0) dout = dx ? (char*)dx + (size_t)m * mb_bytes : scratch_out + s->Lo.y_bytes;
         else if (l == l0) dout = bhand(op.stage - 1, m);
-        else dout = fuse ? grad_rec(s, l - 1, m).dy : tmp.ping[l & 1];
+        else dout = fuse ? grad_rec(s, l - 1 - l0, m).dy : tmp.ping[l & 1];
         GradRec keep{};
-        if (fuse) keep = grad_rec(s, l, m);
+        if (fuse) keep = grad_rec(s, l - l0, m);
         BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, st));
         --live;
       }
@@ -706,8 +736,8 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
           size_t stride;
           if (l == c.N_layers - 1) { dy0 = dy; stride = mb_bytes / es; }
           else if (l == l1 - 1) { dy0 = bhand(op.stage, 0); stride = s->Lo.y_bytes / es; }
-          else { dy0 = grad_rec(s, l, 0).dy; stride = s->Lo.grec_bytes / es; }
-          BF_TRY(layer_wgrad_fused(s, l, S_mb, N_mb, dy0, stride, st));
+          else { dy0 = grad_rec(s, l - l0, 0).dy; stride = s->Lo.grec_bytes / es; }
+          BF_TRY(layer_wgrad_fused(s, l, l - l0, S_mb, N_mb, dy0, stride, st));
         }
       }
     }

@@ -97,15 +97,20 @@ def test_step_matches_oracle_in_both_orders(mode, dtype, ckpt, kernels, Lyr, N_l
     ("bf16", bf.BF_BF16, 4, 2, 256, 2, 1024, 256, 1, 4),
     ("bf16", bf.BF_BF16, 4, 4, 512, 4, 2048, 128, 2, 3),
 ])
-def test_fused_weight_gradient_in_breadth_first_order(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+@pytest.mark.parametrize("ckpt,loop_hint", [(bf.BF_CKPT_NONE, 0), (bf.BF_CKPT_LAYER, 0), (bf.BF_CKPT_LAYER, -1), (bf.BF_CKPT_NONE, -1)])
+def test_fused_weight_gradient_in_breadth_first_order(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, ckpt, loop_hint):
     """fuse_wgrad = 1: one weight-gradient product per stage over all micro-batches (BF only).
     Same sum, one long contraction: equal to the oracle within the tolerance, equal to the
     per-micro-batch accumulation up to fp32 rounding; DF ignores the flag."""
     b16 = dtype == bf.BF_BF16
     params = bf_inputs.make_params(13, Lyr, h, f, bf16=b16)
     x, dy = bf_inputs.make_batch(13, N_mb, S_mb, S_seq, h, bf16=b16)
-    fused = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1)
-    plain = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=0)
+    hint = N_loop if loop_hint < 0 else 0     # per-stage buffers sized exactly for this N_loop, or for any
+    fused = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, ckpt_mode=ckpt, N_loop_min=hint)
+    plain = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=0, ckpt_mode=ckpt)
+    if hint:
+        assert bf.bf_workspace_bytes(fused) <= bf.bf_workspace_bytes(
+            bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, ckpt_mode=ckpt))
     ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a)
     g_f = _run_gpu(fused, params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
     g_p = _run_gpu(plain, params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
@@ -117,6 +122,12 @@ def test_fused_weight_gradient_in_breadth_first_order(mode, dtype, Lyr, N_loop, 
             assert rel_err(g_f["grads"][l][name], g_p["grads"][l][name]) <= 2e-6, (l, name)
             assert np.array_equal(g_df["grads"][l][name], g_p["grads"][l][name]), (l, name)
     assert g_f["trace"] == g_p["trace"]
+    if hint and N_loop % 2 == 0:
+        # stages twice as large as the buffers were sized for: the step accumulates per micro-batch instead
+        g_big = _run_gpu(fused, params, x, dy, bf.BF_SCHED_BF, N_loop // 2, N_mb, S_mb)
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                assert np.array_equal(g_big["grads"][l][name], g_p["grads"][l][name]), (l, name)
 
 
 @pytest.mark.parametrize("mode,dtype", [("fp32", bf.BF_FP32), ("bf16", bf.BF_BF16)])
