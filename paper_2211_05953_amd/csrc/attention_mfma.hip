@@ -135,8 +135,9 @@ template <int D>
 __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                         float* __restrict__ lse, int S_seq, int N_heads, int causal,
                                                         float scale) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BLK * D];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[BLK * D];
+  // K/V tiles are double-buffered in LDS: tile j+1 (in registers since the previous iteration) is
+  // written to the idle stage while tile j is consumed, so an iteration has a single barrier.
+  __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int qblk = gridDim.x - 1 - blockIdx.x;  // longest rows first
   const int head = blockIdx.y, b = blockIdx.z;
@@ -157,17 +158,26 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
   TileRegs<BLK, D> kr, vr;
   kr.load(base + h, ld, tid);
   vr.load(base + 2 * h, ld, tid);
+  kr.store(KVs[0][0], tid);
+  vr.store(KVs[0][1], tid);
+  if (nblk > 1) {
+    kr.load(base + (size_t)BLK * ld + h, ld, tid);
+    vr.load(base + (size_t)BLK * ld + 2 * h, ld, tid);
+  }
+  __syncthreads();
   for (int j = 0; j < nblk; ++j) {
-    __syncthreads();  // previous block's readers are done
-    kr.store(Ks, tid);
-    vr.store(Vs, tid);
-    __syncthreads();
+    const bf16_t* Ks = KVs[j & 1][0];
+    const bf16_t* Vs = KVs[j & 1][1];
     if (j + 1 < nblk) {
-      kr.load(base + (size_t)(j + 1) * BLK * ld + h, ld, tid);
-      vr.load(base + (size_t)(j + 1) * BLK * ld + 2 * h, ld, tid);
+      kr.store(KVs[(j + 1) & 1][0], tid);
+      vr.store(KVs[(j + 1) & 1][1], tid);
+    }
+    if (j + 2 < nblk) {
+      kr.load(base + (size_t)(j + 2) * BLK * ld + h, ld, tid);
+      vr.load(base + (size_t)(j + 2) * BLK * ld + 2 * h, ld, tid);
     }
     const int kb = j * BLK;
-    if (causal && kb > qw + 31) continue;  // the whole tile is above this wave's diagonal
+    if (causal && kb > qw + 31) { __syncthreads(); continue; }  // the whole tile is above this wave's diagonal
     f32x16 s[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -221,6 +231,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
         for (int dt = 0; dt < D / 32; ++dt)
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Vs, 32 * t + 16 * k2, 32 * dt, lane), pb, o[dt], 0, 0, 0);
       }
+    __syncthreads();
   }
   l += __shfl_xor(l, 32, 64);
   store_rows<D>(o, ctx + ((size_t)b * S_seq + q) * h + head * D, lane, 1.0f / l);
@@ -247,8 +258,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
                                                            float scale) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BLK * D];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[BLK * D];
+  __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];  // double-buffered, one barrier per tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
@@ -270,17 +280,26 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
   TileRegs<BLK, D> kr, vr;
   kr.load(base + h, ld, tid);
   vr.load(base + 2 * h, ld, tid);
+  kr.store(KVs[0][0], tid);
+  vr.store(KVs[0][1], tid);
+  if (nblk > 1) {
+    kr.load(base + (size_t)BLK * ld + h, ld, tid);
+    vr.load(base + (size_t)BLK * ld + 2 * h, ld, tid);
+  }
+  __syncthreads();
   for (int j = 0; j < nblk; ++j) {
-    __syncthreads();
-    kr.store(Ks, tid);
-    vr.store(Vs, tid);
-    __syncthreads();
+    const bf16_t* Ks = KVs[j & 1][0];
+    const bf16_t* Vs = KVs[j & 1][1];
     if (j + 1 < nblk) {
-      kr.load(base + (size_t)(j + 1) * BLK * ld + h, ld, tid);
-      vr.load(base + (size_t)(j + 1) * BLK * ld + 2 * h, ld, tid);
+      kr.store(KVs[(j + 1) & 1][0], tid);
+      vr.store(KVs[(j + 1) & 1][1], tid);
+    }
+    if (j + 2 < nblk) {
+      kr.load(base + (size_t)(j + 2) * BLK * ld + h, ld, tid);
+      vr.load(base + (size_t)(j + 2) * BLK * ld + 2 * h, ld, tid);
     }
     const int kb = j * BLK;
-    if (causal && kb > qw + 31) continue;
+    if (causal && kb > qw + 31) { __syncthreads(); continue; }
     const bool diag = causal && kb + BLK - 1 > qw;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -306,6 +325,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
           dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Ks, 32 * t + 16 * k2, 32 * dt, lane), dsb, dq[dt], 0, 0, 0);
       }
     }
+    __syncthreads();
   }
   store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, scale);
 }
@@ -323,10 +343,8 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
                                                                 bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
                                                                 float scale) {
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[BLK * D];
-  __shared__ __attribute__((aligned(16))) bf16_t dOs[BLK * D];
-  __shared__ __attribute__((aligned(16))) float lse_s[BLK];
-  __shared__ __attribute__((aligned(16))) float delta_s[BLK];
+  __shared__ __attribute__((aligned(16))) bf16_t QOs[2][2][BLK * D];  // Q and dO tiles, double-buffered
+  __shared__ __attribute__((aligned(16))) float stat_s[2][2][BLK];    // lse * log2(e) and delta of the tile's queries
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int kg = w & 3;
   const bool dk_role = w >= 4;  // wave-uniform
@@ -354,19 +372,33 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
   dor.load(dob + (size_t)jbeg * BLK * h, h, tid);
   float lnext = 0.f, dnext = 0.f;
   if (tid < BLK) { lnext = lrow[jbeg * BLK + tid] * LOG2E; dnext = drow[jbeg * BLK + tid]; }
+  qr.store(QOs[0][0], tid);
+  dor.store(QOs[0][1], tid);
+  if (tid < BLK) { stat_s[0][0][tid] = lnext; stat_s[0][1][tid] = dnext; }
+  if (jbeg + 1 < nblk) {
+    qr.load(base + (size_t)(jbeg + 1) * BLK * ld, ld, tid);
+    dor.load(dob + (size_t)(jbeg + 1) * BLK * h, h, tid);
+    if (tid < BLK) { lnext = lrow[(jbeg + 1) * BLK + tid] * LOG2E; dnext = drow[(jbeg + 1) * BLK + tid]; }
+  }
+  __syncthreads();
   for (int j = jbeg; j < nblk; ++j) {
-    __syncthreads();
-    qr.store(Qs, tid);
-    dor.store(dOs, tid);
-    if (tid < BLK) { lse_s[tid] = lnext; delta_s[tid] = dnext; }
-    __syncthreads();
+    const int cur = (j - jbeg) & 1;
+    const bf16_t* Qs = QOs[cur][0];
+    const bf16_t* dOs = QOs[cur][1];
+    const float* lse_s = stat_s[cur][0];
+    const float* delta_s = stat_s[cur][1];
     if (j + 1 < nblk) {
-      qr.load(base + (size_t)(j + 1) * BLK * ld, ld, tid);
-      dor.load(dob + (size_t)(j + 1) * BLK * h, h, tid);
-      if (tid < BLK) { lnext = lrow[(j + 1) * BLK + tid] * LOG2E; dnext = drow[(j + 1) * BLK + tid]; }
+      qr.store(QOs[cur ^ 1][0], tid);
+      dor.store(QOs[cur ^ 1][1], tid);
+      if (tid < BLK) { stat_s[cur ^ 1][0][tid] = lnext; stat_s[cur ^ 1][1][tid] = dnext; }
+    }
+    if (j + 2 < nblk) {
+      qr.load(base + (size_t)(j + 2) * BLK * ld, ld, tid);
+      dor.load(dob + (size_t)(j + 2) * BLK * h, h, tid);
+      if (tid < BLK) { lnext = lrow[(j + 2) * BLK + tid] * LOG2E; dnext = drow[(j + 2) * BLK + tid]; }
     }
     const int qb = j * BLK;
-    if (causal && qb + BLK - 1 < kw) continue;  // every query of the tile is before this wave's keys
+    if (causal && qb + BLK - 1 < kw) { __syncthreads(); continue; }  // every query of the tile is before this wave's keys
     const bool diag = causal && qb < kw + 31;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -415,6 +447,7 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
         }
       }
     }
+    __syncthreads();
   }
   bf16_t* out = dqkv + ((size_t)b * S_seq + key) * ld + head * D;
   if (dk_role) store_rows<D>(acc, out + h, lane, scale);

@@ -160,7 +160,33 @@ __global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ d
 #pragma unroll
   for (int j = 0; j < VEC; ++j) a0[j] = a1[j] = 0.f;
   if (c0 < N) {
-    for (int t = ry; t < T_rows; t += RG) {
+    // UN rows in flight per thread: the loads of a batch are issued together, the sums keep their order
+    constexpr int UN = 8;
+    int t = ry;
+    for (; t + (UN - 1) * RG < T_rows; t += UN * RG) {
+      float d[UN][VEC], v[UN][VEC], mean[UN], rstd[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        load_vec<T, VEC>(dY + (size_t)(t + u * RG) * N + c0, d[u]);
+        if (MODE == 1) {
+          load_vec<T, VEC>(x + (size_t)(t + u * RG) * N + c0, v[u]);
+          mean[u] = stats[2 * (t + u * RG)];
+          rstd[u] = stats[2 * (t + u * RG) + 1];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          if (MODE == 1) {
+            a0[j] += d[u][j] * ((v[u][j] - mean[u]) * rstd[u]);
+            a1[j] += d[u][j];
+          } else {
+            a0[j] += d[u][j];
+          }
+        }
+    }
+    for (; t < T_rows; t += RG) {
       float d[VEC];
       load_vec<T, VEC>(dY + (size_t)t * N + c0, d);
       if (MODE == 1) {

@@ -1,8 +1,8 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
 //
 // One workgroup computes a BM x BN tile of C, stepping BK = 64 along K.  Each step's A and
-// B tiles are copied global -> registers -> LDS (16-byte accesses, double-buffered LDS, the
-// next tile's global loads in flight during the current tile's MFMAs).  Operands whose
+// B tiles are copied global -> registers -> LDS (16-byte buffer loads, double-buffered LDS, the
+// loads of tile kt+2 in flight during the MFMAs of tile kt).  Operands whose
 // global layout is K-contiguous sit in LDS as [row][BK] with the 16-byte chunk index
 // XOR-swizzled by row bits (conflict-free ds_read_b128 of MFMA fragments on the 64-bank LDS).  Operands whose
 // global layout has K as the slow dimension (B of the forward product, both operands of
@@ -13,7 +13,6 @@
 // Wave w of the workgroup owns a (BM / WM) x (BN / WN) sub-tile as MI x NI MFMA tiles of
 // 32 x 32.  Accumulator layout of one MFMA tile: lane l, register r holds
 // row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -33,9 +32,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 constexpr int BK = 64;
 constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
 
-template <int BM_, int BN_, int WM_, int WN_, int PIPE_ = 0>
+template <int BM_, int BN_, int WM_, int WN_>
 struct Tile {
-  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, PIPE = PIPE_;
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr int NT = WM * WN * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;
   static constexpr int MI = TM / 32, NI = TN / 32;
@@ -168,7 +167,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
   auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
   auto seg_b_of = [&](int kt) { return B + (size_t)(kt / nk_seg) * seg_b; };
   auto k0_of = [&](int kt) { return (kt % nk_seg) * BK; };
-  if constexpr (TL::PIPE == 2) {
+  {
     // One barrier per k-tile, placed between k-steps 2 and 3.  By then every wave holds its
     // k-step-3 fragments of the current stage in registers and has written tile kt+1 into the other
     // stage, so after the barrier k-step 3's MFMAs run while the k-step-0 fragments of the NEXT
@@ -191,16 +190,19 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
     };
     // mask: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write, 0x020 global read
-    auto interleave = [&](auto extra_mask, auto n_extra) {
+    auto interleave2 = [&](auto mask1, auto n1, auto mask2, auto n2) {
 #pragma unroll
       for (int i = 0; i < NMMA; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         if (i < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMMA - 1) / NMMA, 0);
-        if (decltype(n_extra)::value > 0 && i < decltype(n_extra)::value)
-          __builtin_amdgcn_sched_group_barrier(decltype(extra_mask)::value, 1, 0);
+        if (decltype(n1)::value > 0 && i < decltype(n1)::value)
+          __builtin_amdgcn_sched_group_barrier(decltype(mask1)::value, 1, 0);
+        if (decltype(n2)::value > 0 && i < decltype(n2)::value)
+          __builtin_amdgcn_sched_group_barrier(decltype(mask2)::value, 1, 0);
       }
       __builtin_amdgcn_sched_barrier(0);  // nothing moves across the end of a k-step
     };
+    auto interleave = [&](auto extra_mask, auto n_extra) { interleave2(extra_mask, n_extra, extra_mask, std::integral_constant<int, 0>{}); };
     constexpr int NCH = Stager<AK, BM, NT>::CHUNKS + Stager<BKC, BN, NT>::CHUNKS;
     typedef std::integral_constant<int, 0x200> MW;
     typedef std::integral_constant<int, 0x020> MG;
@@ -229,16 +231,20 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         sa.store(smem + (cur ^ 1) * STAGE);
         sb.store(smem + (cur ^ 1) * STAGE + A_ST);
       }
-      mma(0);
-      if constexpr (decltype(do_store)::value) interleave(MW{}, NC{}); else interleave(MW{}, N0{});
-      // k-step 1: the loads of tile kt+2 start
-      ldf(0, as, bs, 2);
       if constexpr (decltype(do_load)::value) {
+        // the registers are free again as soon as their LDS store has issued: the loads of tile kt+2
+        // follow at once, a full k-tile ahead of their use
         sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
         sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2));
       }
+      mma(0);
+      if constexpr (decltype(do_load)::value) interleave2(MW{}, NC{}, MG{}, NC{});
+      else if constexpr (decltype(do_store)::value) interleave(MW{}, NC{});
+      else interleave(MW{}, N0{});
+      // k-step 1
+      ldf(0, as, bs, 2);
       mma(1);
-      if constexpr (decltype(do_load)::value) interleave(MG{}, NC{}); else interleave(MG{}, N0{});
+      interleave(MW{}, N0{});
       // k-step 2
       ldf(1, as, bs, 3);
       mma(0);
@@ -254,85 +260,6 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     if (kt + 1 < nk) { iter(kt, std::true_type{}, std::false_type{}); ++kt; }
     iter(kt, std::false_type{}, std::false_type{});
     __syncthreads();
-  } else if (TL::PIPE == 0) {
-    sa.load(A, lda, m0, 0);
-    sb.load(B, ldb, n0, 0);
-    sa.store(smem);
-    sb.store(smem + A_ST);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < nk) {
-        sa.load(seg_a_of(kt + 1), lda, m0, k0_of(kt + 1));
-        sb.load(seg_b_of(kt + 1), ldb, n0, k0_of(kt + 1));
-      }
-      const bf16_t* as = smem + cur * STAGE;
-      const bf16_t* bs = as + A_ST;
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 af[MI], bfr[NI];
-#pragma unroll
-        for (int i = 0; i < MI; ++i) af[i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk, lane);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (kt + 1 < nk) {
-        sa.store(smem + (cur ^ 1) * STAGE);
-        sb.store(smem + (cur ^ 1) * STAGE + A_ST);
-      }
-      __syncthreads();
-    }
-  } else {
-    // Tile kt+1 sits in registers when iteration kt starts (loaded one iteration earlier): it goes to
-    // the idle LDS stage first, the loads of tile kt+2 follow, and the fragments of k-step kk+1
-    // are requested before the MFMAs of k-step kk.
-    sa.load(A, lda, m0, 0);
-    sb.load(B, ldb, n0, 0);
-    sa.store(smem);
-    sb.store(smem + A_ST);
-    if (nk > 1) {
-      sa.load(seg_a_of(1), lda, m0, k0_of(1));
-      sb.load(seg_b_of(1), ldb, n0, k0_of(1));
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      const bf16_t* as = smem + cur * STAGE;
-      const bf16_t* bs = as + A_ST;
-      bf16x8 af[2][MI], bfr[2][NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[0][i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, 0, lane);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[0][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, 0, lane);
-      if (kt + 1 < nk) {
-        sa.store(smem + (cur ^ 1) * STAGE);
-        sb.store(smem + (cur ^ 1) * STAGE + A_ST);
-      }
-      if (kt + 2 < nk) {
-        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
-        sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2));
-      }
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        const int cb = kk & 1, nb = cb ^ 1;
-        if (kk + 1 < BK / 16) {
-#pragma unroll
-          for (int i = 0; i < MI; ++i) af[nb][i] = load_frag<AK, BM>(as, wm * TL::TM + i * 32, kk + 1, lane);
-#pragma unroll
-          for (int j = 0; j < NI; ++j) bfr[nb][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 32, kk + 1, lane);
-        }
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NI; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
-      }
-      __syncthreads();
-    }
   }
 
   if constexpr (EPI == E_ACCUM) {
@@ -417,11 +344,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
   }
 }
 
-int g_variant = 0;  // experiment switch (BF_GEMM_VARIANT): low bits pick the big tile, bit 4 turns the XCD remap off
-typedef Tile<256, 256, 2, 4, 2> TileBig;  // 8 waves, 128 x 64 per wave, mid-tile barrier + pinned interleave
-typedef Tile<256, 256, 2, 2, 1> TileBig4;   // 4 waves, 128 x 128 per wave, pipelined
-typedef Tile<256, 256, 2, 4, 1> TileBigP;   // 8 waves, 128 x 64 per wave, barrier at the end of the tile
-typedef Tile<128, 128, 2, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
+typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave
+typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
 
 template <typename TL, bool AK, bool BKC>
 constexpr size_t lds_bytes() { return 2 * (size_t)(stage_elems<AK, TL::BM>() + stage_elems<BKC, TL::BN>()) * sizeof(bf16_t); }
@@ -437,7 +361,7 @@ bf_status launch(const GemmArgs& a, hipStream_t st) {
     attr_set = true;
   }
   const int tiles_m = a.M / TL::BM, tiles_n = a.N / TL::BN;
-  const int remap = ((tiles_m * tiles_n) % 8 == 0 && !(g_variant & 16)) ? 1 : 0;
+  const int remap = (tiles_m * tiles_n) % 8 == 0 ? 1 : 0;
   kern<<<tiles_m * tiles_n, TL::NT, lds, st>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.B, (TO*)a.C, a.bias,
                                                 (const TO*)a.R, (TO*)a.C2, a.accumulate, tiles_m, remap, a.n_seg > 1 ? a.n_seg : 1,
                                                 a.seg_stride_a, a.seg_stride_b);
@@ -494,13 +418,7 @@ bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
-  static bool read_env = false;
-  if (!read_env) { const char* e = getenv("BF_GEMM_VARIANT"); g_variant = e ? atoi(e) : 0; read_env = true; }
-  if (big_fits(a.M, a.N)) {
-    if ((g_variant & 15) == 1) return by_layout<TileBig4>(layout, epi, a, st);
-    if ((g_variant & 15) == 3) return by_layout<TileBigP>(layout, epi, a, st);
-    return by_layout<TileBig>(layout, epi, a, st);
-  }
+  if (big_fits(a.M, a.N)) return by_layout<TileBig>(layout, epi, a, st);
   return by_layout<TileSmall>(layout, epi, a, st);
 }
 
