@@ -107,6 +107,21 @@ __device__ __forceinline__ void load_rowfrags(const bf16_t* __restrict__ row, in
   for (int kk = 0; kk < D / 16; ++kk) f[kk] = *reinterpret_cast<const bf16x8*>(row + kk * 16 + 8 * (lane >> 5));
 }
 
+// Scheduling hint for a run of NMMA MFMAs that each consume RPM LDS reads: the reads run AHEAD
+// MFMAs in front of their use (an LDS read takes a few MFMA times to return), then nothing moves
+// across the end of the run.
+template <int NMMA, int RPM, int AHEAD>
+__device__ __forceinline__ void mfma_lds_pipeline() {
+  __builtin_amdgcn_sched_group_barrier(0x100, AHEAD * RPM, 0);
+#pragma unroll
+  for (int i = 0; i < NMMA - AHEAD; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 __device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -133,14 +148,16 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], bf16_t* 
 // ------------------------------------------------------------------------------ forward
 template <int D>
 __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
-                                                        float* __restrict__ lse, int S_seq, int N_heads, int causal,
+                                                        float* __restrict__ lse, int S_seq, int N_heads, int S_mb, int causal,
                                                         float scale) {
   // K/V tiles are double-buffered in LDS: tile j+1 (in registers since the previous iteration) is
   // written to the idle stage while tile j is consumed, so an iteration has a single barrier.
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int qblk = gridDim.x - 1 - blockIdx.x;  // longest rows first
-  const int head = blockIdx.y, b = blockIdx.z;
+  // 1-D grid ordered by work: the last (longest) query block of every head first, then the next ...
+  const int nhb = N_heads * S_mb;
+  const int qblk = S_seq / WG_ROWS - 1 - blockIdx.x / nhb;
+  const int head = (blockIdx.x % nhb) % N_heads, b = (blockIdx.x % nhb) / N_heads;
   const int h = N_heads * D;
   const size_t ld = 3 * (size_t)h;
   const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
@@ -178,14 +195,14 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
     }
     const int kb = j * BLK;
     if (causal && kb > qw + 31) { __syncthreads(); continue; }  // the whole tile is above this wave's diagonal
-    f32x16 s[2];
+    f32x16 s[2] = {zero16(), zero16()};
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      s[t] = zero16();
+    for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk)
+      for (int t = 0; t < 2; ++t)
         s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s[t], 0, 0, 0);
-    }
+    mfma_lds_pipeline<2 * (D / 16), 1, 4>();
     // Online softmax on the raw scores: m is the running max of the unscaled scores, the scale
     // 1/sqrt(S_head) log2(e) enters through one fma per element, the exponentials are the
     // hardware exp2 (arguments <= 0; masked scores are -inf and give exactly 0).
@@ -222,15 +239,20 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
       m = mx;
     }
     l += sum;
+    bf16x8 pb[2][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        const bf16x8 pb = pack8(s[t], k2);
+      for (int k2 = 0; k2 < 2; ++k2) pb[t][k2] = pack8(s[t], k2);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Vs, 32 * t + 16 * k2, 32 * dt, lane), pb, o[dt], 0, 0, 0);
-      }
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Vs, 32 * t + 16 * k2, 32 * dt, lane), pb[t][k2], o[dt], 0, 0, 0);
+    mfma_lds_pipeline<4 * (D / 32), 2, 4>();
     __syncthreads();
   }
   l += __shfl_xor(l, 32, 64);
@@ -256,12 +278,13 @@ __global__ __launch_bounds__(NTHR) void attn_delta_kernel(const bf16_t* __restri
 template <int D>
 __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
+                                                           bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb, int causal,
                                                            float scale) {
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];  // double-buffered, one barrier per tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int qblk = gridDim.x - 1 - blockIdx.x;
-  const int head = blockIdx.y, b = blockIdx.z;
+  const int nhb = N_heads * S_mb;
+  const int qblk = S_seq / WG_ROWS - 1 - blockIdx.x / nhb;  // longest query blocks of every head first
+  const int head = (blockIdx.x % nhb) % N_heads, b = (blockIdx.x % nhb) / N_heads;
   const int h = N_heads * D;
   const size_t ld = 3 * (size_t)h;
   const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
@@ -304,11 +327,13 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       f32x16 s = zero16(), dp = zero16();
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Vs, 32 * t, kk, lane), dof[kk], dp, 0, 0, 0);
       }
+      mfma_lds_pipeline<2 * (D / 16), 1, 4>();
       // p = exp(s/sqrt(d) - lse); dS = p (dP - delta) (the factor 1/sqrt(d) is applied once, to dQ)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2)) * (dp[r] - dl);
@@ -317,13 +342,14 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
         for (int r = 0; r < 16; ++r)
           if (kb + 32 * t + acc_row(r, lane) > q) s[r] = 0.f;
       }
+      const bf16x8 dsb[2] = {pack8(s, 0), pack8(s, 1)};
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        const bf16x8 dsb = pack8(s, k2);
+      for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
-          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Ks, 32 * t + 16 * k2, 32 * dt, lane), dsb, dq[dt], 0, 0, 0);
-      }
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Ks, 32 * t + 16 * k2, 32 * dt, lane), dsb[k2], dq[dt], 0, 0, 0);
+      mfma_lds_pipeline<2 * (D / 32), 2, 4>();
     }
     __syncthreads();
   }
@@ -341,15 +367,16 @@ constexpr int NTHR_DKV = 512;
 template <int D>
 __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int causal,
+                                                                bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb, int causal,
                                                                 float scale) {
   __shared__ __attribute__((aligned(16))) bf16_t QOs[2][2][BLK * D];  // Q and dO tiles, double-buffered
   __shared__ __attribute__((aligned(16))) float stat_s[2][2][BLK];    // lse * log2(e) and delta of the tile's queries
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int kg = w & 3;
   const bool dk_role = w >= 4;  // wave-uniform
-  const int kblk = blockIdx.x;  // earliest keys see the most queries: they go first
-  const int head = blockIdx.y, b = blockIdx.z;
+  const int nhb = N_heads * S_mb;
+  const int kblk = blockIdx.x / nhb;  // earliest keys see the most queries: those blocks of every head go first
+  const int head = (blockIdx.x % nhb) % N_heads, b = (blockIdx.x % nhb) / N_heads;
   const int h = N_heads * D;
   const size_t ld = 3 * (size_t)h;
   const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
@@ -403,10 +430,12 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       f32x16 s = zero16();
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk)
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Qs, 32 * t, kk, lane), kf[kk], s, 0, 0, 0);
       if (!dk_role) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Qs, 32 * t, kk, lane), kf[kk], s, 0, 0, 0);
+        mfma_lds_pipeline<D / 16, 1, 4>();
         // P = exp(S / sqrt(d) - lse);  dV += dO^T P
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse_s[32 * t + acc_row(r, lane)]));
@@ -415,19 +444,24 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
           for (int r = 0; r < 16; ++r)
             if (key > qb + 32 * t + acc_row(r, lane)) s[r] = 0.f;
         }
+        const bf16x8 pb[2] = {pack8(s, 0), pack8(s, 1)};
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-          const bf16x8 pb = pack8(s, k2);
+        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(dOs, 32 * t + 16 * k2, 32 * dt, lane), pb, acc[dt], 0, 0, 0);
-        }
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(dOs, 32 * t + 16 * k2, 32 * dt, lane), pb[k2], acc[dt], 0, 0, 0);
+        mfma_lds_pipeline<2 * (D / 32), 2, 4>();
       } else {
         // dP = dO V^T;  dS = P (dP - delta) (the factor 1/sqrt(d) is applied once, to dK);  dK += Q^T dS
         f32x16 dp = zero16();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
+        for (int kk = 0; kk < D / 16; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Qs, 32 * t, kk, lane), kf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(dOs, 32 * t, kk, lane), vf[kk], dp, 0, 0, 0);
+        }
+        mfma_lds_pipeline<2 * (D / 16), 1, 4>();
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int ql = 32 * t + acc_row(r, lane);
@@ -438,13 +472,14 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
           for (int r = 0; r < 16; ++r)
             if (key > qb + 32 * t + acc_row(r, lane)) s[r] = 0.f;
         }
+        const bf16x8 dsb[2] = {pack8(s, 0), pack8(s, 1)};
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-          const bf16x8 dsb = pack8(s, k2);
+        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Qs, 32 * t + 16 * k2, 32 * dt, lane), dsb, acc[dt], 0, 0, 0);
-        }
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Qs, 32 * t + 16 * k2, 32 * dt, lane), dsb[k2], acc[dt], 0, 0, 0);
+        mfma_lds_pipeline<2 * (D / 32), 2, 4>();
       }
     }
     __syncthreads();
@@ -456,8 +491,8 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
 
 template <int D>
 bf_status fwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, void* ctx, float* lse, hipStream_t st) {
-  dim3 grid(S_seq / WG_ROWS, N_heads, S_mb);
-  attn_fwd_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, causal, 1.0f / sqrtf((float)D));
+  const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
+  attn_fwd_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, S_mb, causal, 1.0f / sqrtf((float)D));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_fwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
@@ -468,9 +503,9 @@ bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, c
                 const void* dctx, void* dqkv, float* delta, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   attn_delta_kernel<D><<<dim3(S_seq / 4, N_heads, S_mb), NTHR, 0, st>>>((const bf16_t*)ctx, (const bf16_t*)dctx, delta, S_seq, N_heads);
-  dim3 grid(S_seq / WG_ROWS, N_heads, S_mb);
-  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
-  attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, causal, scale);
+  const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
+  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+  attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
