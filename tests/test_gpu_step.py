@@ -159,6 +159,47 @@ def test_two_optimizer_steps(mode, dtype, schedule):
                     assert np.abs(upd - upd_ref).max() <= 1e-3 * adam["lr"] + 2e-7 * np.abs(params[l][name]).max()
 
 
+@pytest.mark.parametrize("mode,dtype,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", [
+    ("fp32", bf.BF_FP32, 3, 3, 72, 3, 200, 50, 2, 3),          # generic kernels
+    ("bf16", bf.BF_BF16, 4, 2, 256, 2, 1024, 256, 1, 4),       # MFMA kernels
+    ("bf16", bf.BF_BF16, 2, 1, 512, 4, 2048, 128, 2, 3),
+])
+def test_optimizer_step_after_the_fused_weight_gradient(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+    """Breadth-first with fuse_wgrad = 1 and the optimizer on (the configuration the benchmark times),
+    with weight decay: every parameter moves exactly once per step, the main-grads stay readable, and
+    the result is the oracle's (Sec. 4.2, per-stage update)."""
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(17, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(17, N_mb, S_mb, S_seq, h, bf16=b16)
+    adam = {k: float(np.float32(v)) for k, v in dict(lr=1e-3, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.01).items()}
+    mk = lambda fuse: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, lr=adam["lr"],
+                                     weight_decay=adam["weight_decay"], fuse_wgrad=fuse)
+    for steps in (1, 2):
+        fused = _run_gpu(mk(1), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        plain = _run_gpu(mk(0), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a, adam=adam, steps=steps)
+        tol = TOL[mode] * (1 if steps == 1 else 20)
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                g_ref = ref["grads"][l][name].reshape(-1)
+                m_ref, v_ref = (t.reshape(-1) for t in ref["new_adam_state"][l][name])
+                assert rel_err(fused["grads"][l][name], g_ref) <= tol, (steps, l, name)
+                assert rel_err(fused["m"][l][name], m_ref) <= tol, (steps, l, name)
+                assert rel_err(fused["v"][l][name], v_ref) <= 2 * tol, (steps, l, name)
+                if steps == 1:
+                    # same gradients up to fp32 summation order: same moments, same -lr * sign(g) moves
+                    assert rel_err(fused["m"][l][name], plain["m"][l][name]) <= 1e-5, (l, name)
+                    assert rel_err(fused["v"][l][name], plain["v"][l][name]) <= 2e-5, (l, name)
+                    big = np.abs(g_ref) > 1e-2 * np.abs(g_ref).max()
+                    w0 = params[l][name].reshape(-1)
+                    upd = (fused["params"][l][name].astype(np.float64) - w0)[big]
+                    upd_ref = (ref["new_params"][l][name].reshape(-1) - w0)[big]
+                    assert np.abs(upd - upd_ref).max() <= 1e-3 * adam["lr"] + 2e-7 * np.abs(w0).max(), (l, name)
+                    # no parameter was skipped or stepped twice
+                    moved = np.abs(fused["params"][l][name].astype(np.float64) - w0)[big]
+                    assert moved.min() > 0.5 * adam["lr"] and moved.max() < 1.5 * adam["lr"], (l, name)
+
+
 def test_run_step_argument_errors():
     cfg = bf.make_config(64, 2, 256, 16, 4, 2, 1, dtype=bf.BF_FP32)
     st = bf.Stack(cfg)
