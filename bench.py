@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--no-df", action="store_true")
     ap.add_argument("--no-fuse-wgrad", action="store_true",
                     help="accumulate weight gradients per micro-batch in BF order too (default: one product per stage)")
+    ap.add_argument("--no-dp-fs", action="store_true",
+                    help="skip the fully-sharded (dp_fs = 1) BF and DF steps reported under \"dp_fs\"")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run a 1 GiB device copy (known HBM traffic) so that FETCH_SIZE / WRITE_SIZE "
                          "readings of a rocprofv3 --pmc run of this command can be scaled")
@@ -180,6 +182,27 @@ def main():
         "roofline": roofline,
     }
     st.close()
+    del st
+    torch.cuda.empty_cache()
+    if b16 and not args.no_dp_fs:
+        # the same step with the bf16 weights rebuilt per interval of use into a two-stage double buffer
+        # (Sec. 3.1, App. D.1): BF rebuilds a stage twice per step, DF twice per micro-batch
+        cfg.dp_fs = 1
+        fs = bf.Stack(cfg, device="cuda:0")
+        out_fs = {}
+        for name, sched, k in (("bf", bf.BF_SCHED_BF, min(args.steps, 3)), ("df", bf.BF_SCHED_DF, min(args.steps, 2))):
+            if name == "df" and args.no_df:
+                continue
+            sec, reps = time_steps(fs, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, k, 1, 2)
+            rp = reps[-1]
+            i = bf.binding.KERNEL_CLASSES.index("reconstruct")
+            out_fs[name] = {"ms_per_step": sec * 1e3, "model_tflops": rp.flops_model / sec / 1e12,
+                            "n_weight_intervals": rp.n_weight_intervals, "n_reconstruct": rp.n_reconstruct,
+                            "reconstruct_bytes": rp.reconstruct_bytes, "reconstruct_ms": rp.kernel_ms[i],
+                            "weight_buffer_bytes": rp.weight_buffer_bytes, "state_bytes": rp.state_bytes}
+        line["dp_fs"] = out_fs
+        fs.close()
+        del fs
     del x, dy, y, dx
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -78,6 +78,15 @@ typedef struct {
   int32_t N_loop_min;   /* smallest N_loop bf_run_step will be called with (0 or 1: any).  Sizes the per-stage
                            buffers of fuse_wgrad for ceil(N_layers / N_loop_min) layers; a step whose stages
                            are larger than that accumulates per micro-batch instead. */
+  int32_t dp_fs;        /* 1 (bf16 only): fully sharded data parallelism as one GPU can show it (Sec. 3.1, App. D.1).
+                           The low-precision weights are not kept resident: the stack holds a double buffer of two
+                           stages (each ceil(N_layers / N_loop_min) layers) and reconstructs a stage's bf16 weights
+                           from the fp32 master copy (the rank's shard; with one rank, all of it) into the idle
+                           half before the stage is used, on the side stream, while the other half computes.
+                           A stage still resident in a half is not reconstructed again.  Results are bit-identical
+                           to dp_fs = 0; bf_step_report counts the reconstructions (breadth-first: one forward and
+                           one backward interval per stage; depth-first: as many per micro-batch, Sec. 4.2).
+                           Stages larger than a half: BF_EINVAL from bf_run_step. */
   uint64_t seed;        /* device-side initialisation: weights ~ N(0, init_std), biases 0, LN gain 1 */
   float init_std;
   float ln_eps;
@@ -96,7 +105,8 @@ typedef enum {
   BF_K_GEMM_WGRAD = 2, /* G += X^T dY into the fp32 main-grad */
   BF_K_ATTN_FWD = 3, BF_K_ATTN_BWD = 4,
   BF_K_LN_FWD = 5, BF_K_LN_BWD = 6, BF_K_COLSUM = 7, BF_K_ADAM = 8,
-  BF_N_KERNEL_CLASSES = 9
+  BF_K_RECONSTRUCT = 9, /* dp_fs: fp32 master -> bf16 stage weights into a half of the double buffer */
+  BF_N_KERNEL_CLASSES = 10
 } bf_kernel_class;
 
 typedef struct {
@@ -119,6 +129,14 @@ typedef struct {
   double kernel_flops[BF_N_KERNEL_CLASSES];
   double kernel_bytes[BF_N_KERNEL_CLASSES];
   int64_t kernel_launches[BF_N_KERNEL_CLASSES];
+  /* dp_fs = 1 (else 0): contiguous runs of ops on one stage in one direction, each of which needs the
+   * stage's weights (the paper's count of reconstructions: 2 N_loop breadth-first, 2 N_loop N_mb
+   * depth-first at N_PP = 1); reconstructions actually run (a stage found in the double buffer is
+   * reused); bytes they moved (4 read + 2 written per parameter); size of the double buffer. */
+  int64_t n_weight_intervals;
+  int64_t n_reconstruct;
+  int64_t reconstruct_bytes;
+  int64_t weight_buffer_bytes;
 } bf_step_report;
 
 typedef struct {
@@ -143,7 +161,8 @@ bf_status bf_destroy_stack(bf_stack* s);
 size_t bf_tensor_elems(const bf_stack* s, int tensor_id);
 
 /* Copy n = bf_tensor_elems fp32 values between host memory and the fp32 master weights
- * (set also refreshes the low-precision copy and leaves the Adam moments alone).
+ * (set also refreshes the low-precision copy, or with dp_fs drops what the double buffer
+ * holds, and leaves the Adam moments alone).
  * Synchronous.  BF_EINVAL on a bad layer / tensor / n. */
 bf_status bf_set_params(bf_stack* s, int layer, int tensor_id, const float* host_src, size_t n);
 bf_status bf_get_params(bf_stack* s, int layer, int tensor_id, float* host_dst, size_t n);

@@ -125,3 +125,38 @@ def simulate(kind, N_PP, N_loop, N_mb, t_fwd=1, t_bwd=2):
         peak_live.append(peak)
     return dict(makespan=makespan, busy=busy, bubble=Fraction(makespan - busy, busy),
                 peak_live=peak_live, events=events)
+
+
+def weight_intervals(ops):
+    """Intervals over which a device needs one stage's weights: maximal runs of consecutive
+    ops of one stage in one direction.  With fully sharded data parallelism the stage is
+    reconstructed for each such interval (Sec. 3.1: before every use, forward and backward);
+    breadth-first has one forward and one backward interval per stage, the other orders
+    repeat them per micro-batch or micro-batch sequence (Sec. 4.2).
+    Returns the list of (op, stage, first index, length)."""
+    out = []
+    for i, (op, stage, _m) in enumerate(ops):
+        if out and out[-1][0] == op and out[-1][1] == stage:
+            out[-1][3] += 1
+        else:
+            out.append([op, stage, i, 1])
+    return [tuple(v) for v in out]
+
+
+def reconstructions(ops, n_buffers=2, resident=()):
+    """Reconstructions a device runs when it keeps the weights of the n_buffers most recently
+    used stages (App. D.1: a double buffer, one half computing while the other is restored):
+    an interval whose stage is still held costs nothing, otherwise the stage replaces the one
+    unused for longest.  `resident`: stages held at the start, least recently used first.
+    Returns (count, stages held at the end in the same order)."""
+    held = list(resident)[-n_buffers:]
+    count = 0
+    for _op, stage, _i, _n in weight_intervals(ops):
+        if stage in held:
+            held.remove(stage)
+        else:
+            count += 1
+            if len(held) == n_buffers:
+                held.pop(0)
+        held.append(stage)
+    return count, tuple(held)

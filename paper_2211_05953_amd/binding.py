@@ -21,7 +21,7 @@ TENSOR_IDS = {"ln1_g": 0, "ln1_b": 1, "w_qkv": 2, "b_qkv": 3, "w_o": 4, "b_o": 5
 class bf_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("S_hidden", "N_heads", "S_head", "S_mlp", "S_seq", "N_layers", "N_mb_max",
                                          "S_mb_max", "dtype", "ckpt_mode", "causal", "kernels", "queue_depth",
-                                         "fuse_wgrad", "N_loop_min")] + \
+                                         "fuse_wgrad", "N_loop_min", "dp_fs")] + \
                [("seed", C.c_uint64)] + \
                [(n, C.c_float) for n in ("init_std", "ln_eps", "lr", "beta1", "beta2", "adam_eps", "weight_decay")]
 
@@ -34,11 +34,13 @@ class bf_step_report(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("gpu_ms", "adam_ms", "flops_model", "flops_paper", "flops_executed")] + \
                [(n, C.c_int64) for n in ("peak_ckpt_count", "peak_ckpt_bytes", "peak_act_bytes", "state_bytes")] + \
                [("n_events", C.c_int32), ("timed", C.c_int32)] + \
-               [("kernel_ms", C.c_double * 9), ("kernel_flops", C.c_double * 9), ("kernel_bytes", C.c_double * 9),
-                ("kernel_launches", C.c_int64 * 9)]
+               [("kernel_ms", C.c_double * 10), ("kernel_flops", C.c_double * 10), ("kernel_bytes", C.c_double * 10),
+                ("kernel_launches", C.c_int64 * 10)] + \
+               [(n, C.c_int64) for n in ("n_weight_intervals", "n_reconstruct", "reconstruct_bytes", "weight_buffer_bytes")]
 
 
-KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam")
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam",
+                  "reconstruct")
 
 
 class bf_sched_stats(C.Structure):
@@ -122,10 +124,10 @@ def _stream():
 
 
 def make_config(S_hidden, N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype=BF_BF16, ckpt_mode=BF_CKPT_NONE,
-                causal=1, kernels=BF_KERNELS_AUTO, queue_depth=0, fuse_wgrad=0, N_loop_min=0, seed=0x221105953, init_std=0.02, ln_eps=1e-5,
+                causal=1, kernels=BF_KERNELS_AUTO, queue_depth=0, fuse_wgrad=0, N_loop_min=0, dp_fs=0, seed=0x221105953, init_std=0.02, ln_eps=1e-5,
                 lr=1e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0):
     return bf_config(S_hidden, N_heads, S_hidden // N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype,
-                     ckpt_mode, causal, kernels, queue_depth, fuse_wgrad, N_loop_min, seed, init_std, ln_eps, lr, beta1, beta2, adam_eps,
+                     ckpt_mode, causal, kernels, queue_depth, fuse_wgrad, N_loop_min, dp_fs, seed, init_std, ln_eps, lr, beta1, beta2, adam_eps,
                      weight_decay)
 
 

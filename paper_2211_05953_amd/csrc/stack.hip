@@ -4,6 +4,7 @@
 // Workspace layout (all offsets 256-byte aligned, everything pre-allocated, App. D.2):
 //   w32 | m | v | g32           fp32 master weights, Adam moments, main-grads  [P_total each]
 //   w_lp                        bf16 copy of the weights (bf16 mode only)        [P_total]
+//                               (dp_fs: a double buffer of two stages instead, App. D.1)
 //   records                     stored activations, one record per (layer, micro-batch)
 //                               (BF_CKPT_NONE) or one checkpoint per (layer, micro-batch)
 //                               plus a single scratch record (BF_CKPT_LAYER)
@@ -68,6 +69,8 @@ bool valid_config(const bf_config* c) {
   if (c->queue_depth < 0) { set_error("config: queue_depth < 0"); return false; }
   if (c->fuse_wgrad != 0 && c->fuse_wgrad != 1) { set_error("config: fuse_wgrad must be 0 or 1"); return false; }
   if (c->N_loop_min < 0 || c->N_loop_min > c->N_layers) { set_error("config: N_loop_min outside 0..N_layers"); return false; }
+  if (c->dp_fs != 0 && c->dp_fs != 1) { set_error("config: dp_fs must be 0 or 1"); return false; }
+  if (c->dp_fs && c->dtype != BF_BF16) { set_error("config: dp_fs reconstructs bf16 weights: dtype must be BF_BF16"); return false; }
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
   if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
   return true;
@@ -91,6 +94,7 @@ struct Record {
 struct WsLayout {
   size_t P_total;
   size_t off_w32, off_m, off_v, off_g32, off_wlp;
+  size_t half_bytes;       // dp_fs: one half of the weight double buffer
   size_t rec_bytes;        // one full record (without y)
   size_t y_bytes;          // one [T, h] tensor
   size_t off_records;      // NONE: L * N_mb_max full records (each with y); LAYER: 1 scratch record
@@ -151,7 +155,9 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   Lo->off_v = off; off += up(Lo->P_total * 4);
   Lo->off_g32 = off; off += up(Lo->P_total * 4);
   Lo->off_wlp = off;
-  if (c.dtype == BF_BF16) off += up(Lo->P_total * 2);
+  Lo->half_bytes = up((size_t)lps_max(c) * D.layer_elems * 2);
+  if (c.dp_fs) off += 2 * Lo->half_bytes;  // double buffer of two stages instead of every layer's copy
+  else if (c.dtype == BF_BF16) off += up(Lo->P_total * 2);
   Lo->rec_bytes = rec_sizes(c).total;
   Lo->y_bytes = up(T * c.S_hidden * es);
   Lo->off_records = off;
@@ -194,8 +200,14 @@ struct bf_stack {
   WsLayout Lo;
   char* ws;
   float *w32, *m, *v, *g32;
-  bf16_t* wlp;
-  hipStream_t side;       // Adam stream
+  bf16_t* wlp;            // resident bf16 copy (null in fp32 mode and with dp_fs)
+  // dp_fs: the two halves of the weight buffer, the first layer / layer count each holds (-1: nothing
+  // valid), the half and first layer the op being issued reads, and the events that order the halves
+  bf16_t* fs_half[2];
+  int fs_l0[2], fs_n[2];
+  int fs_cur, fs_cur_l0;
+  hipEvent_t fs_ready[2], fs_free[2];
+  hipStream_t side;       // Adam and weight-reconstruction stream
   hipEvent_t ev_grad_ready, ev_side_done, ev_t0, ev_t1;
   std::vector<hipEvent_t> adam_ev;   // pairs of events per stage for timing
   std::vector<hipEvent_t> queue_ev;  // ring for the bounded launch queue
@@ -219,6 +231,8 @@ float* param_ptr(bf_stack* s, float* arena, int layer, int tid) {
 
 // weight operand of the GEMMs: bf16 copy in bf16 mode, the master itself in fp32 mode
 const void* weight_ptr(bf_stack* s, int layer, int tid) {
+  if (s->cfg.dp_fs)
+    return s->fs_half[s->fs_cur] + (size_t)(layer - s->fs_cur_l0) * s->D.layer_elems + s->D.tensor_off[tid];
   const size_t off = (size_t)layer * s->D.layer_elems + s->D.tensor_off[tid];
   return s->cfg.dtype == BF_BF16 ? (const void*)(s->wlp + off) : (const void*)(s->w32 + off);
 }
@@ -502,7 +516,14 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->m = (float*)(s->ws + s->Lo.off_m);
   s->v = (float*)(s->ws + s->Lo.off_v);
   s->g32 = (float*)(s->ws + s->Lo.off_g32);
-  s->wlp = cfg->dtype == BF_BF16 ? (bf16_t*)(s->ws + s->Lo.off_wlp) : nullptr;
+  s->wlp = cfg->dtype == BF_BF16 && !cfg->dp_fs ? (bf16_t*)(s->ws + s->Lo.off_wlp) : nullptr;
+  for (int i = 0; i < 2; ++i) {
+    s->fs_half[i] = cfg->dp_fs ? (bf16_t*)(s->ws + s->Lo.off_wlp + i * s->Lo.half_bytes) : nullptr;
+    s->fs_l0[i] = s->fs_n[i] = -1;
+    s->fs_ready[i] = s->fs_free[i] = nullptr;
+  }
+  s->fs_cur = 0;
+  s->fs_cur_l0 = 0;
   s->step = 0;
   s->have_grads = false;
   s->prof_on = false;
@@ -521,6 +542,11 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   CK(hipEventCreateWithFlags(&s->ev_side_done, hipEventDisableTiming));
   CK(hipEventCreate(&s->ev_t0));
   CK(hipEventCreate(&s->ev_t1));
+  if (cfg->dp_fs)
+    for (int i = 0; i < 2; ++i) {
+      CK(hipEventCreateWithFlags(&s->fs_ready[i], hipEventDisableTiming));
+      CK(hipEventCreateWithFlags(&s->fs_free[i], hipEventDisableTiming));
+    }
   s->adam_ev.resize(2 * (size_t)cfg->N_layers, nullptr);
   for (auto& e : s->adam_ev) CK(hipEventCreate(&e));
   if (cfg->queue_depth > 0) {
@@ -554,7 +580,8 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
 bf_status bf_destroy_stack(bf_stack* s) {
   if (!s) return BF_OK;
   if (s->side) { (void)hipStreamSynchronize(s->side); (void)hipStreamDestroy(s->side); }
-  hipEvent_t evs[4] = {s->ev_grad_ready, s->ev_side_done, s->ev_t0, s->ev_t1};
+  hipEvent_t evs[8] = {s->ev_grad_ready, s->ev_side_done, s->ev_t0, s->ev_t1,
+                       s->fs_ready[0], s->fs_ready[1], s->fs_free[0], s->fs_free[1]};
   for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : s->adam_ev) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : s->queue_ev) if (e) (void)hipEventDestroy(e);
@@ -584,6 +611,7 @@ bf_status bf_set_params(bf_stack* s, int layer, int tid, const float* host_src, 
     BF_TRY(cast_f32_to_bf16(n, dst, s->wlp + (dst - s->w32), nullptr));
     BF_HIP_CHECK(hipDeviceSynchronize());
   }
+  s->fs_l0[0] = s->fs_l0[1] = -1;  // dp_fs: whatever the double buffer holds is stale now
   return BF_OK;
 }
 
@@ -675,10 +703,54 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
   auto bhand = [&](int stage, int m) { return s->ws + s->Lo.off_bhand + ((size_t)(stage & 1) * c.N_mb_max + m) * s->Lo.y_bytes; };
   char* scratch_out = s->ws + s->Lo.off_scratch_out;
   const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c) && per_stage <= lps_max(c);
+  if (c.dp_fs && per_stage > lps_max(c)) {
+    set_error("bf_run_step: dp_fs holds stages of up to %d layers (N_loop_min = %d), N_loop = %d gives %d", lps_max(c),
+              c.N_loop_min, N_loop, per_stage);
+    return BF_EINVAL;
+  }
 
   std::vector<SchedOp> ops;
   std::string why;
   if (!rank_order(schedule, 1, N_loop, N_mb, 0, &ops, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+
+  // dp_fs: cut the order into intervals (runs of one stage in one direction) and decide, in order,
+  // which half of the double buffer serves each and whether the stage has to be reconstructed into
+  // it: a stage still resident is reused, otherwise it goes to the half the previous interval is
+  // not reading, so that the reconstruction can run beside that interval (App. D.1).
+  struct Interval { int stage, half; bool load; };
+  std::vector<Interval> ivs;
+  std::vector<int> iv_of(ops.size(), -1);
+  if (c.dp_fs) {
+    int l0h[2] = {s->fs_l0[0], s->fs_l0[1]}, nh[2] = {s->fs_n[0], s->fs_n[1]};
+    for (size_t i = 0; i < ops.size(); ++i) {
+      if (i == 0 || ops[i].stage != ops[i - 1].stage || ops[i].op != ops[i - 1].op) {
+        const int l0 = ops[i].stage * per_stage;
+        Interval iv{ops[i].stage, 0, true};
+        const int prev = ivs.empty() ? 1 : ivs.back().half;
+        if (l0h[0] == l0 && nh[0] == per_stage) { iv.half = 0; iv.load = false; }
+        else if (l0h[1] == l0 && nh[1] == per_stage) { iv.half = 1; iv.load = false; }
+        else { iv.half = prev ^ 1; l0h[iv.half] = l0; nh[iv.half] = per_stage; }
+        ivs.push_back(iv);
+      }
+      iv_of[i] = (int)ivs.size() - 1;
+    }
+  }
+  int64_t n_recon = 0;
+  // enqueue the reconstruction of interval j on the side stream, after everything issued so far
+  // on the caller's stream (the earlier readers of that half, earlier optimizer steps)
+  auto reconstruct = [&](int j) -> bf_status {
+    const Interval& iv = ivs[j];
+    const size_t off = (size_t)iv.stage * per_stage * s->D.layer_elems, n = (size_t)per_stage * s->D.layer_elems;
+    BF_HIP_CHECK(hipEventRecord(s->fs_free[iv.half], st));
+    BF_HIP_CHECK(hipStreamWaitEvent(s->side, s->fs_free[iv.half], 0));
+    BF_TRY(timed(s, BF_K_RECONSTRUCT, 0.0, 6.0 * (double)n, s->side,
+                 [&] { return cast_f32_to_bf16(n, s->w32 + off, s->fs_half[iv.half], s->side); }));
+    BF_HIP_CHECK(hipEventRecord(s->fs_ready[iv.half], s->side));
+    s->fs_l0[iv.half] = iv.stage * per_stage;
+    s->fs_n[iv.half] = per_stage;
+    ++n_recon;
+    return BF_OK;
+  };
 
   s->trace.clear();
   s->have_grads = false;
@@ -696,8 +768,18 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
     return record_for(s, layer - 1, m).y;
   };
 
-  for (const SchedOp& op : ops) {
+  for (size_t oi = 0; oi < ops.size(); ++oi) {
+    const SchedOp& op = ops[oi];
     const int l0 = op.stage * per_stage, l1 = l0 + per_stage, m = op.mb;
+    if (c.dp_fs && (oi == 0 || iv_of[oi] != iv_of[oi - 1])) {
+      // a new interval starts: its weights must have arrived, and the next interval's are sent for
+      const int j = iv_of[oi];
+      if (j == 0 && ivs[0].load) BF_TRY(reconstruct(0));
+      if (ivs[j].load) BF_HIP_CHECK(hipStreamWaitEvent(st, s->fs_ready[ivs[j].half], 0));
+      s->fs_cur = ivs[j].half;
+      s->fs_cur_l0 = l0;
+      if (j + 1 < (int)ivs.size() && ivs[j + 1].load) BF_TRY(reconstruct(j + 1));
+    }
     if (op.op == 0) {
       for (int l = l0; l < l1; ++l) {
         Record R = record_for(s, l, m);
@@ -760,6 +842,8 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
           return adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
                            c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as);
         }));
+        // dp_fs: the halves hold this stage's old weights at most until here
+        for (int i = 0; i < 2; ++i) if (s->fs_l0[i] == l0) s->fs_l0[i] = -1;
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam + 1], as));
         ++n_adam;
       }
@@ -800,7 +884,12 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
     const int64_t rec_live = (int64_t)((double)(s->Lo.rec_bytes) * frac) + (int64_t)mb_bytes;
     report->peak_act_bytes = c.ckpt_mode == BF_CKPT_NONE ? peak_live * rec_live
                                                          : peak_live * (int64_t)mb_bytes + (int64_t)((double)s->Lo.rec_bytes * frac);
-    report->state_bytes = (int64_t)s->Lo.P_total * (c.dtype == BF_BF16 ? 18 : 16);
+    report->state_bytes = (int64_t)s->Lo.P_total * (c.dtype == BF_BF16 && !c.dp_fs ? 18 : 16) +
+                          (c.dp_fs ? 2 * (int64_t)s->Lo.half_bytes : 0);
+    report->n_weight_intervals = (int64_t)ivs.size();
+    report->n_reconstruct = n_recon;
+    report->reconstruct_bytes = n_recon * 6 * (int64_t)per_stage * (int64_t)s->D.layer_elems;
+    report->weight_buffer_bytes = c.dp_fs ? 2 * (int64_t)s->Lo.half_bytes : 0;
     report->n_events = (int32_t)s->trace.size();
   }
   if (timing) {

@@ -224,3 +224,61 @@ def test_run_step_argument_errors():
     h = C.c_void_p()
     rc = bf.load().bf_create_stack(C.byref(cfg), small.data_ptr(), 1024, None, C.byref(h))
     assert rc == bf.BF_ENOMEM
+
+
+def _fs_expected(schedule, N_loop, N_mb, resident=()):
+    from oracle import schedule as S
+    order = S.device_order("BF" if schedule == bf.BF_SCHED_BF else "DF", 1, N_loop, N_mb, 0)
+    n, held = S.reconstructions(order, resident=resident)
+    return len(S.weight_intervals(order)), n, held
+
+
+@pytest.mark.parametrize("schedule", [bf.BF_SCHED_BF, bf.BF_SCHED_DF])
+@pytest.mark.parametrize("Lyr,N_loop,N_mb,fuse,ckpt", [
+    (4, 4, 3, 0, bf.BF_CKPT_NONE), (4, 2, 4, 1, bf.BF_CKPT_NONE), (3, 3, 2, 1, bf.BF_CKPT_LAYER), (2, 1, 3, 0, bf.BF_CKPT_NONE),
+    (6, 3, 2, 0, bf.BF_CKPT_LAYER),
+])
+def test_fully_sharded_double_buffer_is_bit_identical_and_counts_reconstructions(schedule, Lyr, N_loop, N_mb, fuse, ckpt):
+    """dp_fs = 1: bf16 stage weights are rebuilt from the fp32 master copy into a two-stage double
+    buffer before each interval of use (Sec. 3.1, App. D.1).  Same bf16 weights reach the same kernels:
+    outputs, gradients, and two optimizer steps are bit-identical to the resident copy; the interval
+    and reconstruction counts are the oracle's (BF 2 N_loop intervals, DF 2 N_loop N_mb, Sec. 4.2)."""
+    h, a, f, S_seq, S_mb = 256, 2, 1024, 128, 1
+    params = bf_inputs.make_params(19, Lyr, h, f, bf16=True)
+    x, dy = bf_inputs.make_batch(19, N_mb, S_mb, S_seq, h, bf16=True)
+    mk = lambda fs: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, lr=1e-3, fuse_wgrad=fuse,
+                                   ckpt_mode=ckpt, N_loop_min=N_loop, dp_fs=fs)
+    if N_loop > 2:
+        saved = bf.bf_workspace_bytes(mk(0)) - bf.bf_workspace_bytes(mk(1))
+        P = bf.bf_param_count(mk(0))
+        assert 0 < saved <= 2 * P and saved >= 2 * P * (N_loop - 2) // N_loop - 1024
+    for opt in (0, 1):
+        g1 = _run_gpu(mk(1), params, x, dy, schedule, N_loop, N_mb, S_mb, apply_optimizer=opt, steps=2)
+        g0 = _run_gpu(mk(0), params, x, dy, schedule, N_loop, N_mb, S_mb, apply_optimizer=opt, steps=2)
+        assert np.array_equal(g1["y"], g0["y"]) and np.array_equal(g1["dx"], g0["dx"])
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                for key in ("grads", "params", "m", "v"):
+                    assert np.array_equal(g1[key][l][name], g0[key][l][name]), (opt, key, l, name)
+        assert g1["trace"] == g0["trace"]
+        if not opt:
+            _compare(g1, _oracle(params, x, dy, K.SCHED_BF, N_loop, a), TOL["bf16"], Lyr)
+        # second step: without an optimizer step the stages left in the buffer are still good
+        _, _, held = _fs_expected(schedule, N_loop, N_mb)
+        n_iv, n_rec, _ = _fs_expected(schedule, N_loop, N_mb, resident=() if opt else held)
+        r = g1["report"]
+        assert (r.n_weight_intervals, r.n_reconstruct) == (n_iv, n_rec)
+        assert r.reconstruct_bytes == n_rec * 6 * (bf.bf_param_count(mk(1)) // N_loop)
+        assert g0["report"].n_reconstruct == 0 and g0["report"].weight_buffer_bytes == 0
+        assert r.weight_buffer_bytes >= 2 * 2 * (bf.bf_param_count(mk(1)) // N_loop)
+
+
+def test_fully_sharded_argument_errors():
+    assert bf.bf_workspace_bytes(bf.make_config(64, 2, 256, 16, 4, 2, 1, dtype=bf.BF_FP32, dp_fs=1)) == 0
+    cfg = bf.make_config(128, 2, 512, 64, 4, 2, 1, dtype=bf.BF_BF16, dp_fs=1, N_loop_min=4)
+    st = bf.Stack(cfg)
+    x = torch.zeros(2, 1, 64, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(bf.BfError, match="dp_fs"):
+        st.bf_run_step(bf.BF_SCHED_BF, 2, 2, 1, x, x, None, None)     # stages of 2 layers, halves of 1
+    st.bf_run_step(bf.BF_SCHED_BF, 4, 2, 1, x, x, None, None)
+    st.close()

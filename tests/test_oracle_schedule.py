@@ -76,3 +76,59 @@ def test_bf_needs_enough_microbatches_and_df_multiple():
         S.device_order("BF", 4, 2, 3, 0)
     with pytest.raises(ValueError):
         S.device_order("DF", 4, 2, 6, 0)
+
+
+def test_weight_intervals_match_the_sharded_intensities():
+    """Fully sharded data parallelism reconstructs a stage once per interval of use.  Breadth-first:
+    a single forward and a single backward interval per stage, whatever N_mb (Sec. 4.2); plain
+    gradient accumulation (depth-first at N_PP = 1) repeats them for every micro-batch (Sec. 3.1).
+    The ratio of the two counts is the ratio of the intensities I_FS-BF / I_FS of App. A.3.1."""
+    for N_PP in (1, 2, 4):
+        for N_loop in (1, 2, 3, 4, 8):
+            for N_mb in (N_PP, 2 * N_PP, 4 * N_PP, 16 * N_PP):
+                for rank in range(N_PP):
+                    bf = S.weight_intervals(S.device_order("BF", N_PP, N_loop, N_mb, rank))
+                    assert len(bf) == 2 * N_loop
+                    assert sorted(st for _, st, _, _ in bf) == sorted(2 * [l * N_PP + rank for l in range(N_loop)])
+                    assert all(n == N_mb for _, _, _, n in bf)
+                    df = S.weight_intervals(S.device_order("DF", N_PP, N_loop, N_mb, rank))
+                    # a sequence holds N_PP micro-batches: never fewer intervals than one per sequence
+                    assert 2 * N_loop * N_mb // N_PP <= len(df) <= 2 * N_loop * N_mb
+                    assert sum(n for _, _, _, n in df) == 2 * N_loop * N_mb
+                    if N_PP == 1:
+                        assert len(df) == 2 * N_loop * N_mb
+                        assert Fraction(len(df), len(bf)) == F.intensity_fs("BF", N_mb, 1, 2048) / F.intensity_fs("plain", N_mb, 1, 2048)
+
+
+def _count_misses_brute(stages, n_buffers):
+    """Least-recently-used replacement written the slow way: time stamps, no list surgery."""
+    last, held, misses = {}, set(), 0
+    for t, st in enumerate(stages):
+        if st not in held:
+            misses += 1
+            if len(held) == n_buffers:
+                held.remove(min(held, key=lambda k: last[k]))
+            held.add(st)
+        last[st] = t
+    return misses
+
+
+def test_reconstruction_counts_with_a_double_buffer():
+    """With the two most recent stages kept (App. D.1, double buffer) the turn-around from the last
+    forward stage into the backward pass finds both stages in place."""
+    for N_loop in (1, 2, 3, 4, 8):
+        for N_mb in (1, 2, 5, 16):
+            bf = S.device_order("BF", 1, N_loop, N_mb, 0)
+            df = S.device_order("DF", 1, N_loop, N_mb, 0)
+            n_bf, held_bf = S.reconstructions(bf)
+            n_df, _ = S.reconstructions(df)
+            assert n_bf == (N_loop if N_loop <= 2 else 2 * N_loop - 2)
+            assert n_df == (N_loop if N_loop <= 2 else N_mb * (2 * N_loop - 4) + 2)
+            assert held_bf[-1] == 0
+            for order, n in ((bf, n_bf), (df, n_df)):
+                assert n == _count_misses_brute([st for _, st, _, _ in S.weight_intervals(order)], 2)
+            # one buffer: every interval but the forward-to-backward turn of the last stage reloads
+            assert S.reconstructions(bf, n_buffers=1)[0] == 2 * N_loop - 1
+            # a second step with nothing changed starts from what the first left behind
+            again, _ = S.reconstructions(bf, resident=held_bf)
+            assert again == (0 if N_loop <= 2 else 2 * N_loop - 4)
