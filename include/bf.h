@@ -194,7 +194,25 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
                       const void* x, const void* dy, void* y, void* dx,
                       int apply_optimizer, int timing, void* stream, bf_step_report* report);
 
-/* Integer event trace of the last bf_run_step: copies min(cap, n) events, *n = total. */
+/* The same step as rank `rank` (0..N_PP-1) of an N_PP-deep looped pipeline runs it (Sec. 4.1, Sec. 4.2): the
+ * rank holds the global stages l * N_PP + rank, l = 0..N_loop-1 (N_layers / N_loop layers each), and walks them
+ * in the breadth-first order (forward-first, every micro-batch through a stage before the next stage; needs
+ * N_mb >= N_PP) or the depth-first order (backward-first, sequences of N_PP micro-batches, interleaved warm-up;
+ * needs N_mb % N_PP == 0).  The neighbouring ranks are not run: the caller's buffers stand in for what they
+ * would send and receive,
+ *   x, dy   device, [N_loop, N_mb, S_mb, S_seq, S_hidden]: input of local stage l for micro-batch m, and the
+ *           gradient arriving at that stage's output
+ *   y, dx   device outputs of the same shape (either may be NULL): the stage's output and the gradient
+ *           leaving its input
+ * so the rank's stages do not feed each other (at N_PP = 1 bf_run_step chains them instead).  Everything
+ * else (optimizer per stage when its gradient is final, fuse_wgrad in breadth-first order, dp_fs, timing,
+ * report, trace with GLOBAL stage indices, error codes) is as for bf_run_step; BF_EINVAL also for a rank
+ * outside 0..N_PP-1 or an N_mb the order does not allow. */
+bf_status bf_run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, int N_loop, int N_mb, int S_mb,
+                           const void* x, const void* dy, void* y, void* dx,
+                           int apply_optimizer, int timing, void* stream, bf_step_report* report);
+
+/* Integer event trace of the last bf_run_step / bf_run_rank_step: copies min(cap, n) events, *n = total. */
 bf_status bf_get_trace(const bf_stack* s, bf_event* dst, size_t cap, size_t* n);
 
 /* Pure host arithmetic, no device needed: the order in which rank `rank` of an N_PP-deep

@@ -154,3 +154,45 @@ def run_one_big_batch(params, x, dy, N_heads, eps=1e-5, causal=True, gelu_form="
     for l in reversed(range(len(params))):
         d, grads[l] = L.layer_bwd(params[l], caches[l], d, N_heads)
     return dict(y=t.reshape(x.shape), dx=d.reshape(x.shape), grads=grads)
+
+
+def run_rank_step(params, x, dy, kind, N_PP, rank, N_loop, N_heads, eps=1e-5, causal=True, gelu_form="tanh"):
+    """One step of rank `rank` of an N_PP-deep looped pipeline (Sec. 4.1, Sec. 4.2), the other ranks
+    absent: the rank's local stage l (global stage l N_PP + rank, the layers stage_layers(.., l) of
+    `params`) takes its input x[l, m] and the gradient dy[l, m] of its output from outside and hands
+    y[l, m], dx[l, m] back.  Ops run in the order of schedule.device_order (kind "BF" or "DF").
+
+    x, dy: [N_loop, N_mb, S_mb, S_seq, S_hidden].
+    Returns dict(y, dx, grads, trace, peak_ckpt); trace entries (op, global stage, mb, live
+    checkpoints), with an OP_OPT entry after the last backward of each stage."""
+    from . import schedule as S
+    N_layers = len(params)
+    N_mb = x.shape[1]
+    y = np.zeros_like(x)
+    dx = np.zeros_like(x)
+    grads = [None] * N_layers
+    caches = {}
+    trace = []
+    peak = 0
+    for op, stage, m in S.device_order(kind, N_PP, N_loop, N_mb, rank):
+        l_loc = (stage - rank) // N_PP
+        if op == OP_F:
+            t = x[l_loc, m]
+            for l in stage_layers(N_layers, N_loop, l_loc):
+                t, caches[(l, m)] = L.layer_fwd(params[l], t, N_heads, eps, causal, gelu_form)
+            y[l_loc, m] = t
+        else:
+            d = dy[l_loc, m]
+            for l in reversed(stage_layers(N_layers, N_loop, l_loc)):
+                d, G = L.layer_bwd(params[l], caches.pop((l, m)), d, N_heads)
+                if grads[l] is None:
+                    grads[l] = G
+                else:
+                    for k in G:
+                        grads[l][k] = grads[l][k] + G[k]
+            dx[l_loc, m] = d
+        peak = max(peak, len(caches))
+        trace.append((op, stage, m, len(caches)))
+        if op == OP_B and m == N_mb - 1:
+            trace.append((OP_OPT, stage, -1, len(caches)))
+    return dict(y=y, dx=dx, grads=grads, trace=trace, peak_ckpt=peak)

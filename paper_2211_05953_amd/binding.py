@@ -61,6 +61,8 @@ _SIGNATURES = {
     "bf_reset_optimizer": (C.c_int, [_P]),
     "bf_run_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, _P,
                               C.POINTER(bf_step_report)]),
+    "bf_run_rank_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, _P,
+                              C.POINTER(bf_step_report)]),
     "bf_get_trace": (C.c_int, [_P, C.POINTER(bf_event), C.c_size_t, C.POINTER(C.c_size_t)]),
     "bf_schedule_trace": (C.c_int, [C.c_int] * 7 + [C.POINTER(bf_event), C.c_size_t, C.POINTER(C.c_size_t),
                                                     C.POINTER(bf_sched_stats)]),
@@ -201,6 +203,13 @@ class Stack:
         rep = bf_step_report()
         check(load().bf_run_step(self.handle, schedule, N_loop, N_mb, S_mb, _ptr(x), _ptr(dy), _ptr(y), _ptr(dx),
                                  apply_optimizer, timing, _stream(), C.byref(rep)))
+        return rep
+
+    def bf_run_rank_step(self, schedule, N_PP, rank, N_loop, N_mb, S_mb, x, dy, y=None, dx=None, apply_optimizer=0,
+                         timing=0):
+        rep = bf_step_report()
+        check(load().bf_run_rank_step(self.handle, schedule, N_PP, rank, N_loop, N_mb, S_mb, _ptr(x), _ptr(dy), _ptr(y),
+                                      _ptr(dx), apply_optimizer, timing, _stream(), C.byref(rep)))
         return rep
 
     def bf_get_trace(self):

@@ -680,8 +680,14 @@ bf_status bf_schedule_trace(int schedule, int N_PP, int N_loop, int N_mb, int ra
   return BF_OK;
 }
 
-bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb, const void* x, const void* dy, void* y,
-                      void* dx, int apply_optimizer, int timing, void* stream, bf_step_report* report) {
+// One step of rank `rank` of an N_PP-deep looped pipeline.  chained: the rank's stages feed each
+// other (N_PP = 1: x / dy / y / dx hold one tensor per micro-batch); otherwise every stage takes
+// its input and incoming gradient from the caller's buffers and leaves its output and outgoing
+// gradient there (one tensor per local stage and micro-batch), as a rank that receives from and
+// sends to its neighbours would.
+static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bool chained, int N_loop, int N_mb, int S_mb,
+                               const void* x, const void* dy, void* y, void* dx, int apply_optimizer, int timing,
+                               void* stream, bf_step_report* report) {
   if (!s) { set_error("bf_run_step: null stack"); return BF_EINVAL; }
   const bf_config& c = s->cfg;
   if (schedule != BF_SCHED_BF && schedule != BF_SCHED_DF) { set_error("bf_run_step: unknown schedule %d", schedule); return BF_EINVAL; }
@@ -711,7 +717,11 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
 
   std::vector<SchedOp> ops;
   std::string why;
-  if (!rank_order(schedule, 1, N_loop, N_mb, 0, &ops, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+  if (!rank_order(schedule, N_PP, N_loop, N_mb, rank, &ops, &why)) { set_error("%s", why.c_str()); return BF_EINVAL; }
+  // local index of an op's stage: the rank holds the global stages ls * N_PP + rank (Sec. 4.1)
+  auto local = [&](const SchedOp& o) { return o.stage / N_PP; };
+  // the caller's tensor of (local stage, micro-batch)
+  auto io_off = [&](int ls, int m) { return ((size_t)(chained ? 0 : ls) * N_mb + m) * mb_bytes; };
 
   // dp_fs: cut the order into intervals (runs of one stage in one direction) and decide, in order,
   // which half of the double buffer serves each and whether the stage has to be reconstructed into
@@ -724,8 +734,8 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
     int l0h[2] = {s->fs_l0[0], s->fs_l0[1]}, nh[2] = {s->fs_n[0], s->fs_n[1]};
     for (size_t i = 0; i < ops.size(); ++i) {
       if (i == 0 || ops[i].stage != ops[i - 1].stage || ops[i].op != ops[i - 1].op) {
-        const int l0 = ops[i].stage * per_stage;
-        Interval iv{ops[i].stage, 0, true};
+        const int l0 = local(ops[i]) * per_stage;
+        Interval iv{local(ops[i]), 0, true};
         const int prev = ivs.empty() ? 1 : ivs.back().half;
         if (l0h[0] == l0 && nh[0] == per_stage) { iv.half = 0; iv.load = false; }
         else if (l0h[1] == l0 && nh[1] == per_stage) { iv.half = 1; iv.load = false; }
@@ -762,15 +772,19 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
   size_t n_adam = 0, qi = 0;
   if (timing) BF_HIP_CHECK(hipEventRecord(s->ev_t0, st));
 
-  // layer input of (layer, mb): the caller's x for layer 0, else the previous layer's stored output
+  // where a stage meets the caller's buffers: the first layer's input and outgoing gradient, the
+  // last layer's output and incoming gradient (chained: only the rank's first and last layer)
+  auto is_bottom = [&](int layer) { return chained ? layer == 0 : layer % per_stage == 0; };
+  auto is_top = [&](int layer) { return chained ? layer == c.N_layers - 1 : layer % per_stage == per_stage - 1; };
+  // layer input of (layer, mb): the caller's x at a stage bottom, else the previous layer's stored output
   auto input_of = [&](int layer, int m) -> const void* {
-    if (layer == 0) return (const char*)x + (size_t)m * mb_bytes;
+    if (is_bottom(layer)) return (const char*)x + io_off(layer / per_stage, m);
     return record_for(s, layer - 1, m).y;
   };
 
   for (size_t oi = 0; oi < ops.size(); ++oi) {
     const SchedOp& op = ops[oi];
-    const int l0 = op.stage * per_stage, l1 = l0 + per_stage, m = op.mb;
+    const int ls = local(op), l0 = ls * per_stage, l1 = l0 + per_stage, m = op.mb;
     if (c.dp_fs && (oi == 0 || iv_of[oi] != iv_of[oi - 1])) {
       // a new interval starts: its weights must have arrived, and the next interval's are sent for
       const int j = iv_of[oi];
@@ -784,7 +798,7 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
       for (int l = l0; l < l1; ++l) {
         Record R = record_for(s, l, m);
         void* out = R.y;
-        if (l == c.N_layers - 1) out = y ? (char*)y + (size_t)m * mb_bytes : scratch_out;
+        if (is_top(l)) out = y ? (char*)y + io_off(ls, m) : scratch_out;
         BF_TRY(layer_forward(s, l, S_mb, input_of(l, m), R, out, false, st));
         ++live;
       }
@@ -799,12 +813,12 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
         // gradient in: caller's dy for the last layer, the hand-off buffer at a stage top, else the ping-pong
         // (with the fused weight gradient every layer's incoming gradient is kept per micro-batch instead)
         const void* din;
-        if (l == c.N_layers - 1) din = (const char*)dy + (size_t)m * mb_bytes;
-        else if (l == l1 - 1) din = bhand(op.stage, m);
+        if (is_top(l)) din = (const char*)dy + io_off(ls, m);
+        else if (l == l1 - 1) din = bhand(ls, m);
         else din = fuse ? grad_rec(s, l - l0, m).dy : tmp.ping[(l + 1) & 1];
         void* dout;
-        if (l == 0) dout = dx ? (char*)dx + (size_t)m * mb_bytes : scratch_out + s->Lo.y_bytes;
-        else if (l == l0) dout = bhand(op.stage - 1, m);
+        if (is_bottom(l)) dout = dx ? (char*)dx + io_off(ls, m) : scratch_out + s->Lo.y_bytes;
+        else if (l == l0) dout = bhand(ls - 1, m);
         else dout = fuse ? grad_rec(s, l - 1 - l0, m).dy : tmp.ping[l & 1];
         GradRec keep{};
         if (fuse) keep = grad_rec(s, l - l0, m);
@@ -816,8 +830,8 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
         for (int l = l1 - 1; l >= l0; --l) {
           const void* dy0;
           size_t stride;
-          if (l == c.N_layers - 1) { dy0 = dy; stride = mb_bytes / es; }
-          else if (l == l1 - 1) { dy0 = bhand(op.stage, 0); stride = s->Lo.y_bytes / es; }
+          if (is_top(l)) { dy0 = (const char*)dy + io_off(ls, 0); stride = mb_bytes / es; }
+          else if (l == l1 - 1) { dy0 = bhand(ls, 0); stride = s->Lo.y_bytes / es; }
           else { dy0 = grad_rec(s, l - l0, 0).dy; stride = s->Lo.grec_bytes / es; }
           BF_TRY(layer_wgrad_fused(s, l, l - l0, S_mb, N_mb, dy0, stride, st));
         }
@@ -919,6 +933,18 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
     }
   }
   return BF_OK;
+}
+
+bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb, const void* x, const void* dy, void* y,
+                      void* dx, int apply_optimizer, int timing, void* stream, bf_step_report* report) {
+  return run_rank_step(s, schedule, 1, 0, true, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer, timing, stream, report);
+}
+
+bf_status bf_run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, int N_loop, int N_mb, int S_mb, const void* x,
+                           const void* dy, void* y, void* dx, int apply_optimizer, int timing, void* stream,
+                           bf_step_report* report) {
+  if (N_PP < 1 || rank < 0 || rank >= N_PP) { set_error("bf_run_rank_step: rank %d outside 0..N_PP-1 (N_PP = %d)", rank, N_PP); return BF_EINVAL; }
+  return run_rank_step(s, schedule, N_PP, rank, false, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer, timing, stream, report);
 }
 
 }  // extern "C"

@@ -282,3 +282,84 @@ def test_fully_sharded_argument_errors():
         st.bf_run_step(bf.BF_SCHED_BF, 2, 2, 1, x, x, None, None)     # stages of 2 layers, halves of 1
     st.bf_run_step(bf.BF_SCHED_BF, 4, 2, 1, x, x, None, None)
     st.close()
+
+
+def _run_gpu_rank(cfg, params, x, dy, schedule, N_PP, rank, N_loop, N_mb, S_mb):
+    b16 = cfg.dtype == bf.BF_BF16
+    st = bf.Stack(cfg)
+    for l, p in enumerate(params):
+        for name, tid in bf.TENSOR_IDS.items():
+            st.bf_set_params(l, tid, p[name].reshape(-1))
+    dX, dDY = to_dev(x, b16), to_dev(dy, b16)
+    y, dx = torch.empty_like(dX), torch.empty_like(dX)
+    rep = st.bf_run_rank_step(schedule, N_PP, rank, N_loop, N_mb, S_mb, dX, dDY, y, dx)
+    torch.cuda.synchronize()
+    out = dict(y=to_host(y), dx=to_host(dx), report=rep, trace=st.bf_get_trace(),
+               grads=[{n: st.bf_get_grads(l, t) for n, t in bf.TENSOR_IDS.items()} for l in range(cfg.N_layers)])
+    st.close()
+    return out
+
+
+@pytest.mark.parametrize("mode,dtype,N_PP,rank,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb,fuse,ckpt,fs", [
+    ("fp32", bf.BF_FP32, 2, 0, 4, 2, 128, 2, 512, 64, 1, 4, 0, bf.BF_CKPT_NONE, 0),
+    ("fp32", bf.BF_FP32, 2, 1, 4, 2, 128, 2, 512, 64, 1, 4, 1, bf.BF_CKPT_LAYER, 0),
+    ("fp32", bf.BF_FP32, 4, 2, 3, 3, 72, 3, 200, 50, 2, 8, 0, bf.BF_CKPT_NONE, 0),
+    ("fp32", bf.BF_FP32, 1, 0, 4, 2, 128, 2, 512, 64, 1, 3, 1, bf.BF_CKPT_NONE, 0),
+    ("bf16", bf.BF_BF16, 4, 3, 4, 2, 256, 2, 1024, 128, 1, 8, 1, bf.BF_CKPT_NONE, 1),
+    ("bf16", bf.BF_BF16, 2, 0, 4, 4, 256, 2, 1024, 128, 1, 2, 0, bf.BF_CKPT_LAYER, 1),
+])
+def test_rank_of_a_deeper_pipeline_matches_oracle(mode, dtype, N_PP, rank, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb,
+                                                  fuse, ckpt, fs):
+    """bf_run_rank_step: the rank's order for N_PP > 1 (Sec. 4.2), its stages fed from the caller's
+    buffers.  Numbers against the oracle's rank step; the trace is the oracle's device order; the
+    peak checkpoint count is the simulator's and respects Eq. mem_ckpt and its depth-first cap."""
+    from oracle import schedule as S
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(23, Lyr, h, f, bf16=b16)
+    p64 = [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
+    xs, dys = zip(*[bf_inputs.make_batch(100 + l, N_mb, S_mb, S_seq, h, bf16=b16) for l in range(N_loop)])
+    x, dy = np.stack(xs), np.stack(dys)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=fuse, ckpt_mode=ckpt, N_loop_min=N_loop,
+                         dp_fs=fs)
+    per_stage = Lyr // N_loop
+    N_layers_total = Lyr * N_PP
+    got = {}
+    for kind, code in (("BF", bf.BF_SCHED_BF), ("DF", bf.BF_SCHED_DF)):
+        ref = K.run_rank_step(p64, x.astype(np.float64), dy.astype(np.float64), kind, N_PP, rank, N_loop, a)
+        g = got[kind] = _run_gpu_rank(cfg, params, x, dy, code, N_PP, rank, N_loop, N_mb, S_mb)
+        _compare(g, ref, TOL[mode], Lyr)
+        assert g["trace"] == [tuple(e) for e in ref["trace"]]
+        assert [e[:3] for e in g["trace"] if e[0] != 2] == S.device_order(kind, N_PP, N_loop, N_mb, rank)
+        peak = g["report"].peak_ckpt_count
+        assert peak == ref["peak_ckpt"] == S.simulate(kind, N_PP, N_loop, N_mb)["peak_live"][rank] * per_stage
+        if kind == "BF":
+            assert peak == F.ckpt_count("BF", N_mb, N_layers_total, N_PP)
+        else:
+            # the cap of Eq. mem_ckpt counts stages of one layer: here a stage is per_stage layers
+            assert peak <= F.ckpt_count("DF" if N_loop > 1 else "1F1B", N_mb, N_PP * N_loop, N_PP) * per_stage
+        if fs:
+            order = S.device_order(kind, N_PP, N_loop, N_mb, rank)
+            assert g["report"].n_weight_intervals == len(S.weight_intervals(order))
+            assert g["report"].n_reconstruct == S.reconstructions(order)[0]
+    # the two orders add each stage's micro-batches in the same sequence (fused: one long contraction instead)
+    assert np.array_equal(got["BF"]["y"], got["DF"]["y"]) and np.array_equal(got["BF"]["dx"], got["DF"]["dx"])
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            if fuse:
+                assert rel_err(got["BF"]["grads"][l][name], got["DF"]["grads"][l][name]) <= 1e-5, (l, name)
+            else:
+                assert np.array_equal(got["BF"]["grads"][l][name], got["DF"]["grads"][l][name]), (l, name)
+
+
+def test_rank_step_argument_errors():
+    cfg = bf.make_config(64, 2, 256, 16, 4, 4, 1, dtype=bf.BF_FP32)
+    st = bf.Stack(cfg)
+    x = torch.zeros(2, 4, 1, 16, 64, device="cuda")
+    with pytest.raises(bf.BfError):
+        st.bf_run_rank_step(bf.BF_SCHED_BF, 2, 2, 2, 4, 1, x, x)      # rank outside 0..N_PP-1
+    with pytest.raises(bf.BfError):
+        st.bf_run_rank_step(bf.BF_SCHED_DF, 2, 0, 2, 3, 1, x, x)      # depth-first needs N_mb % N_PP == 0
+    with pytest.raises(bf.BfError):
+        st.bf_run_rank_step(bf.BF_SCHED_BF, 4, 0, 2, 2, 1, x, x)      # breadth-first needs N_mb >= N_PP
+    st.bf_run_rank_step(bf.BF_SCHED_BF, 2, 1, 2, 4, 1, x, x)
+    st.close()

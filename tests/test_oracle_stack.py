@@ -106,3 +106,50 @@ def test_optimizer_fires_per_stage_and_uses_final_gradient():
     # weights used by the backward are the old ones: y does not depend on the optimizer
     noopt = K.run_step(params, x, dy, K.SCHED_BF, 2, a)
     assert np.array_equal(noopt["dx"], bf["dx"])
+
+
+def test_rank_step_composes_to_the_chained_step_and_keeps_the_pipeline_order():
+    """A pipeline rank's stages, fed by hand with what their neighbours would send, must give what the
+    chained stack gives (the stack pinned above by finite differences and the one-big-batch run): the
+    two ranks of an N_PP = 2 pipeline over 4 layers in 4 stages, forward rank by rank and backward in
+    reverse, reproduce the N_loop = 4 single-device step.  The order changes nothing but the trace."""
+    from oracle import schedule as S
+    params, x, dy, a = _setup(N_layers=4, N_mb=4)
+    whole = K.run_step(params, x, dy, K.SCHED_BF, 4, a)
+    N_PP, N_loop, N_mb = 2, 2, 4
+    # layers of rank r, local stage l: global stage l * N_PP + r = layer index here (one layer per stage)
+    rank_params = [[params[l * N_PP + r] for l in range(N_loop)] for r in range(N_PP)]
+    zeros = np.zeros((N_loop,) + x.shape)
+    # forward sweep: stage j's input is stage j-1's output; run ranks with the inputs known so far
+    xin = [zeros.copy() for _ in range(N_PP)]
+    xin[0][0] = x
+    for j in range(N_PP * N_loop):
+        r, l = j % N_PP, j // N_PP
+        out = K.run_rank_step(rank_params[r], xin[r], zeros, "BF", N_PP, r, N_loop, a)
+        if j + 1 < N_PP * N_loop:
+            xin[(j + 1) % N_PP][(j + 1) // N_PP] = out["y"][l]
+    assert np.array_equal(out["y"][N_loop - 1], whole["y"])
+    # backward sweep: stage j's incoming gradient is what stage j+1 hands back
+    din = [zeros.copy() for _ in range(N_PP)]
+    din[N_PP - 1][N_loop - 1] = dy
+    for j in reversed(range(N_PP * N_loop)):
+        r, l = j % N_PP, j // N_PP
+        out = K.run_rank_step(rank_params[r], xin[r], din[r], "BF", N_PP, r, N_loop, a)
+        if j > 0:
+            din[(j - 1) % N_PP][(j - 1) // N_PP] = out["dx"][l]
+    assert np.array_equal(out["dx"][0], whole["dx"])
+    for r in range(N_PP):
+        res = {kind: K.run_rank_step(rank_params[r], xin[r], din[r], kind, N_PP, r, N_loop, a) for kind in ("BF", "DF")}
+        for l in range(N_loop):
+            for k in params[0]:
+                assert np.array_equal(res["BF"]["grads"][l][k], whole["grads"][l * N_PP + r][k]), (r, l, k)
+                assert np.array_equal(res["DF"]["grads"][l][k], res["BF"]["grads"][l][k]), (r, l, k)
+        for kind in ("BF", "DF"):
+            ops = [e[:3] for e in res[kind]["trace"] if e[0] != K.OP_OPT]
+            assert ops == S.device_order(kind, N_PP, N_loop, N_mb, r)
+            assert res[kind]["peak_ckpt"] == S.simulate(kind, N_PP, N_loop, N_mb)["peak_live"][r]
+        # Eq. mem_ckpt: breadth-first holds every micro-batch of every local stage, depth-first at most
+        # N_layers + N_PP - 1 checkpoints
+        assert res["BF"]["peak_ckpt"] == F.ckpt_count("BF", N_mb, 4, N_PP)
+        assert res["DF"]["peak_ckpt"] <= F.ckpt_count("DF", N_mb, 4, N_PP)
+        assert res["DF"]["peak_ckpt"] < res["BF"]["peak_ckpt"]
