@@ -75,3 +75,37 @@ def normal(seed, tag, shape, std=1.0, bf16=False):
     a = np.random.Generator(np.random.PCG64([seed, 2000, tag])).standard_normal(shape, dtype=np.float32)
     a = a * np.float32(std)
     return round_bf16(a) if bf16 else a
+
+
+VOCAB_PARAM_NAMES = ("e_tok", "e_pos", "lnf_g", "lnf_b", "w_out")
+
+
+def make_vocab_params(seed, S_voc, S_seq, S_hidden, init_std=0.02, ln_std=0.1, bf16=False):
+    """Input / output layer parameters, dict name -> float32 array: token and position
+    embeddings and the output projection ~ N(0, init_std), final LayerNorm as the layers' ones."""
+    shapes = {"e_tok": (S_voc, S_hidden), "e_pos": (S_seq, S_hidden), "lnf_g": (S_hidden,), "lnf_b": (S_hidden,),
+              "w_out": (S_voc, S_hidden)}
+    p = {}
+    for i, name in enumerate(VOCAB_PARAM_NAMES):
+        rng = np.random.Generator(np.random.PCG64([seed, 3000, i]))
+        a = rng.standard_normal(shapes[name], dtype=np.float32)
+        if name == "lnf_g":
+            a = np.float32(1.0) + a * np.float32(ln_std)
+        elif name == "lnf_b":
+            a = a * np.float32(ln_std)
+        else:
+            a = a * np.float32(init_std)
+        p[name] = round_bf16(a) if bf16 else a
+    return p
+
+
+def make_tokens(seed, N_mb, S_mb, S_seq, S_voc, zipf=1.1):
+    """(tokens, labels) int32 [N_mb, S_mb, S_seq].  Token ids follow a Zipf-like law over the vocabulary
+    (text has a few very frequent tokens and a long tail, so rows of the embedding repeat inside a
+    micro-batch); labels are the next token of the same stream."""
+    rng = np.random.Generator(np.random.PCG64([seed, 4000]))
+    w = 1.0 / np.arange(1, S_voc + 1, dtype=np.float64) ** zipf
+    perm = rng.permutation(S_voc)
+    stream = perm[rng.choice(S_voc, size=N_mb * S_mb * (S_seq + 1), p=w / w.sum())].astype(np.int32)
+    stream = stream.reshape(N_mb, S_mb, S_seq + 1)
+    return np.ascontiguousarray(stream[..., :-1]), np.ascontiguousarray(stream[..., 1:])

@@ -83,7 +83,8 @@ def run_step(params, x, dy, schedule, N_loop, N_heads, eps=1e-5, causal=True,
     """Executes one step in the given order.
 
     params: list (one per layer) of dicts name -> float64 array
-    x, dy:  [N_mb, S_mb, S_seq, S_hidden]
+    x, dy:  [N_mb, S_mb, S_seq, S_hidden]; dy may instead be a function (m, y_m) -> dy_m that is
+            called when micro-batch m leaves the last stage (an output layer and loss attached to it)
     adam:   None (no optimizer step) or dict(lr, beta1, beta2, adam_eps, weight_decay, t)
     adam_state: list of dicts name -> (m, v); zeros if None
     Returns dict(y, dx, grads, trace, peak_ckpt, new_params, new_adam_state)
@@ -96,6 +97,7 @@ def run_step(params, x, dy, schedule, N_loop, N_heads, eps=1e-5, causal=True,
     caches = {}                               # (layer, mb) -> cache; its presence = one live checkpoint
     hand = {}                                 # mb -> tensor handed from stage s to s+1 (forward) / s to s-1 (backward)
     bhand = {}
+    dy_of = {}
     new_params = [dict(p) for p in params]
     if adam_state is None:
         adam_state = [{k: (np.zeros_like(v), np.zeros_like(v)) for k, v in p.items()} for p in params]
@@ -111,8 +113,10 @@ def run_step(params, x, dy, schedule, N_loop, N_heads, eps=1e-5, causal=True,
             hand[m] = t
             if s == N_loop - 1:
                 y[m] = t
+                if callable(dy):
+                    dy_of[m] = dy(m, t)
         elif op == OP_B:
-            d = dy[m] if s == N_loop - 1 else bhand[m]
+            d = (dy_of[m] if callable(dy) else dy[m]) if s == N_loop - 1 else bhand[m]
             for l in reversed(stage_layers(N_layers, N_loop, s)):
                 d, G = L.layer_bwd(params[l], caches.pop((l, m)), d, N_heads)
                 if grads[l] is None:
@@ -196,3 +200,34 @@ def run_rank_step(params, x, dy, kind, N_PP, rank, N_loop, N_heads, eps=1e-5, ca
         if op == OP_B and m == N_mb - 1:
             trace.append((OP_OPT, stage, -1, len(caches)))
     return dict(y=y, dx=dx, grads=grads, trace=trace, peak_ckpt=peak)
+
+
+def run_lm_step(params, vparams, tokens, labels, schedule, N_loop, N_heads, eps=1e-5, causal=True, gelu_form="tanh"):
+    """The step on token ids: input layer attached to the first stage, output layer and loss to
+    the last (App. A.1; Eq. compute's S_voc term).  The loss gradient of a micro-batch is taken as
+    soon as the micro-batch leaves the last stage's forward; the input layer's gradient after the
+    first stage's backward.
+
+    vparams: dict e_tok, e_pos, lnf_g, lnf_b, w_out (float64); tokens, labels int [N_mb, S_mb, S_seq].
+    Returns run_step's dict plus loss (batch mean), loss_mb [N_mb], vgrads (dict like vparams)."""
+    from . import vocab as V
+    N_mb = tokens.shape[0]
+    n_total = tokens.size
+    x = np.stack([V.embedding_fwd(vparams, tokens[m]) for m in range(N_mb)])
+    loss_mb = np.zeros(N_mb)
+    vgrads = {}
+
+    def add(G):
+        for k, g in G.items():
+            vgrads[k] = g if k not in vgrads else vgrads[k] + g      # ascending micro-batch order
+
+    def head(m, y_m):
+        loss_mb[m], dy_m, G = V.head_loss_fwd_bwd(vparams, y_m, labels[m], n_total, eps)
+        add(G)
+        return dy_m
+
+    r = run_step(params, x, head, schedule, N_loop, N_heads, eps, causal, gelu_form)
+    for m in range(N_mb):
+        add(V.embedding_bwd(vparams, tokens[m], r["dx"][m]))
+    r.update(loss=loss_mb.sum(), loss_mb=loss_mb, vgrads=vgrads, x=x)
+    return r
