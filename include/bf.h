@@ -55,7 +55,12 @@ typedef enum {
   BF_LN2_G = 6, BF_LN2_B = 7,
   BF_W_FC1 = 8, /* [S_hidden, S_mlp]      */ BF_B_FC1 = 9,
   BF_W_FC2 = 10,/* [S_mlp, S_hidden]      */ BF_B_FC2 = 11,
-  BF_N_TENSORS = 12
+  BF_N_TENSORS = 12,
+  /* Input and output layers (config S_voc > 0; App. A.1), held once, addressed as pseudo-layer N_layers:
+   * token embedding [S_voc, S_hidden], position embedding [S_seq, S_hidden], final LayerNorm gain and
+   * bias, output projection [S_voc, S_hidden] (not tied to the token embedding). */
+  BF_E_TOK = 12, BF_E_POS = 13, BF_LNF_G = 14, BF_LNF_B = 15, BF_W_OUT = 16,
+  BF_N_VOCAB_TENSORS = 5
 } bf_tensor_id;
 
 typedef struct {
@@ -87,6 +92,10 @@ typedef struct {
                            to dp_fs = 0; bf_step_report counts the reconstructions (breadth-first: one forward and
                            one backward interval per stage; depth-first: as many per micro-batch, Sec. 4.2).
                            Stages larger than a half: BF_EINVAL from bf_run_step. */
+  int32_t S_voc;        /* > 0: the stack also holds the input layer (token + position embedding, attached to
+                           the first stage) and the output layer (final LayerNorm, projection to S_voc logits,
+                           mean cross-entropy; attached to the last stage), for bf_run_lm_step.  With dp_fs
+                           these two keep a resident bf16 copy.  0: none. */
   uint64_t seed;        /* device-side initialisation: weights ~ N(0, init_std), biases 0, LN gain 1 */
   float init_std;
   float ln_eps;
@@ -106,7 +115,8 @@ typedef enum {
   BF_K_ATTN_FWD = 3, BF_K_ATTN_BWD = 4,
   BF_K_LN_FWD = 5, BF_K_LN_BWD = 6, BF_K_COLSUM = 7, BF_K_ADAM = 8,
   BF_K_RECONSTRUCT = 9, /* dp_fs: fp32 master -> bf16 stage weights into a half of the double buffer */
-  BF_N_KERNEL_CLASSES = 10
+  BF_K_VOCAB = 10,      /* embedding forward / backward and softmax cross-entropy (bf_run_lm_step) */
+  BF_N_KERNEL_CLASSES = 11
 } bf_kernel_class;
 
 typedef struct {
@@ -211,6 +221,22 @@ bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
 bf_status bf_run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, int N_loop, int N_mb, int S_mb,
                            const void* x, const void* dy, void* y, void* dx,
                            int apply_optimizer, int timing, void* stream, bf_step_report* report);
+
+/* The step of bf_run_step on token ids (config S_voc > 0): the input layer feeds the first stage, the output
+ * layer and the loss follow the last (App. A.1; the S_voc / (16 N_layers) term of Eq. compute).
+ *   tokens, labels   device int32 [N_mb, S_mb, S_seq], ids in 0..S_voc-1.  A token id outside that range
+ *                    embeds as the position row alone and gets no gradient; a label outside it leaves its
+ *                    position out of the loss.
+ *   loss             device float [N_mb]: micro-batch m's share, sum of its tokens' cross-entropies divided by
+ *                    N_mb * S_mb * S_seq; the batch loss is the sum of the N_mb entries.
+ * A micro-batch's loss and the gradient of the output layer are taken when it leaves the last stage's
+ * forward; the input layer's gradient after the first stage's backward, without atomics (every sum in a
+ * fixed order).  With apply_optimizer the input layer steps with the first stage and the output layer with
+ * the last.  report->flops_* include the output projection.  Other arguments and errors as bf_run_step;
+ * BF_ESTATE if the stack was created with S_voc = 0. */
+bf_status bf_run_lm_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,
+                         const int32_t* tokens, const int32_t* labels, float* loss,
+                         int apply_optimizer, int timing, void* stream, bf_step_report* report);
 
 /* Integer event trace of the last bf_run_step / bf_run_rank_step: copies min(cap, n) events, *n = total. */
 bf_status bf_get_trace(const bf_stack* s, bf_event* dst, size_t cap, size_t* n);

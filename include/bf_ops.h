@@ -65,6 +65,21 @@ bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N
                               void* dqkv, float* delta, void* stream);
 int bf_op_attention_uses_mfma(int S_seq, int S_head);
 
+/* Input layer (App. A.1): x[t, :] = e_tok[tokens[t], :] + e_pos[t mod S_seq, :] for n_rows = S_mb * S_seq rows.
+ * tokens: device int32 [n_rows]; e_tok [S_voc, S_hidden], e_pos [S_seq, S_hidden] device fp32; x in `dtype`.
+ * An id outside 0..S_voc-1 contributes no token row. */
+bf_status bf_op_embedding_fwd(int dtype, int n_rows, int S_seq, int S_voc, int S_hidden, const int32_t* tokens,
+                              const float* e_tok, const float* e_pos, void* x, void* stream);
+/* Its gradient for one micro-batch d [S_mb, S_seq, S_hidden]: g_tok[tokens[t], :] += d[t, :] (always added,
+ * ascending t, no atomics); g_pos[i, :] = (accumulate_pos ? g_pos[i, :] : 0) + sum over samples of d[b, i, :]. */
+bf_status bf_op_embedding_bwd(int dtype, int S_mb, int S_seq, int S_voc, int S_hidden, const int32_t* tokens,
+                              const void* d, float* g_tok, float* g_pos, int accumulate_pos, void* stream);
+/* Softmax cross-entropy over rows of logits z [n_rows, S_voc] (`dtype`), in place: z becomes
+ * (softmax(z) - onehot(label)) * scale; row_loss[t] = (logsumexp(z[t]) - z[t, label]) * scale (device fp32
+ * [n_rows]); loss_out[0] = sum of row_loss in a fixed order.  A label outside 0..S_voc-1 zeroes its row. */
+bf_status bf_op_ce_loss(int dtype, int n_rows, int S_voc, void* z, const int32_t* labels, float scale, float* row_loss,
+                        float* loss_out, void* stream);
+
 /* Fused Adam over n contiguous fp32 parameters (bias-corrected, decoupled weight decay), step t >= 1;
  * w_lp: bf16 copy of w to refresh, or NULL. */
 bf_status bf_op_adam(size_t n, float* w, float* m, float* v, const float* g, void* w_lp, int t,

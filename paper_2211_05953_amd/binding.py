@@ -14,6 +14,7 @@ BF_CKPT_NONE, BF_CKPT_LAYER = 0, 1
 BF_KERNELS_AUTO, BF_KERNELS_PLAIN = 0, 1
 BF_NN, BF_NT, BF_TN = 0, 1, 2
 BF_EPI_NONE, BF_EPI_BIAS, BF_EPI_BIAS_RES, BF_EPI_BIAS_GELU, BF_EPI_GELU_BWD, BF_EPI_ACCUM = range(6)
+VOCAB_TENSOR_IDS = {"e_tok": 12, "e_pos": 13, "lnf_g": 14, "lnf_b": 15, "w_out": 16}
 TENSOR_IDS = {"ln1_g": 0, "ln1_b": 1, "w_qkv": 2, "b_qkv": 3, "w_o": 4, "b_o": 5,
               "ln2_g": 6, "ln2_b": 7, "w_fc1": 8, "b_fc1": 9, "w_fc2": 10, "b_fc2": 11}
 
@@ -21,7 +22,7 @@ TENSOR_IDS = {"ln1_g": 0, "ln1_b": 1, "w_qkv": 2, "b_qkv": 3, "w_o": 4, "b_o": 5
 class bf_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("S_hidden", "N_heads", "S_head", "S_mlp", "S_seq", "N_layers", "N_mb_max",
                                          "S_mb_max", "dtype", "ckpt_mode", "causal", "kernels", "queue_depth",
-                                         "fuse_wgrad", "N_loop_min", "dp_fs")] + \
+                                         "fuse_wgrad", "N_loop_min", "dp_fs", "S_voc")] + \
                [("seed", C.c_uint64)] + \
                [(n, C.c_float) for n in ("init_std", "ln_eps", "lr", "beta1", "beta2", "adam_eps", "weight_decay")]
 
@@ -34,13 +35,13 @@ class bf_step_report(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("gpu_ms", "adam_ms", "flops_model", "flops_paper", "flops_executed")] + \
                [(n, C.c_int64) for n in ("peak_ckpt_count", "peak_ckpt_bytes", "peak_act_bytes", "state_bytes")] + \
                [("n_events", C.c_int32), ("timed", C.c_int32)] + \
-               [("kernel_ms", C.c_double * 10), ("kernel_flops", C.c_double * 10), ("kernel_bytes", C.c_double * 10),
-                ("kernel_launches", C.c_int64 * 10)] + \
+               [("kernel_ms", C.c_double * 11), ("kernel_flops", C.c_double * 11), ("kernel_bytes", C.c_double * 11),
+                ("kernel_launches", C.c_int64 * 11)] + \
                [(n, C.c_int64) for n in ("n_weight_intervals", "n_reconstruct", "reconstruct_bytes", "weight_buffer_bytes")]
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam",
-                  "reconstruct")
+                  "reconstruct", "vocab")
 
 
 class bf_sched_stats(C.Structure):
@@ -61,6 +62,8 @@ _SIGNATURES = {
     "bf_reset_optimizer": (C.c_int, [_P]),
     "bf_run_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, _P,
                               C.POINTER(bf_step_report)]),
+    "bf_run_lm_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_int, C.c_int, _P,
+                                 C.POINTER(bf_step_report)]),
     "bf_run_rank_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, _P,
                               C.POINTER(bf_step_report)]),
     "bf_get_trace": (C.c_int, [_P, C.POINTER(bf_event), C.c_size_t, C.POINTER(C.c_size_t)]),
@@ -76,6 +79,9 @@ _SIGNATURES = {
     "bf_op_attention_fwd": (C.c_int, [C.c_int] * 7 + [_P] * 4),
     "bf_op_attention_bwd": (C.c_int, [C.c_int] * 7 + [_P] * 7),
     "bf_op_attention_uses_mfma": (C.c_int, [C.c_int, C.c_int]),
+    "bf_op_embedding_fwd": (C.c_int, [C.c_int] * 5 + [_P, _P, _P, _P, _P]),
+    "bf_op_embedding_bwd": (C.c_int, [C.c_int] * 5 + [_P, _P, _P, _P, C.c_int, _P]),
+    "bf_op_ce_loss": (C.c_int, [C.c_int] * 3 + [_P, _P, C.c_float, _P, _P, _P]),
     "bf_op_adam": (C.c_int, [C.c_size_t, _P, _P, _P, _P, _P, C.c_int] + [C.c_float] * 5 + [_P]),
 }
 
@@ -126,10 +132,10 @@ def _stream():
 
 
 def make_config(S_hidden, N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype=BF_BF16, ckpt_mode=BF_CKPT_NONE,
-                causal=1, kernels=BF_KERNELS_AUTO, queue_depth=0, fuse_wgrad=0, N_loop_min=0, dp_fs=0, seed=0x221105953, init_std=0.02, ln_eps=1e-5,
+                causal=1, kernels=BF_KERNELS_AUTO, queue_depth=0, fuse_wgrad=0, N_loop_min=0, dp_fs=0, S_voc=0, seed=0x221105953, init_std=0.02, ln_eps=1e-5,
                 lr=1e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0):
     return bf_config(S_hidden, N_heads, S_hidden // N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype,
-                     ckpt_mode, causal, kernels, queue_depth, fuse_wgrad, N_loop_min, dp_fs, seed, init_std, ln_eps, lr, beta1, beta2, adam_eps,
+                     ckpt_mode, causal, kernels, queue_depth, fuse_wgrad, N_loop_min, dp_fs, S_voc, seed, init_std, ln_eps, lr, beta1, beta2, adam_eps,
                      weight_decay)
 
 
@@ -205,6 +211,12 @@ class Stack:
                                  apply_optimizer, timing, _stream(), C.byref(rep)))
         return rep
 
+    def bf_run_lm_step(self, schedule, N_loop, N_mb, S_mb, tokens, labels, loss, apply_optimizer=0, timing=0):
+        rep = bf_step_report()
+        check(load().bf_run_lm_step(self.handle, schedule, N_loop, N_mb, S_mb, _ptr(tokens), _ptr(labels), _ptr(loss),
+                                    apply_optimizer, timing, _stream(), C.byref(rep)))
+        return rep
+
     def bf_run_rank_step(self, schedule, N_PP, rank, N_loop, N_mb, S_mb, x, dy, y=None, dx=None, apply_optimizer=0,
                          timing=0):
         rep = bf_step_report()
@@ -266,6 +278,20 @@ def bf_op_attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qk
 
 def bf_op_attention_uses_mfma(S_seq, S_head):
     return bool(load().bf_op_attention_uses_mfma(S_seq, S_head))
+
+
+def bf_op_embedding_fwd(dtype, n_rows, S_seq, S_voc, S_hidden, tokens, e_tok, e_pos, x):
+    check(load().bf_op_embedding_fwd(dtype, n_rows, S_seq, S_voc, S_hidden, _ptr(tokens), _ptr(e_tok), _ptr(e_pos), _ptr(x),
+                                     _stream()))
+
+
+def bf_op_embedding_bwd(dtype, S_mb, S_seq, S_voc, S_hidden, tokens, d, g_tok, g_pos, accumulate_pos):
+    check(load().bf_op_embedding_bwd(dtype, S_mb, S_seq, S_voc, S_hidden, _ptr(tokens), _ptr(d), _ptr(g_tok), _ptr(g_pos),
+                                     accumulate_pos, _stream()))
+
+
+def bf_op_ce_loss(dtype, n_rows, S_voc, z, labels, scale, row_loss, loss_out):
+    check(load().bf_op_ce_loss(dtype, n_rows, S_voc, _ptr(z), _ptr(labels), scale, _ptr(row_loss), _ptr(loss_out), _stream()))
 
 
 def bf_op_adam(n, w, m, v, g, w_lp, t, lr, beta1, beta2, adam_eps, weight_decay):

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libbf.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["stack.hip", "schedule.cpp", "ops_api.hip", "elementwise.hip", "gemm_plain.hip", "gemm_mfma.hip",
-           "attention_plain.hip", "attention_mfma.hip"]
+           "attention_plain.hip", "attention_mfma.hip", "vocab.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

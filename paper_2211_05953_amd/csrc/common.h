@@ -86,6 +86,18 @@ bf_status attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads
                         const void* qkv, const void* ctx, const float* lse, const void* dctx,
                         void* dqkv, float* delta, hipStream_t st);
 
+// Input layer: x[t, :] = e_tok[tok[t], :] + e_pos[t mod S_seq, :] for n_rows = S_mb * S_seq rows (fp32 tables).
+bf_status embedding_fwd(int dtype, int n_rows, int S_seq, int S_voc, int h, const int32_t* tok, const float* e_tok,
+                        const float* e_pos, void* x, hipStream_t st);
+// g_tok[tok[t], :] += d[t, :] (always added: the caller zeroes g_tok before the first micro-batch);
+// g_pos[i, :] = or += sum over the samples of d[b, i, :].
+bf_status embedding_bwd(int dtype, int S_mb, int S_seq, int S_voc, int h, const int32_t* tok, const void* d, float* g_tok,
+                        float* g_pos, int accumulate_pos, hipStream_t st);
+// Softmax cross-entropy of n_rows rows of logits z [n_rows, S_voc] (activation dtype): z is overwritten with
+// (softmax(z) - onehot(label)) * scale, row_loss[t] = (logsumexp - z[label]) * scale, loss_out[0] = their sum.
+bf_status ce_loss(int dtype, int n_rows, int S_voc, void* z, const int32_t* labels, float scale, float* row_loss,
+                  float* loss_out, hipStream_t st);
+
 // Fused Adam over n contiguous parameters; w_lp (bf16 copy) may be null.
 bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t,
                     float lr, float beta1, float beta2, float eps, float wd, hipStream_t st);

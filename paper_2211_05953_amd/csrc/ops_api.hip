@@ -58,6 +58,24 @@ bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N
 
 int bf_op_attention_uses_mfma(int S_seq, int S_head) { return attention_mfma_supported(S_seq, S_head) ? 1 : 0; }
 
+bf_status bf_op_embedding_fwd(int dtype, int n_rows, int S_seq, int S_voc, int S_hidden, const int32_t* tokens,
+                              const float* e_tok, const float* e_pos, void* x, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return embedding_fwd(dtype, n_rows, S_seq, S_voc, S_hidden, tokens, e_tok, e_pos, x, (hipStream_t)stream);
+}
+
+bf_status bf_op_embedding_bwd(int dtype, int S_mb, int S_seq, int S_voc, int S_hidden, const int32_t* tokens, const void* d,
+                              float* g_tok, float* g_pos, int accumulate_pos, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return embedding_bwd(dtype, S_mb, S_seq, S_voc, S_hidden, tokens, d, g_tok, g_pos, accumulate_pos, (hipStream_t)stream);
+}
+
+bf_status bf_op_ce_loss(int dtype, int n_rows, int S_voc, void* z, const int32_t* labels, float scale, float* row_loss,
+                        float* loss_out, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return ce_loss(dtype, n_rows, S_voc, z, labels, scale, row_loss, loss_out, (hipStream_t)stream);
+}
+
 bf_status bf_op_adam(size_t n, float* w, float* m, float* v, const float* g, void* w_lp, int t, float lr, float beta1,
                      float beta2, float adam_eps, float weight_decay, void* stream) {
   return adam_step(n, w, m, v, g, (bf16_t*)w_lp, t, lr, beta1, beta2, adam_eps, weight_decay, (hipStream_t)stream);

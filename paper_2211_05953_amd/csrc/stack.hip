@@ -42,6 +42,10 @@ struct Dims {
   size_t tensor_elems[BF_N_TENSORS];
   size_t tensor_off[BF_N_TENSORS];  // element offset inside a layer
   size_t layer_elems;               // padded
+  // input / output layers (S_voc > 0): e_tok, e_pos, lnf_g, lnf_b, w_out after the last layer
+  size_t voc_elems[BF_N_VOCAB_TENSORS];
+  size_t voc_off[BF_N_VOCAB_TENSORS];  // element offset from the end of the layers
+  size_t voc_total;
 };
 
 void fill_dims(const bf_config& c, Dims* D) {
@@ -55,6 +59,15 @@ void fill_dims(const bf_config& c, Dims* D) {
     off += up(n[i], 128);  // 128 elements: 512 B in fp32, 256 B in bf16
   }
   D->layer_elems = off;
+  const size_t V = c.S_voc > 0 ? (size_t)c.S_voc : 0;
+  const size_t nv[BF_N_VOCAB_TENSORS] = {V * h, V ? (size_t)c.S_seq * h : 0, V ? h : 0, V ? h : 0, V * h};
+  off = 0;
+  for (int i = 0; i < BF_N_VOCAB_TENSORS; ++i) {
+    D->voc_elems[i] = nv[i];
+    D->voc_off[i] = off;
+    off += up(nv[i], 128);
+  }
+  D->voc_total = off;
 }
 
 bool valid_config(const bf_config* c) {
@@ -69,6 +82,7 @@ bool valid_config(const bf_config* c) {
   if (c->queue_depth < 0) { set_error("config: queue_depth < 0"); return false; }
   if (c->fuse_wgrad != 0 && c->fuse_wgrad != 1) { set_error("config: fuse_wgrad must be 0 or 1"); return false; }
   if (c->N_loop_min < 0 || c->N_loop_min > c->N_layers) { set_error("config: N_loop_min outside 0..N_layers"); return false; }
+  if (c->S_voc < 0) { set_error("config: S_voc < 0"); return false; }
   if (c->dp_fs != 0 && c->dp_fs != 1) { set_error("config: dp_fs must be 0 or 1"); return false; }
   if (c->dp_fs && c->dtype != BF_BF16) { set_error("config: dp_fs reconstructs bf16 weights: dtype must be BF_BF16"); return false; }
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
@@ -92,9 +106,11 @@ struct Record {
 };
 
 struct WsLayout {
-  size_t P_total;
+  size_t P_layers, P_total;  // parameters of the layers; with the input / output layers
   size_t off_w32, off_m, off_v, off_g32, off_wlp;
   size_t half_bytes;       // dp_fs: one half of the weight double buffer
+  size_t off_wlp_voc;      // dp_fs: bf16 copy of the input / output layers
+  size_t off_lm, logits_bytes;  // S_voc > 0: buffers of the input / output layers
   size_t rec_bytes;        // one full record (without y)
   size_t y_bytes;          // one [T, h] tensor
   size_t off_records;      // NONE: L * N_mb_max full records (each with y); LAYER: 1 scratch record
@@ -148,7 +164,8 @@ int lps_max(const bf_config& c) {
 void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
   const size_t T = (size_t)c.S_mb_max * c.S_seq;
-  Lo->P_total = D.layer_elems * (size_t)c.N_layers;
+  Lo->P_layers = D.layer_elems * (size_t)c.N_layers;
+  Lo->P_total = Lo->P_layers + D.voc_total;
   size_t off = 0;
   Lo->off_w32 = off; off += up(Lo->P_total * 4);
   Lo->off_m = off; off += up(Lo->P_total * 4);
@@ -156,8 +173,14 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   Lo->off_g32 = off; off += up(Lo->P_total * 4);
   Lo->off_wlp = off;
   Lo->half_bytes = up((size_t)lps_max(c) * D.layer_elems * 2);
-  if (c.dp_fs) off += 2 * Lo->half_bytes;  // double buffer of two stages instead of every layer's copy
-  else if (c.dtype == BF_BF16) off += up(Lo->P_total * 2);
+  Lo->off_wlp_voc = 0;
+  if (c.dp_fs) {
+    off += 2 * Lo->half_bytes;  // double buffer of two stages instead of every layer's copy
+    Lo->off_wlp_voc = off;      // the input / output layers keep a resident copy
+    off += up(D.voc_total * 2);
+  } else if (c.dtype == BF_BF16) {
+    off += up(Lo->P_total * 2);
+  }
   Lo->rec_bytes = rec_sizes(c).total;
   Lo->y_bytes = up(T * c.S_hidden * es);
   Lo->off_records = off;
@@ -186,6 +209,11 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   }
   Lo->off_bhand = off; off += 2 * (size_t)c.N_mb_max * Lo->y_bytes;
   Lo->off_scratch_out = off; off += 2 * Lo->y_bytes;
+  // input / output layers: embedded inputs and loss gradients per micro-batch, the last layer's output,
+  // its normalised form and the gradient of that, LayerNorm statistics, logits of one micro-batch, row losses
+  Lo->off_lm = off;
+  Lo->logits_bytes = up(T * (size_t)(c.S_voc > 0 ? c.S_voc : 0) * es);
+  if (c.S_voc > 0) off += (2 * (size_t)c.N_mb_max + 3) * Lo->y_bytes + up(T * 8) + Lo->logits_bytes + up(T * 4);
   Lo->total = off;
 }
 
@@ -201,6 +229,7 @@ struct bf_stack {
   char* ws;
   float *w32, *m, *v, *g32;
   bf16_t* wlp;            // resident bf16 copy (null in fp32 mode and with dp_fs)
+  bf16_t* wlp_voc;        // dp_fs: resident bf16 copy of the input / output layers
   // dp_fs: the two halves of the weight buffer, the first layer / layer count each holds (-1: nothing
   // valid), the half and first layer the op being issued reads, and the events that order the halves
   bf16_t* fs_half[2];
@@ -226,11 +255,23 @@ namespace bf {
 namespace {
 
 float* param_ptr(bf_stack* s, float* arena, int layer, int tid) {
+  if (tid >= BF_E_TOK) return arena + s->Lo.P_layers + s->D.voc_off[tid - BF_E_TOK];
   return arena + (size_t)layer * s->D.layer_elems + s->D.tensor_off[tid];
+}
+
+// bf16 copy of the master element at offset `off`, or null where there is none
+bf16_t* lp_ptr(bf_stack* s, size_t off) {
+  if (s->wlp) return s->wlp + off;
+  if (s->wlp_voc && off >= s->Lo.P_layers) return s->wlp_voc + (off - s->Lo.P_layers);
+  return nullptr;
 }
 
 // weight operand of the GEMMs: bf16 copy in bf16 mode, the master itself in fp32 mode
 const void* weight_ptr(bf_stack* s, int layer, int tid) {
+  if (tid >= BF_E_TOK) {
+    float* m = param_ptr(s, s->w32, layer, tid);
+    return s->cfg.dtype == BF_BF16 ? (const void*)lp_ptr(s, m - s->w32) : (const void*)m;
+  }
   if (s->cfg.dp_fs)
     return s->fs_half[s->fs_cur] + (size_t)(layer - s->fs_cur_l0) * s->D.layer_elems + s->D.tensor_off[tid];
   const size_t off = (size_t)layer * s->D.layer_elems + s->D.tensor_off[tid];
@@ -484,7 +525,9 @@ int64_t bf_param_count(const bf_config* cfg) {
   fill_dims(*cfg, &D);
   int64_t n = 0;
   for (int i = 0; i < BF_N_TENSORS; ++i) n += (int64_t)D.tensor_elems[i];
-  return n * cfg->N_layers;
+  n *= cfg->N_layers;
+  for (int i = 0; i < BF_N_VOCAB_TENSORS; ++i) n += (int64_t)D.voc_elems[i];
+  return n;
 }
 
 size_t bf_workspace_bytes(const bf_config* cfg) {
@@ -517,6 +560,7 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->v = (float*)(s->ws + s->Lo.off_v);
   s->g32 = (float*)(s->ws + s->Lo.off_g32);
   s->wlp = cfg->dtype == BF_BF16 && !cfg->dp_fs ? (bf16_t*)(s->ws + s->Lo.off_wlp) : nullptr;
+  s->wlp_voc = cfg->dp_fs && cfg->S_voc > 0 ? (bf16_t*)(s->ws + s->Lo.off_wlp_voc) : nullptr;
   for (int i = 0; i < 2; ++i) {
     s->fs_half[i] = cfg->dp_fs ? (bf16_t*)(s->ws + s->Lo.off_wlp + i * s->Lo.half_bytes) : nullptr;
     s->fs_l0[i] = s->fs_n[i] = -1;
@@ -570,7 +614,17 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
     if ((r = fill_f32(s->D.tensor_elems[BF_LN1_G], param_ptr(s, s->w32, l, BF_LN1_G), 1.f, st)) != BF_OK) return fail(r);
     if ((r = fill_f32(s->D.tensor_elems[BF_LN2_G], param_ptr(s, s->w32, l, BF_LN2_G), 1.f, st)) != BF_OK) return fail(r);
   }
+  if (cfg->S_voc > 0) {
+    const int wt[3] = {BF_E_TOK, BF_E_POS, BF_W_OUT};
+    for (int i = 0; i < 3; ++i) {
+      const uint64_t sd = cfg->seed * 0x9E3779B97F4A7C15ull + (uint64_t)cfg->N_layers * BF_N_TENSORS + wt[i];
+      if ((r = init_normal(s->D.voc_elems[wt[i] - BF_E_TOK], param_ptr(s, s->w32, 0, wt[i]), sd, cfg->init_std, st)) != BF_OK)
+        return fail(r);
+    }
+    if ((r = fill_f32(s->D.voc_elems[BF_LNF_G - BF_E_TOK], param_ptr(s, s->w32, 0, BF_LNF_G), 1.f, st)) != BF_OK) return fail(r);
+  }
   if (s->wlp && (r = cast_f32_to_bf16(P, s->w32, s->wlp, st)) != BF_OK) return fail(r);
+  if (s->wlp_voc && (r = cast_f32_to_bf16(s->D.voc_total, s->w32 + s->Lo.P_layers, s->wlp_voc, st)) != BF_OK) return fail(r);
   hipError_t e = hipStreamSynchronize(st);
   if (e != hipSuccess) { set_error("bf_create_stack: initialisation failed: %s", hipGetErrorString(e)); return fail(BF_EDEVICE); }
   *out = s;
@@ -591,14 +645,19 @@ bf_status bf_destroy_stack(bf_stack* s) {
 }
 
 size_t bf_tensor_elems(const bf_stack* s, int tensor_id) {
-  if (!s || tensor_id < 0 || tensor_id >= BF_N_TENSORS) return 0;
-  return s->D.tensor_elems[tensor_id];
+  if (!s || tensor_id < 0 || tensor_id >= BF_N_TENSORS + BF_N_VOCAB_TENSORS) return 0;
+  return tensor_id < BF_N_TENSORS ? s->D.tensor_elems[tensor_id] : s->D.voc_elems[tensor_id - BF_E_TOK];
 }
 
 static bf_status check_tensor(bf_stack* s, int layer, int tid, const void* host, size_t n) {
   if (!s || !host) { set_error("null stack or host pointer"); return BF_EINVAL; }
-  if (layer < 0 || layer >= s->cfg.N_layers || tid < 0 || tid >= BF_N_TENSORS) { set_error("bad layer %d or tensor id %d", layer, tid); return BF_EINVAL; }
-  if (n != s->D.tensor_elems[tid]) { set_error("tensor %d has %zu elements, caller passed %zu", tid, s->D.tensor_elems[tid], n); return BF_EINVAL; }
+  const bool voc = tid >= BF_E_TOK && tid < BF_E_TOK + BF_N_VOCAB_TENSORS && s->cfg.S_voc > 0;
+  // the input / output layers are addressed as pseudo-layer N_layers
+  if (voc ? layer != s->cfg.N_layers : (layer < 0 || layer >= s->cfg.N_layers || tid < 0 || tid >= BF_N_TENSORS)) {
+    set_error("bad layer %d or tensor id %d", layer, tid);
+    return BF_EINVAL;
+  }
+  if (n != bf_tensor_elems(s, tid)) { set_error("tensor %d has %zu elements, caller passed %zu", tid, bf_tensor_elems(s, tid), n); return BF_EINVAL; }
   return BF_OK;
 }
 
@@ -607,8 +666,8 @@ bf_status bf_set_params(bf_stack* s, int layer, int tid, const float* host_src, 
   BF_HIP_CHECK(hipDeviceSynchronize());
   float* dst = param_ptr(s, s->w32, layer, tid);
   BF_HIP_CHECK(hipMemcpy(dst, host_src, n * sizeof(float), hipMemcpyHostToDevice));
-  if (s->wlp) {
-    BF_TRY(cast_f32_to_bf16(n, dst, s->wlp + (dst - s->w32), nullptr));
+  if (bf16_t* lp = lp_ptr(s, dst - s->w32)) {
+    BF_TRY(cast_f32_to_bf16(n, dst, lp, nullptr));
     BF_HIP_CHECK(hipDeviceSynchronize());
   }
   s->fs_l0[0] = s->fs_l0[1] = -1;  // dp_fs: whatever the double buffer holds is stale now
@@ -685,16 +744,20 @@ bf_status bf_schedule_trace(int schedule, int N_PP, int N_loop, int N_mb, int ra
 // its input and incoming gradient from the caller's buffers and leaves its output and outgoing
 // gradient there (one tensor per local stage and micro-batch), as a rank that receives from and
 // sends to its neighbours would.
+// lm: null, or the token ids, labels and loss output of a step with the input and output layers
+// (chained only; x / dy / y / dx are then unused).
+struct LmIO { const int32_t* tokens; const int32_t* labels; float* loss; };
+
 static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bool chained, int N_loop, int N_mb, int S_mb,
-                               const void* x, const void* dy, void* y, void* dx, int apply_optimizer, int timing,
-                               void* stream, bf_step_report* report) {
+                               const void* x, const void* dy, void* y, void* dx, const LmIO* lm, int apply_optimizer,
+                               int timing, void* stream, bf_step_report* report) {
   if (!s) { set_error("bf_run_step: null stack"); return BF_EINVAL; }
   const bf_config& c = s->cfg;
   if (schedule != BF_SCHED_BF && schedule != BF_SCHED_DF) { set_error("bf_run_step: unknown schedule %d", schedule); return BF_EINVAL; }
   if (N_loop < 1 || c.N_layers % N_loop) { set_error("bf_run_step: N_loop = %d must divide N_layers = %d", N_loop, c.N_layers); return BF_EINVAL; }
   if (N_mb < 1 || N_mb > c.N_mb_max) { set_error("bf_run_step: N_mb = %d outside 1..%d", N_mb, c.N_mb_max); return BF_EINVAL; }
   if (S_mb < 1 || S_mb > c.S_mb_max) { set_error("bf_run_step: S_mb = %d outside 1..%d", S_mb, c.S_mb_max); return BF_EINVAL; }
-  if (!x || !dy) { set_error("bf_run_step: x and dy must not be null"); return BF_EINVAL; }
+  if (!lm && (!x || !dy)) { set_error("bf_run_step: x and dy must not be null"); return BF_EINVAL; }
   int cur = -1;
   BF_HIP_CHECK(hipGetDevice(&cur));
   if (cur != s->device) { set_error("bf_run_step: stack lives on device %d, current device is %d", s->device, cur); return BF_EINVAL; }
@@ -708,6 +771,24 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   // gradients a stage received stay intact until its fused weight-gradient products have run
   auto bhand = [&](int stage, int m) { return s->ws + s->Lo.off_bhand + ((size_t)(stage & 1) * c.N_mb_max + m) * s->Lo.y_bytes; };
   char* scratch_out = s->ws + s->Lo.off_scratch_out;
+  // input / output layers: embedded input and loss gradient of every micro-batch, then one micro-batch's
+  // last-layer output, its normalised form, the gradient of that, LayerNorm statistics, logits, row losses
+  char* lm_base = s->ws + s->Lo.off_lm;
+  auto emb_x = [&](int m) { return lm_base + (size_t)m * s->Lo.y_bytes; };
+  auto dy_lm = [&](int m) { return lm_base + ((size_t)c.N_mb_max + m) * s->Lo.y_bytes; };
+  char* y_top = lm_base + 2 * (size_t)c.N_mb_max * s->Lo.y_bytes;
+  char* hn = y_top + s->Lo.y_bytes;
+  char* dhn = hn + s->Lo.y_bytes;
+  float* lnf_stats = (float*)(dhn + s->Lo.y_bytes);
+  char* logits = (char*)lnf_stats + up((size_t)c.S_mb_max * c.S_seq * 8);
+  float* row_loss = (float*)(logits + s->Lo.logits_bytes);
+  const int T_mb = S_mb * c.S_seq;
+  if (lm) {
+    x = emb_x(0);
+    dy = dy_lm(0);
+    y = nullptr;
+    dx = nullptr;
+  }
   const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c) && per_stage <= lps_max(c);
   if (c.dp_fs && per_stage > lps_max(c)) {
     set_error("bf_run_step: dp_fs holds stages of up to %d layers (N_loop_min = %d), N_loop = %d gives %d", lps_max(c),
@@ -721,7 +802,8 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   // local index of an op's stage: the rank holds the global stages ls * N_PP + rank (Sec. 4.1)
   auto local = [&](const SchedOp& o) { return o.stage / N_PP; };
   // the caller's tensor of (local stage, micro-batch)
-  auto io_off = [&](int ls, int m) { return ((size_t)(chained ? 0 : ls) * N_mb + m) * mb_bytes; };
+  const size_t io_stride = lm ? s->Lo.y_bytes : mb_bytes;
+  auto io_off = [&](int ls, int m) { return ((size_t)(chained ? 0 : ls) * N_mb + m) * io_stride; };
 
   // dp_fs: cut the order into intervals (runs of one stage in one direction) and decide, in order,
   // which half of the double buffer serves each and whether the stage has to be reconstructed into
@@ -795,12 +877,39 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
       if (j + 1 < (int)ivs.size() && ivs[j + 1].load) BF_TRY(reconstruct(j + 1));
     }
     if (op.op == 0) {
+      if (lm && l0 == 0) {
+        if (m == 0)  // the token rows' gradients are added to, use by use: start from zero
+          BF_TRY(fill_f32(s->D.voc_elems[0], param_ptr(s, s->g32, 0, BF_E_TOK), 0.f, st));
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (8.0 + es), st, [&] {
+          return embedding_fwd(c.dtype, T_mb, c.S_seq, c.S_voc, c.S_hidden, lm->tokens + (size_t)m * T_mb,
+                               param_ptr(s, s->w32, 0, BF_E_TOK), param_ptr(s, s->w32, 0, BF_E_POS), emb_x(m), st);
+        }));
+      }
       for (int l = l0; l < l1; ++l) {
         Record R = record_for(s, l, m);
         void* out = R.y;
-        if (is_top(l)) out = y ? (char*)y + io_off(ls, m) : scratch_out;
+        if (is_top(l)) out = lm ? y_top : y ? (char*)y + io_off(ls, m) : scratch_out;
         BF_TRY(layer_forward(s, l, S_mb, input_of(l, m), R, out, false, st));
         ++live;
+      }
+      if (lm && l1 == c.N_layers) {
+        // output layer, loss and their backward at once: nothing downstream has to be waited for
+        const int h = c.S_hidden, V = c.S_voc;
+        float* gw = param_ptr(s, s->g32, 0, BF_W_OUT);
+        BF_TRY(p_ln_fwd(s, T_mb, h, y_top, param_ptr(s, s->w32, 0, BF_LNF_G), param_ptr(s, s->w32, 0, BF_LNF_B), c.ln_eps, hn,
+                        lnf_stats, st));
+        GemmArgs g{T_mb, V, h, hn, weight_ptr(s, 0, BF_W_OUT), logits, nullptr, nullptr, nullptr, 0};
+        BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
+        const float scale = 1.0f / ((float)N_mb * (float)T_mb);
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, 3.0 * es * T_mb * V, st, [&] {
+          return ce_loss(c.dtype, T_mb, V, logits, lm->labels + (size_t)m * T_mb, scale, row_loss, lm->loss + m, st);
+        }));
+        g = GemmArgs{T_mb, h, V, logits, weight_ptr(s, 0, BF_W_OUT), dhn, nullptr, nullptr, nullptr, 0};
+        BF_TRY(p_gemm(s, L_NN, E_NONE, g, st));
+        g = GemmArgs{V, h, T_mb, logits, hn, gw, nullptr, nullptr, nullptr, m > 0};
+        BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+        BF_TRY(p_ln_bwd(s, T_mb, h, dhn, y_top, param_ptr(s, s->w32, 0, BF_LNF_G), lnf_stats, nullptr, dy_lm(m),
+                        param_ptr(s, s->g32, 0, BF_LNF_G), param_ptr(s, s->g32, 0, BF_LNF_B), m > 0, st));
       }
     } else {
       for (int l = l1 - 1; l >= l0; --l) {
@@ -825,12 +934,19 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, st));
         --live;
       }
+      if (lm && l0 == 0) {
+        char* dxe = scratch_out + s->Lo.y_bytes;  // where layer 0 left the gradient of its input
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (es + 16.0), st, [&] {
+          return embedding_bwd(c.dtype, S_mb, c.S_seq, c.S_voc, c.S_hidden, lm->tokens + (size_t)m * T_mb, dxe,
+                               param_ptr(s, s->g32, 0, BF_E_TOK), param_ptr(s, s->g32, 0, BF_E_POS), m > 0, st);
+        }));
+      }
       if (fuse && m == N_mb - 1) {
         // every micro-batch of the stage is through: one weight-gradient product per matrix
         for (int l = l1 - 1; l >= l0; --l) {
           const void* dy0;
           size_t stride;
-          if (is_top(l)) { dy0 = (const char*)dy + io_off(ls, 0); stride = mb_bytes / es; }
+          if (is_top(l)) { dy0 = (const char*)dy + io_off(ls, 0); stride = io_stride / es; }
           else if (l == l1 - 1) { dy0 = bhand(ls, 0); stride = s->Lo.y_bytes / es; }
           else { dy0 = grad_rec(s, l - l0, 0).dy; stride = s->Lo.grec_bytes / es; }
           BF_TRY(layer_wgrad_fused(s, l, l - l0, S_mb, N_mb, dy0, stride, st));
@@ -856,6 +972,19 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
           return adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
                            c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as);
         }));
+        if (lm) {
+          // the input layer steps with the first stage, the output layer with the last
+          auto voc_range = [&](int first, int last) {
+            const size_t o = s->Lo.P_layers + s->D.voc_off[first - BF_E_TOK];
+            const size_t cnt = s->D.voc_off[last - BF_E_TOK] + s->D.voc_elems[last - BF_E_TOK] - s->D.voc_off[first - BF_E_TOK];
+            return timed(s, BF_K_ADAM, 0.0, (double)cnt * (lp_ptr(s, o) ? 30.0 : 28.0), as, [&] {
+              return adam_step(cnt, s->w32 + o, s->m + o, s->v + o, s->g32 + o, lp_ptr(s, o), s->step, c.lr, c.beta1, c.beta2,
+                               c.adam_eps, c.weight_decay, as);
+            });
+          };
+          if (l0 == 0) BF_TRY(voc_range(BF_E_TOK, BF_E_POS));
+          if (l1 == c.N_layers) BF_TRY(voc_range(BF_LNF_G, BF_W_OUT));
+        }
         // dp_fs: the halves hold this stage's old weights at most until here
         for (int i = 0; i < 2; ++i) if (s->fs_l0[i] == l0) s->fs_l0[i] = -1;
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam + 1], as));
@@ -882,14 +1011,15 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     const double T = (double)S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
     const double lin = 2.0 * T * (3 * h * h + h * h + 2 * h * f);
     const double att = 4.0 * c.S_seq * T * h;  // full S_seq x S_seq scores
-    const double lm = (double)c.N_layers * N_mb;
-    report->flops_model = 3.0 * (lin + att) * lm;
-    report->flops_paper = 4.0 * (lin + att) * lm;
+    const double lm_ = (double)c.N_layers * N_mb;
+    const double head = lm ? 2.0 * T * h * (double)c.S_voc * N_mb : 0.0;  // output projection, forward
+    report->flops_model = 3.0 * (lin + att) * lm_ + 3.0 * head;
+    report->flops_paper = 4.0 * (lin + att) * lm_ + 3.0 * head;  // Eq. compute: no recomputation of the output layer
     const double att_f = c.causal ? att / 2 : att;
     // backward attention runs 7 score-sized products (dq pass: S, dP, dQ; dk/dv pass: S, dP, dK, dV) vs 2 forward
     double exec = 3.0 * lin + att_f * (1.0 + 3.5);
     if (c.ckpt_mode == BF_CKPT_LAYER) exec += (lin - 2.0 * T * h * f) + att_f;
-    report->flops_executed = exec * lm;
+    report->flops_executed = exec * lm_ + 3.0 * head;
     report->peak_ckpt_count = peak_live;
     report->peak_ckpt_bytes = peak_live * (int64_t)mb_bytes;
     RecSizes rs = rec_sizes(c);
@@ -937,14 +1067,27 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
 
 bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb, const void* x, const void* dy, void* y,
                       void* dx, int apply_optimizer, int timing, void* stream, bf_step_report* report) {
-  return run_rank_step(s, schedule, 1, 0, true, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer, timing, stream, report);
+  return run_rank_step(s, schedule, 1, 0, true, N_loop, N_mb, S_mb, x, dy, y, dx, nullptr, apply_optimizer, timing, stream,
+                       report);
+}
+
+bf_status bf_run_lm_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb, const int32_t* tokens,
+                         const int32_t* labels, float* loss, int apply_optimizer, int timing, void* stream,
+                         bf_step_report* report) {
+  if (!s) { set_error("bf_run_lm_step: null stack"); return BF_EINVAL; }
+  if (s->cfg.S_voc <= 0) { set_error("bf_run_lm_step: the stack was created without input / output layers (S_voc = 0)"); return BF_ESTATE; }
+  if (!tokens || !labels || !loss) { set_error("bf_run_lm_step: tokens, labels and loss must not be null"); return BF_EINVAL; }
+  const LmIO lm{tokens, labels, loss};
+  return run_rank_step(s, schedule, 1, 0, true, N_loop, N_mb, S_mb, nullptr, nullptr, nullptr, nullptr, &lm, apply_optimizer,
+                       timing, stream, report);
 }
 
 bf_status bf_run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, int N_loop, int N_mb, int S_mb, const void* x,
                            const void* dy, void* y, void* dx, int apply_optimizer, int timing, void* stream,
                            bf_step_report* report) {
   if (N_PP < 1 || rank < 0 || rank >= N_PP) { set_error("bf_run_rank_step: rank %d outside 0..N_PP-1 (N_PP = %d)", rank, N_PP); return BF_EINVAL; }
-  return run_rank_step(s, schedule, N_PP, rank, false, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer, timing, stream, report);
+  return run_rank_step(s, schedule, N_PP, rank, false, N_loop, N_mb, S_mb, x, dy, y, dx, nullptr, apply_optimizer, timing, stream,
+                       report);
 }
 
 }  // extern "C"
