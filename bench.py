@@ -29,30 +29,42 @@ WORKLOADS = {
     "c3": (8, 4, 8192, 64, 32768, 2048, 1, 16, "bf16", "none"),
     "c4": (8, 4, 8192, 64, 32768, 2048, 4, 4, "bf16", "none"),
     "c5": (16, 16, 6144, 48, 24576, 2048, 1, 32, "bf16", "layer"),
+    "c3v": (8, 4, 8192, 64, 32768, 2048, 1, 16, "bf16", "none"),
+    "bert": (8, 4, 8192, 64, 32768, 1024, 1, 16, "bf16", "none"),
 }
+# workloads that differ from the default causal stack without input / output layers
+EXTRA = {"c3v": {"S_voc": 50304}, "bert": {"causal": 0}}
 WORKLOAD_TEXT = {
     "c1": "tiny GPT stack fp32 (parity case)",
     "c2": "1.3B-shaped stack",
     "c3": "52B-shaped rank share, S_mb=1, N_mb=16",
     "c4": "52B-shaped rank share, S_mb=4, N_mb=4",
     "c5": "deep-loop stress case, N_loop=16, N_mb=32, per-layer checkpoints",
+    "c3v": "c3 on token ids: embedding + 8 layers + final LayerNorm, 50304-way output projection and loss",
+    "bert": "52B-shaped rank share as the paper measured it: bidirectional attention, S_seq=1024",
 }
 
 
 def time_steps(st, bf, schedule, N_loop, N_mb, S_mb, x, dy, y, dx, steps, warmup, timing):
+    """x, dy, y, dx: activations in and out; or token ids, labels, per-micro-batch loss, None for the
+    step with input and output layers."""
     import torch
+    if dx is None:
+        run = lambda tm: st.bf_run_lm_step(schedule, N_loop, N_mb, S_mb, x, dy, y, apply_optimizer=1, timing=tm)
+    else:
+        run = lambda tm: st.bf_run_step(schedule, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer=1, timing=tm)
     for _ in range(warmup):
-        st.bf_run_step(schedule, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer=1, timing=0)
+        run(0)
     torch.cuda.synchronize()
     reports = []
     t0 = time.perf_counter()
     for _ in range(steps):
-        reports.append(st.bf_run_step(schedule, N_loop, N_mb, S_mb, x, dy, y, dx, apply_optimizer=1, timing=timing))
+        reports.append(run(timing))
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps, reports
 
 
-def cpu_baseline(w, budget_note=True):
+def cpu_baseline(w, causal=True):
     """The CPU oracle, as it stands, on one layer and one micro-batch of the same workload
     (forward + backward), timed on the host cores."""
     import numpy as np
@@ -66,7 +78,7 @@ def cpu_baseline(w, budget_note=True):
     del params
     x, dy = bf_inputs.make_batch(1, 1, S_mb, S_seq, h, bf16=dtype == "bf16")
     t0 = time.perf_counter()
-    K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), K.SCHED_BF, 1, a)
+    K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), K.SCHED_BF, 1, a, causal=causal)
     dt = time.perf_counter() - t0
     flops = 3.0 * float(F.fwd_flops_layer_mb(h, S_seq, S_mb)) if f == 4 * h else None
     try:
@@ -109,7 +121,8 @@ def main():
     b16 = dtype == "bf16"
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
                          ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
-                         fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop)
+                         fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop, **EXTRA.get(args.workload, {}))
+    S_voc = cfg.S_voc
     torch.cuda.set_device(0)
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
@@ -124,9 +137,17 @@ def main():
     gen.manual_seed(0x221105953)
     td = torch.bfloat16 if b16 else torch.float32
     shape = (N_mb, S_mb, S_seq, h)
-    x = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
-    dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
-    y, dx = torch.empty_like(x), torch.empty_like(x)
+    if S_voc:
+        # token ids with a Zipf-like law (a few frequent tokens, a long tail), labels = next token
+        wz = 1.0 / torch.arange(1, S_voc + 1, device="cuda:0", dtype=torch.float64) ** 1.1
+        stream = torch.multinomial(wz / wz.sum(), N_mb * S_mb * (S_seq + 1), replacement=True, generator=gen)
+        stream = stream.to(torch.int32).reshape(N_mb, S_mb, S_seq + 1)
+        x, dy = stream[..., :-1].contiguous(), stream[..., 1:].contiguous()
+        y, dx = torch.zeros(N_mb, device="cuda:0"), None
+    else:
+        x = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+        dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
 
     sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 2)
     r = rep_bf[-1]
@@ -169,7 +190,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "N_layers": Lyr, "N_loop": N_loop,
                    "S_hidden": h, "N_heads": a, "S_mlp": f, "S_seq": S_seq, "S_mb": S_mb, "N_mb": N_mb,
-                   "schedule": "BF", "ckpt": ckpt, "fuse_wgrad": not args.no_fuse_wgrad, "tokens_per_step": N_mb * S_mb * S_seq},
+                   "schedule": "BF", "ckpt": ckpt, "causal": int(cfg.causal), "S_voc": int(S_voc), "fuse_wgrad": not args.no_fuse_wgrad, "tokens_per_step": N_mb * S_mb * S_seq},
         "frac_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
         "paper_eq_tflops": r.flops_paper / sec_bf / 1e12,
         "executed_tflops": r.flops_executed / sec_bf / 1e12,
@@ -206,7 +227,7 @@ def main():
     del x, dy, y, dx
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w)
+        line["cpu_baseline"] = cpu_baseline(w, causal=bool(EXTRA.get(args.workload, {}).get("causal", 1)))
     print(json.dumps(line))
 
 

@@ -72,33 +72,70 @@ __global__ __launch_bounds__(ROW_THREADS) void embedding_fwd_kernel(const int32_
 // Token-embedding gradient without atomics: the workgroup of the first position that uses a token
 // sums the rows of every position using it, in ascending position, and adds the sum to that
 // token's gradient row; workgroups of later uses leave at once.  Distinct tokens, distinct rows.
+// The positions are found by one wavefront (ballot compaction of a window of ids into LDS, in
+// order); a thread keeps up to NCH column chunks in registers so the ids are scanned once.
 template <typename T, int VEC>
 __global__ __launch_bounds__(ROW_THREADS) void embedding_bwd_tok_kernel(const int32_t* __restrict__ tok,
                                                                         const T* __restrict__ d, float* __restrict__ g_tok,
                                                                         int n_rows, int S_voc, int h) {
+  constexpr int WIN = 2048, NCH = 8, GROUP = ROW_THREADS * VEC * NCH;
+  __shared__ int list[WIN];
+  __shared__ int n_list;
   const int t = blockIdx.x;
   const int v = tok[t];
   if (v < 0 || v >= S_voc) return;
   int earlier = 0;
   for (int i = threadIdx.x; i < t; i += ROW_THREADS) earlier |= tok[i] == v;
   if (__syncthreads_or(earlier)) return;
+  const int lane = threadIdx.x & 63;
   float* gr = g_tok + (size_t)v * h;
-  for (int c = threadIdx.x * VEC; c < h; c += ROW_THREADS * VEC) {
-    float acc[VEC];
+  for (int c0 = 0; c0 < h; c0 += GROUP) {
+    float acc[NCH][VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
-    for (int i = t; i < n_rows; ++i) {
-      if (tok[i] != v) continue;  // uniform over the workgroup
-      float r[VEC];
-      load_vec<T, VEC>(d + (size_t)i * h + c, r);
+    for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) acc[j] += r[j];
+      for (int j = 0; j < VEC; ++j) acc[ch][j] = 0.f;
+    for (int w0 = t; w0 < n_rows; w0 += WIN) {
+      const int end = w0 + WIN < n_rows ? w0 + WIN : n_rows;
+      __syncthreads();  // the list of the previous window has been read
+      if (threadIdx.x < 64) {
+        int count = 0;
+        for (int base = w0; base < end; base += 64) {
+          const int i = base + lane;
+          const bool hit = i < end && tok[i] == v;
+          const unsigned long long mask = __ballot(hit);
+          if (hit) list[count + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+          count += __popcll(mask);
+        }
+        if (lane == 0) n_list = count;
+      }
+      __syncthreads();
+      const int n = n_list;
+      for (int k = 0; k < n; ++k) {
+        const T* dr = d + (size_t)list[k] * h;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          const int c = c0 + (ch * ROW_THREADS + (int)threadIdx.x) * VEC;
+          if (c < h) {
+            float r[VEC];
+            load_vec<T, VEC>(dr + c, r);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[ch][j] += r[j];
+          }
+        }
+      }
     }
-    float g[VEC];
-    load_vec<float, VEC>(gr + c, g);
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) g[j] += acc[j];
-    store_vec<float, VEC>(gr + c, g);
+    for (int ch = 0; ch < NCH; ++ch) {
+      const int c = c0 + (ch * ROW_THREADS + (int)threadIdx.x) * VEC;
+      if (c < h) {
+        float g[VEC];
+        load_vec<float, VEC>(gr + c, g);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) g[j] += acc[ch][j];
+        store_vec<float, VEC>(gr + c, g);
+      }
+    }
   }
 }
 
