@@ -93,6 +93,60 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_fwd_kernel(const T* __restrict
   }
 }
 
+// Rows of at most ROW_THREADS * VEC * NIT elements stay in registers: the row is read once and the
+// three passes (mean, variance, output) run on the copy.
+template <typename T, int VEC, int NIT>
+__global__ __launch_bounds__(ROW_THREADS) void ln_fwd_reg_kernel(const T* __restrict__ x, const float* __restrict__ g,
+                                                                 const float* __restrict__ b, T* __restrict__ y,
+                                                                 float* __restrict__ stats, int h, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * (size_t)h;
+  T* yr = y + row * (size_t)h;
+  float v[NIT][VEC];
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (i < h) {
+      load_vec<T, VEC>(xr + i, v[it]);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) s += v[it][j];
+    }
+  }
+  const float mean = block_sum(s, red) / (float)h;
+  float q = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (i < h) {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        const float d = v[it][j] - mean;
+        q += d * d;
+      }
+    }
+  }
+  const float var = block_sum(q, red) / (float)h;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (threadIdx.x == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (i < h) {
+      float gg[VEC], bb[VEC], o[VEC];
+      load_vec<float, VEC>(g + i, gg);
+      load_vec<float, VEC>(b + i, bb);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) o[j] = (v[it][j] - mean) * rstd * gg[j] + bb[j];
+      store_vec<T, VEC>(yr + i, o);
+    }
+  }
+}
+
 // ------------------------------------------------------ LayerNorm backward, input gradient
 // dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)) [+ dres],  dxhat = dy * g
 template <typename T, int VEC>
@@ -137,6 +191,56 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_kernel(const T* __restr
       o[j] = rstd * (d[j] * gg[j] - s1 - xh * s2) + r[j];
     }
     store_vec<T, VEC>(dx + row * (size_t)h + i, o);
+  }
+}
+
+// The same with dy and x of the row held in registers between the two passes.
+template <typename T, int VEC, int NIT>
+__global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_reg_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                    const float* __restrict__ g,
+                                                                    const float* __restrict__ stats,
+                                                                    const T* __restrict__ dres, T* __restrict__ dx, int h) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* dyr = dy + row * (size_t)h;
+  const T* xr = x + row * (size_t)h;
+  const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+  float dh[NIT][VEC], xh[NIT][VEC];  // dy * g and the normalised input
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (i < h) {
+      float gg[VEC];
+      load_vec<T, VEC>(dyr + i, dh[it]);
+      load_vec<T, VEC>(xr + i, xh[it]);
+      load_vec<float, VEC>(g + i, gg);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        dh[it][j] *= gg[j];
+        xh[it][j] = (xh[it][j] - mean) * rstd;
+        s1 += dh[it][j];
+        s2 += dh[it][j] * xh[it][j];
+      }
+    }
+  }
+  s1 = block_sum(s1, red) / (float)h;
+  s2 = block_sum(s2, red) / (float)h;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (i < h) {
+      float r[VEC], o[VEC];
+      if (dres) {
+        load_vec<T, VEC>(dres + row * (size_t)h + i, r);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) r[j] = 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) o[j] = rstd * (dh[it][j] - s1 - xh[it][j] * s2) + r[j];
+      store_vec<T, VEC>(dx + row * (size_t)h + i, o);
+    }
   }
 }
 
@@ -318,7 +422,10 @@ bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, 
   if (T < 1 || h < 1 || !x || !g || !b || !y || !stats) { set_error("layernorm_fwd: bad argument"); return BF_EINVAL; }
   if (dtype == BF_BF16) {
     const bool vec = h % 8 == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b);
-    if (vec) ln_fwd_kernel<bf16_t, 8><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+    if (vec && h <= ROW_THREADS * 8) ln_fwd_reg_kernel<bf16_t, 8, 1><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+    else if (vec && h <= ROW_THREADS * 16) ln_fwd_reg_kernel<bf16_t, 8, 2><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+    else if (vec && h <= ROW_THREADS * 32) ln_fwd_reg_kernel<bf16_t, 8, 4><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
+    else if (vec) ln_fwd_kernel<bf16_t, 8><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
     else ln_fwd_kernel<bf16_t, 1><<<T, ROW_THREADS, 0, st>>>((const bf16_t*)x, g, b, (bf16_t*)y, stats, h, eps);
   } else {
     const bool vec = h % 4 == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b);
@@ -332,7 +439,14 @@ bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, 
 template <typename T, int VEC>
 static void launch_ln_bwd(int T_rows, int h, const void* dy, const void* x, const float* g, const float* stats,
                           const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st) {
-  ln_bwd_dx_kernel<T, VEC><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
+  if (VEC > 1 && h <= ROW_THREADS * VEC)
+    ln_bwd_dx_reg_kernel<T, VEC, 1><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
+  else if (VEC > 1 && h <= ROW_THREADS * VEC * 2)
+    ln_bwd_dx_reg_kernel<T, VEC, 2><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
+  else if (VEC > 1 && h <= ROW_THREADS * VEC * 4)
+    ln_bwd_dx_reg_kernel<T, VEC, 4><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
+  else
+    ln_bwd_dx_kernel<T, VEC><<<T_rows, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, h);
   launch_col_reduce<T, VEC, 1>(dy, x, stats, dg, db, T_rows, h, accumulate, st);
 }
 
