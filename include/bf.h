@@ -75,7 +75,7 @@ typedef struct {
                            the device (App. D.2, bounded kernel queue); 0: unbounded */
   int32_t fuse_wgrad;   /* 1: in breadth-first order the weight-matrix gradients of a stage are taken once per
                            stage, as one product over all its micro-batches, after the stage's last backward
-                           ("aggregates the steps by layer", Sec. 4.2): the fp32 main-grad is written once
+                           (breadth-first groups the work by stage, Sec. 4.2): the fp32 main-grad is written once
                            instead of read-modified-written N_mb times.  The sum over micro-batches is then
                            one long fp32 contraction, so BF and DF gradients agree to rounding, not bitwise.
                            The per-micro-batch operands of one stage are kept until then (with

@@ -957,7 +957,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     s->trace.push_back(bf_event{op.op, op.stage, m, live});
 
     if (op.op == 1 && m == N_mb - 1) {
-      // this stage's gradient is final (Sec. 4.2: breadth-first aggregates the steps by layer)
+      // this stage's gradient is final (Sec. 4.2: breadth-first groups the work by stage)
       if (apply_optimizer) {
         const size_t off = (size_t)l0 * s->D.layer_elems, n = (size_t)per_stage * s->D.layer_elems;
         // breadth-first: the update runs beside the backward of the earlier stages; depth-first
