@@ -15,6 +15,9 @@
 // row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
 #include <type_traits>
 
+#include <stdlib.h>
+#include <string.h>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -30,6 +33,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int BK = 64;
+// measured throughput of a compute unit on the smaller tiles relative to the 256 x 256 tile
+constexpr double TILE_RATE_MID = 0.88, TILE_RATE_SMALL = 0.75;
 constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
 
 template <int BM_, int BN_, int WM_, int WN_>
@@ -345,6 +350,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 }
 
 typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave
+typedef Tile<256, 128, 4, 2> TileMid;    // 8 waves, 64 x 64 per wave
 typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
 
 template <typename TL, bool AK, bool BKC>
@@ -392,13 +398,31 @@ bf_status by_layout(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   return launch<TL, false, false, E_ACCUM, float>(a, st);
 }
 
-// The 256 x 256 tile needs enough tiles that the last round over the 256 compute units is mostly full.
-inline bool big_fits(int M, int N) {
-  if (M % 256 || N % 256) return false;
-  const long tiles = (long)(M / 256) * (N / 256), rounds = (tiles + 255) / 256;
-  return tiles * 10 >= rounds * 256 * 8;
-}
 inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
+
+// Tile choice: the grid runs in rounds over the chip's workgroup slots, so the estimated time of a
+// tile shape is rounds x tile area / (throughput of a slot relative to a compute unit running the
+// 256 x 256 tile).  Larger tiles reuse more per LDS byte; smaller ones fill the last round.
+// 0: 256 x 256 (one per compute unit), 1: 256 x 128 (one), 2: 128 x 128 (two).
+inline int choose_tile(int M, int N) {
+  static const int forced = [] {
+    const char* e = getenv("BF_GEMM_TILE");  // tuning override: "big", "mid", "small"
+    return !e ? -1 : !strcmp(e, "big") ? 0 : !strcmp(e, "mid") ? 1 : !strcmp(e, "small") ? 2 : -1;
+  }();
+  const int bm[3] = {256, 256, 128}, bn[3] = {256, 128, 128};
+  const long slots[3] = {256, 256, 512};
+  const double rate[3] = {1.0, TILE_RATE_MID, TILE_RATE_SMALL / 2};
+  int best = -1;
+  double best_t = 0;
+  for (int i = 0; i < 3; ++i) {
+    if (M % bm[i] || N % bn[i]) continue;
+    if (i == forced) return i;
+    const long tiles = (long)(M / bm[i]) * (N / bn[i]), rounds = (tiles + slots[i] - 1) / slots[i];
+    const double t = (double)rounds * bm[i] * bn[i] / rate[i];
+    if (best < 0 || t < best_t) { best = i; best_t = t; }
+  }
+  return best;
+}
 
 }  // namespace
 
@@ -418,8 +442,11 @@ bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
-  if (big_fits(a.M, a.N)) return by_layout<TileBig>(layout, epi, a, st);
-  return by_layout<TileSmall>(layout, epi, a, st);
+  switch (choose_tile(a.M, a.N)) {
+    case 0: return by_layout<TileBig>(layout, epi, a, st);
+    case 1: return by_layout<TileMid>(layout, epi, a, st);
+    default: return by_layout<TileSmall>(layout, epi, a, st);
+  }
 }
 
 }  // namespace bf
