@@ -193,7 +193,8 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *   y, dx        device outputs, same shape/dtype; either may be NULL
  *   apply_optimizer  0: gradients only; 1: fused Adam per stage when its gradient is final
  *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end);
- *                2: as 1, plus an event pair around every kernel launch -> report->kernel_*
+ *                2: as 1, plus an event pair around every kernel launch -> report->kernel_* (the optimizer
+ *                   then runs on the caller's stream, so that no launch is timed together with it)
  *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
  *                on it (unless timing != 0); the library's side stream joins it before returning
  *                control of the stream to later work.

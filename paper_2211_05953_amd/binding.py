@@ -6,6 +6,8 @@ import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbf.so")
+if os.environ.get("BF_LIBRARY"):   # another build of the same library (A/B timing of kernel variants)
+    LIB_PATH = os.environ["BF_LIBRARY"]
 
 BF_OK, BF_EINVAL, BF_ENOMEM, BF_ESTATE, BF_EDEVICE = 0, -1, -2, -3, -4
 BF_SCHED_BF, BF_SCHED_DF = 0, 1

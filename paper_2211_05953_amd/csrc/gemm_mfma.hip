@@ -167,6 +167,23 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
   Stager<BKC, BN, NT> sb;
   sa.init(lda, tid);
   sb.init(ldb, tid);
+  // Residual / pre-activation values the epilogue needs (E_BIAS_RES, E_GELU_BWD): requested before
+  // the last k-tile, when the staging registers are free, so that their HBM latency hides behind
+  // that tile's MFMAs instead of stalling every workgroup of the round at once.
+  constexpr int PR = 64, NQ = PR * BN / 8 / NT;
+  constexpr bool HAS_R = EPI == E_BIAS_RES || EPI == E_GELU_BWD;
+  bf16x8 rpre[HAS_R ? BM / PR : 1][HAS_R ? NQ : 1];
+  auto prefetch_r = [&]() {
+    if constexpr (HAS_R) {
+#pragma unroll
+      for (int p = 0; p < BM / PR; ++p)
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int c = tid + q * NT, lr = c / (BN / 8), lc = (c % (BN / 8)) * 8;
+          rpre[p][q] = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(R) + (size_t)(m0 + p * PR + lr) * N + n0 + lc);
+        }
+    }
+  };
   const int nk_seg = K / BK, nk = nk_seg * n_seg;
   // k-tile kt lives in segment kt / nk_seg (one segment unless this is a multi-micro-batch weight gradient)
   auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
@@ -263,6 +280,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     int kt = 0;
     for (; kt + 2 < nk; ++kt) iter(kt, std::true_type{}, std::true_type{});
     if (kt + 1 < nk) { iter(kt, std::true_type{}, std::false_type{}); ++kt; }
+    prefetch_r();
     iter(kt, std::false_type{}, std::false_type{});
     __syncthreads();
   }
@@ -283,21 +301,9 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     // bf16 outputs: the fp32 accumulators pass through LDS, 64 tile rows at a time, so that every
     // thread finishes 8 adjacent columns (bias, residual, GeLU in fp32, one rounding) and the
     // global accesses of C, C2 and R are 16 bytes per lane over whole 512-byte row segments.
-    constexpr int PR = 64, LDC = BN + 4, NQ = PR * BN / 8 / NT;
+    constexpr int LDC = BN + 4;
     float* cs = reinterpret_cast<float*>(smem_raw);
     static_assert((size_t)PR * LDC * 4 <= 2 * (size_t)STAGE * sizeof(bf16_t), "epilogue staging does not fit");
-    // the residual / pre-activation values of all passes are requested up front: their latency hides
-    // behind the LDS round trips instead of being paid once per pass
-    bf16x8 rpre[BM / PR][NQ];
-    if constexpr (EPI == E_BIAS_RES || EPI == E_GELU_BWD) {
-#pragma unroll
-      for (int p = 0; p < BM / PR; ++p)
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-          const int c = tid + q * NT, lr = c / (BN / 8), lc = (c % (BN / 8)) * 8;
-          rpre[p][q] = *reinterpret_cast<const bf16x8*>(R + (size_t)(m0 + p * PR + lr) * N + n0 + lc);
-        }
-    }
 #pragma unroll
     for (int p = 0; p < BM / PR; ++p) {
 #pragma unroll

@@ -962,7 +962,10 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         const size_t off = (size_t)l0 * s->D.layer_elems, n = (size_t)per_stage * s->D.layer_elems;
         // breadth-first: the update runs beside the backward of the earlier stages; depth-first
         // gets no such slot (every stage completes in the last micro-batch), so it stays in line
-        hipStream_t as = schedule == BF_SCHED_BF ? s->side : st;
+        // (with per-launch events the update also stays in line: run beside a GEMM it would be timed
+        // as part of that GEMM's launch, and on one GPU the two do not overlap anyway, the GEMM holding
+        // every compute unit)
+        hipStream_t as = schedule == BF_SCHED_BF && timing != 2 ? s->side : st;
         if (as != st) {
           BF_HIP_CHECK(hipEventRecord(s->ev_grad_ready, st));
           BF_HIP_CHECK(hipStreamWaitEvent(as, s->ev_grad_ready, 0));
