@@ -45,6 +45,13 @@ def _sample_check(got, ref_fn, shape, n, rng, tol, scale):
     ("fc2 dgrad", bf.BF_NT, bf.BF_EPI_GELU_BWD, S, FF, H),
     ("qkv dgrad", bf.BF_NT, bf.BF_EPI_NONE, S, H, 3 * H),
     ("fc1 wgrad", bf.BF_TN, bf.BF_EPI_ACCUM, H, FF, S),
+    # the output layer at a 50304-token vocabulary: logits, gradient of the normalised input, weight gradient
+    ("logits", bf.BF_NT, bf.BF_EPI_NONE, S, 50304, H),
+    ("head dgrad", bf.BF_NN, bf.BF_EPI_NONE, S, H, 50304),
+    ("head wgrad", bf.BF_TN, bf.BF_EPI_ACCUM, 50304, H, S),
+    # 1024-token micro-batches (bidirectional workload): the 256 x 128 tile
+    ("fc2 fwd, 1024 rows", bf.BF_NN, bf.BF_EPI_BIAS_RES, 1024, H, FF),
+    ("qkv dgrad, 1024 rows", bf.BF_NT, bf.BF_EPI_NONE, 1024, H, 3 * H),
 ])
 def test_gemm_shapes_of_the_52b_layer_on_sampled_outputs(name, layout, epi, M, N, Kd):
     assert bf.bf_op_gemm_uses_mfma(layout, epi, M, N, Kd)
@@ -180,3 +187,15 @@ def test_full_52b_rank_share_step_invariants():
     assert [e[:3] for e in res["bf"]["trace"]] == K.event_order(K.SCHED_BF, N_loop, N_mb)
     assert [e[:3] for e in res["df"]["trace"]] == K.event_order(K.SCHED_DF, N_loop, N_mb)
     assert res["bf"]["rep"].flops_paper == float(F.c_gpu(N_mb, 1, Lyr, H, S))
+    # fully sharded weights at this size: same bits as the resident copy, 2 N_loop intervals, and with the
+    # double buffer keeping the last two stages over the forward-to-backward turn 2 N_loop - 2 reconstructions
+    st = bf.Stack(bf.make_config(H, A, FF, S, Lyr, N_mb, 1, fuse_wgrad=1, N_loop_min=N_loop, dp_fs=1))
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    rep = st.bf_run_step(bf.BF_SCHED_BF, N_loop, N_mb, 1, x, dy, y, dx)
+    torch.cuda.synchronize()
+    assert torch.equal(y.cpu(), res["bf_fused"]["y"]) and torch.equal(dx.cpu(), res["bf_fused"]["dx"])
+    for (l, n), gref in res["bf_fused"]["grads"].items():
+        assert np.array_equal(st.bf_get_grads(l, bf.TENSOR_IDS[n]), gref), (l, n)
+    assert (rep.n_weight_intervals, rep.n_reconstruct) == (2 * N_loop, 2 * N_loop - 2)
+    assert rep.weight_buffer_bytes < 2 * bf.bf_param_count(st.cfg) // 1 and rep.weight_buffer_bytes >= 4 * bf.bf_param_count(st.cfg) // N_loop
+    st.close()
