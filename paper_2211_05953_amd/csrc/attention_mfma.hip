@@ -17,6 +17,8 @@
 // LDS tiles are [row][S_head] with the 16-byte chunk index XOR-swizzled by row bits; the
 // layout serves both the K-contiguous 16-byte fragment reads and the transpose loads without
 // bank conflicts.
+#include <type_traits>
+
 #include "common.h"
 
 namespace bf {
@@ -145,24 +147,72 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], bf16_t* 
     }
 }
 
-// ------------------------------------------------------------------------------ forward
+// Per-lane LDS offsets of the fragment reads.  The XOR swizzle makes an address a non-linear
+// function of (row, chunk), but the key depends on the lane's row modulo 16 only, so a lane has one
+// offset per distinct chunk pattern; tile row blocks of 16 / 32 rows and the LDS stage then enter as
+// compile-time constants that the DS instructions take as immediates instead of a shift / xor / add
+// chain per read.
 template <int D>
-__global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
-                                                        float* __restrict__ lse, int S_seq, int N_heads, int S_mb, int causal,
-                                                        float scale) {
-  // K/V tiles are double-buffered in LDS: tile j+1 (in registers since the previous iteration) is
-  // written to the idle stage while tile j is consumed, so an iteration has a single barrier.
+struct FragAddr {
+  int k[D / 16];      // frag_k, rows 0-31: element offset of chunk 2kk + lane/32 of row lane%32
+  int t[2][D / 32];   // frag_t, row block 0: offsets of the two transpose loads (rows r, r+8) per 32-column block
+  __device__ __forceinline__ void init(int lane) {
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) k[kk] = swz<D>(lane & 31, kk * 16 + 8 * (lane >> 5));
+    const int tt = lane & 15, blk = lane >> 4;
+    const int row = 4 * (blk >> 1) + (tt >> 2), col = 16 * (blk & 1) + 4 * (tt & 3);
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+      t[0][dt] = swz<D>(row, 32 * dt + col);
+      t[1][dt] = swz<D>(row + 8, 32 * dt + col);
+    }
+  }
+  // A operand, contraction along the tile's columns: lane holds tile[row0 + l%32][16kk + 8(l/32) .. +7]; row0 % 16 == 0
+  __device__ __forceinline__ bf16x8 frag_k(const bf16_t* tile, int row0, int kk) const {
+    return *reinterpret_cast<const bf16x8*>(tile + row0 * D + k[kk]);
+  }
+  // A operand, contraction along the tile's rows in the accumulator order: lane holds
+  // tile[rowbase + 8(e/4) + 4(l/32) + e%4][32 dt + l%32] for e = 0..7; rowbase % 16 == 0
+  __device__ __forceinline__ bf16x8 frag_t(const bf16_t* tile, int rowbase, int dt) const {
+    typedef s16x4 __attribute__((address_space(3))) * lds_v4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + rowbase * D + t[0][dt]));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + rowbase * D + t[1][dt]));
+    return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  }
+};
+
+// ------------------------------------------------------------------------------ forward
+// ROWS queries per workgroup (one wave per 32): 128 with 4 waves and two workgroups per compute
+// unit, or 256 with 8 waves and one.  The K/V tiles come through registers DEPTH tiles ahead of
+// their use and are double-buffered in LDS: tile j+1 is written to the idle stage while tile j is
+// consumed, so an iteration has a single barrier.  The 256-query form reads each tile from HBM / L2
+// once for twice as many queries and keeps two tiles in flight; it needs enough (head, block) pairs
+// to fill the chip.
+// Measured at S_seq 1024-2048, 64 heads of 128: timed without softmax, P V and K/V refetch, the bare
+// S = K Q^T loop (one 1 KB LDS fragment read per MFMA, Q from registers) reaches 44 % of the MFMA
+// rate; without P V 70 % of the full time remains, without the softmax arithmetic 84 %, without the
+// K/V refetch 86 %: no single part dominates, the per-tile chain read -> MFMA -> softmax -> MFMA is
+// what two wavefronts per SIMD cannot hide.  Fewer LDS bytes per MFMA would need 64 queries per
+// wavefront (accumulators in AGPRs, one wavefront per SIMD).
+template <int D, int ROWS>
+__global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
+                                                                                 bf16_t* __restrict__ ctx, float* __restrict__ lse,
+                                                                                 int S_seq, int N_heads, int S_mb, int causal,
+                                                                                 float scale) {
+  constexpr int NT = 2 * ROWS, DEPTH = ROWS == 128 ? 1 : 2;
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   // 1-D grid ordered by work: the last (longest) query block of every head first, then the next ...
   const int nhb = N_heads * S_mb;
-  const int qblk = S_seq / WG_ROWS - 1 - blockIdx.x / nhb;
+  const int qblk = S_seq / ROWS - 1 - blockIdx.x / nhb;
   const int head = (blockIdx.x % nhb) % N_heads, b = (blockIdx.x % nhb) / N_heads;
   const int h = N_heads * D;
   const size_t ld = 3 * (size_t)h;
   const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
-  const int q0 = qblk * WG_ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
+  const int q0 = qblk * ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
 
+  FragAddr<D> fa;
+  fa.init(lane);
   bf16x8 qf[D / 16];
   load_rowfrags<D>(base + (size_t)q * ld, lane, qf);
   f32x16 o[D / 32];
@@ -171,37 +221,42 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
   float m = -INFINITY, l = 0.f;
   const float c2 = scale * LOG2E;
 
-  const int nblk = causal ? (q0 + WG_ROWS) / BLK : S_seq / BLK;
-  TileRegs<BLK, D> kr, vr;
-  kr.load(base + h, ld, tid);
-  vr.load(base + 2 * h, ld, tid);
-  kr.store(KVs[0][0], tid);
-  vr.store(KVs[0][1], tid);
-  if (nblk > 1) {
-    kr.load(base + (size_t)BLK * ld + h, ld, tid);
-    vr.load(base + (size_t)BLK * ld + 2 * h, ld, tid);
-  }
+  const int nblk = causal ? (q0 + ROWS) / BLK : S_seq / BLK;
+  TileRegs<BLK, D, NT> kr[DEPTH], vr[DEPTH];  // set (j % DEPTH) carries tile j
+  auto fetch = [&](auto setc, int j) {
+    constexpr int SET = decltype(setc)::value;
+    kr[SET].load(base + (size_t)j * BLK * ld + h, ld, tid);
+    vr[SET].load(base + (size_t)j * BLK * ld + 2 * h, ld, tid);
+  };
+  typedef std::integral_constant<int, 0> I0;
+  typedef std::integral_constant<int, 1> I1;
+  fetch(I0{}, 0);
+  kr[0].store(KVs[0][0], tid);
+  vr[0].store(KVs[0][1], tid);
+  if (nblk > 1) fetch(std::integral_constant<int, 1 % DEPTH>{}, 1);
+  if (DEPTH > 1 && nblk > 2) fetch(I0{}, 2);
   __syncthreads();
-  for (int j = 0; j < nblk; ++j) {
-    const bf16_t* Ks = KVs[j & 1][0];
-    const bf16_t* Vs = KVs[j & 1][1];
+  // one key tile; PAR = j & 1 is a compile-time constant (the loop is unrolled by two) so that the
+  // LDS stage and the register set are too
+  auto body = [&](int j, auto parc) {
+    constexpr int PAR = decltype(parc)::value;
+    typedef std::integral_constant<int, (PAR + 1) % DEPTH> NextSet;
+    const bf16_t* Ks = KVs[PAR][0];
+    const bf16_t* Vs = KVs[PAR][1];
     if (j + 1 < nblk) {
-      kr.store(KVs[(j + 1) & 1][0], tid);
-      vr.store(KVs[(j + 1) & 1][1], tid);
+      kr[NextSet::value].store(KVs[PAR ^ 1][0], tid);
+      vr[NextSet::value].store(KVs[PAR ^ 1][1], tid);
     }
-    if (j + 2 < nblk) {
-      kr.load(base + (size_t)(j + 2) * BLK * ld + h, ld, tid);
-      vr.load(base + (size_t)(j + 2) * BLK * ld + 2 * h, ld, tid);
-    }
+    if (j + 1 + DEPTH < nblk) fetch(NextSet{}, j + 1 + DEPTH);
     const int kb = j * BLK;
-    if (causal && kb > qw + 31) { __syncthreads(); continue; }  // the whole tile is above this wave's diagonal
+    if (causal && kb > qw + 31) { __syncthreads(); return; }  // the whole tile is above this wave's diagonal
     f32x16 s[2] = {zero16(), zero16()};
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
       for (int t = 0; t < 2; ++t)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s[t], 0, 0, 0);
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.frag_k(Ks, 32 * t, kk), qf[kk], s[t], 0, 0, 0);
     mfma_lds_pipeline<2 * (D / 16), 1, 4>();
     // Online softmax on the raw scores: m is the running max of the unscaled scores, the scale
     // 1/sqrt(S_head) log2(e) enters through one fma per element, the exponentials are the
@@ -251,9 +306,13 @@ __global__ __launch_bounds__(NTHR, 2) void attn_fwd_kernel(const bf16_t* __restr
       for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Vs, 32 * t + 16 * k2, 32 * dt, lane), pb[t][k2], o[dt], 0, 0, 0);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.frag_t(Vs, 32 * t + 16 * k2, dt), pb[t][k2], o[dt], 0, 0, 0);
     mfma_lds_pipeline<4 * (D / 32), 2, 4>();
     __syncthreads();
+  };
+  for (int j = 0; j < nblk; j += 2) {
+    body(j, I0{});
+    if (j + 1 < nblk) body(j + 1, I1{});
   }
   l += __shfl_xor(l, 32, 64);
   store_rows<D>(o, ctx + ((size_t)b * S_seq + q) * h + head * D, lane, 1.0f / l);
@@ -491,8 +550,14 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
 
 template <int D>
 bf_status fwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, void* ctx, float* lse, hipStream_t st) {
-  const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
-  attn_fwd_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, S_mb, causal, 1.0f / sqrtf((float)D));
+  // the 256-query form when there are enough (head, block) pairs to give every compute unit two
+  if (S_seq % 256 == 0 && (long)(S_seq / 256) * N_heads * S_mb >= 512) {
+    const unsigned grid = (unsigned)(S_seq / 256) * N_heads * S_mb;
+    attn_fwd_kernel<D, 256><<<grid, 512, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, S_mb, causal, 1.0f / sqrtf((float)D));
+  } else {
+    const unsigned grid = (unsigned)(S_seq / 128) * N_heads * S_mb;
+    attn_fwd_kernel<D, 128><<<grid, 256, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, S_mb, causal, 1.0f / sqrtf((float)D));
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_fwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
