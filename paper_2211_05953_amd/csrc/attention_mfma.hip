@@ -319,26 +319,14 @@ __global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_fwd_kernel
   if (lane < 32) lse[((size_t)b * N_heads + head) * S_seq + q] = m * scale + logf(l);
 }
 
-// delta[b, head, i] = sum_c dctx[i, c] * ctx[i, c]: one wave per (token, head)
-template <int D>
-__global__ __launch_bounds__(NTHR) void attn_delta_kernel(const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx,
-                                                          float* __restrict__ delta, int S_seq, int N_heads) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int i = blockIdx.x * 4 + w, head = blockIdx.y, b = blockIdx.z;
-  const size_t off = ((size_t)b * S_seq + i) * (N_heads * D) + head * D;
-  float s = 0.f;
-  for (int c = lane; c < D; c += 64) s = fmaf((float)dctx[off + c], (float)ctx[off + c], s);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-  if (lane == 0) delta[((size_t)b * N_heads + head) * S_seq + i] = s;
-}
-
 // ------------------------------------------------------------------- backward, dQ pass
+// Also takes delta[b, head, i] = sum_c dctx[i, c] ctx[i, c] of its queries (each lane already holds
+// half of its query's dctx row) and leaves it in `delta` for the dK/dV pass.
 template <int D>
-__global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb, int causal,
-                                                           float scale) {
+__global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ ctx,
+                                                           const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
+                                                           float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S_seq,
+                                                           int N_heads, int S_mb, int causal, float scale) {
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];  // double-buffered, one barrier per tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nhb = N_heads * S_mb;
@@ -353,7 +341,18 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
   load_rowfrags<D>(base + (size_t)q * ld, lane, qf);
   load_rowfrags<D>(dctx + ((size_t)b * S_seq + q) * h + head * D, lane, dof);
   const size_t st = ((size_t)b * N_heads + head) * S_seq + q;
-  const float lse2 = lse[st] * LOG2E, dl = delta[st], c2 = scale * LOG2E;
+  float dl = 0.f;
+  {
+    bf16x8 cf[D / 16];
+    load_rowfrags<D>(ctx + ((size_t)b * S_seq + q) * h + head * D, lane, cf);
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl = fmaf((float)dof[kk][e], (float)cf[kk][e], dl);
+    dl += __shfl_xor(dl, 32, 64);  // lanes l and l + 32 hold the two halves of the row
+    if (lane < 32) delta[st] = dl;
+  }
+  const float lse2 = lse[st] * LOG2E, c2 = scale * LOG2E;
   f32x16 dq[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
@@ -567,9 +566,8 @@ template <int D>
 bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, const void* ctx, const float* lse,
                 const void* dctx, void* dqkv, float* delta, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
-  attn_delta_kernel<D><<<dim3(S_seq / 4, N_heads, S_mb), NTHR, 0, st>>>((const bf16_t*)ctx, (const bf16_t*)dctx, delta, S_seq, N_heads);
   const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
-  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
   attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
