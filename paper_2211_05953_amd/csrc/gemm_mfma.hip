@@ -162,6 +162,23 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  if constexpr (EPI == E_ACCUM) {
+    // Accumulating into the main-grad: the accumulators START from the stored values, so the reads
+    // of C overlap the first k-tiles and the epilogue is a plain store (read-modify-write at the end
+    // would stall every workgroup of the round on HBM latency at once).
+    if (accumulate) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const size_t row = m0 + wm * TL::TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const size_t col = n0 + wn * TL::TN + j * 32 + (lane & 31);
+            acc[i][j][r] = C[row * (size_t)N + col];
+          }
+    }
+  }
 
   Stager<AK, BM, NT> sa;
   Stager<BKC, BN, NT> sb;
@@ -295,7 +312,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         for (int r = 0; r < 16; ++r) {
           const size_t row = m0 + wm * TL::TM + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
           const size_t col = n0 + wn * TL::TN + j * 32 + (lane & 31);
-          epilogue_store<EPI, TO>(acc[i][j][r], row, col, (size_t)N, C, bias, R, C2, accumulate);
+          C[row * (size_t)N + col] = acc[i][j][r];
         }
   } else {
     // bf16 outputs: the fp32 accumulators pass through LDS, 64 tile rows at a time, so that every
