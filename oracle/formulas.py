@@ -106,3 +106,28 @@ def intensity_fs(kind, N_mb, S_mb, S_seq, N_PP=1):
     if kind == "BF":
         return Fraction(2 * N_mb * S_mb * S_seq, 3)
     raise ValueError(kind)
+
+
+def dp_overlap(kind, N_mb, N_stage, N_PP=1):
+    """Table 4.1, column "DP overlap": the share of the backward pass that is still to run when the
+    first stage's gradient is complete, i.e. the computation a gradient reduction can hide under.
+    Stages of one layer each in the table (N_layers = N_stage)."""
+    rest = 1 - Fraction(N_PP, N_stage)
+    if kind == "BF":
+        return rest
+    if kind == "DF":
+        return rest * Fraction(N_PP, N_mb)
+    if kind in ("GPIPE", "1F1B", "plain"):       # non-looped pipelines / plain gradient accumulation
+        return rest / N_mb
+    raise ValueError(kind)
+
+
+def batch_overhead(B, B_crit):
+    """Sec. 3.5 (Eq. critical_batch): samples needed grow as 1 + B / B_crit; the relative overhead is B / B_crit."""
+    return Fraction(B) / Fraction(B_crit)
+
+
+def cost_time(beta, N_gpu, B_crit):
+    """Eq. time_cost_tradeoff: (cost, time) up to a common factor, at a fixed batch size per GPU beta."""
+    cost = 1 + Fraction(beta) * N_gpu / Fraction(B_crit)
+    return cost, cost / N_gpu

@@ -132,3 +132,52 @@ def test_reconstruction_counts_with_a_double_buffer():
             # a second step with nothing changed starts from what the first left behind
             again, _ = S.reconstructions(bf, resident=held_bf)
             assert again == (0 if N_loop <= 2 else 2 * N_loop - 4)
+
+
+def _overlap_share(ops):
+    """Backward ops still to run when the first stage of the rank has finished all its backwards."""
+    n_mb = 1 + max(m for _, _, m in ops)
+    done = {}
+    total_b = sum(1 for op, _, _ in ops if op == S.OP_B)
+    seen_b = 0
+    for op, st, m in ops:
+        if op != S.OP_B:
+            continue
+        seen_b += 1
+        done[st] = done.get(st, 0) + 1
+        if done[st] == n_mb:
+            return Fraction(total_b - seen_b, total_b)
+    raise AssertionError
+
+
+def test_gradient_reduction_overlap_matches_the_method_table():
+    """Table 4.1, "DP overlap": breadth-first can hide a stage's reduction under 1 - N_PP / N_stage of the
+    backward pass, depth-first only under the last sequence's share, plain accumulation under one
+    micro-batch's.  Read off the op orders the simulator and the stack execute."""
+    for N_PP in (1, 2, 4):
+        for N_loop in (1, 2, 4, 8):
+            for mult in (1, 2, 4):
+                N_mb = N_PP * mult
+                N_stage = N_PP * N_loop
+                for rank in range(N_PP):
+                    assert _overlap_share(S.device_order("BF", N_PP, N_loop, N_mb, rank)) == F.dp_overlap("BF", N_mb, N_stage, N_PP)
+                    if N_PP == 1 or rank == 0:
+                        assert _overlap_share(S.device_order("DF", N_PP, N_loop, N_mb, rank)) == F.dp_overlap("DF", N_mb, N_stage, N_PP), (N_PP, N_loop, N_mb, rank)
+    # at N_PP = 1 depth-first is plain gradient accumulation (App. C) and the stack's own event order agrees
+    for N_loop, N_mb in [(2, 4), (4, 16), (8, 3)]:
+        for kind, code in (("BF", K.SCHED_BF), ("DF", K.SCHED_DF)):
+            full = K.event_order(code, N_loop, N_mb)
+            first_opt = next(i for i, e in enumerate(full) if e[0] == K.OP_OPT)
+            rest = sum(1 for e in full[first_opt:] if e[0] == K.OP_B)
+            assert Fraction(rest, N_loop * N_mb) == F.dp_overlap(kind, N_mb, N_loop, 1)
+        assert F.dp_overlap("DF", N_mb, N_loop, 1) == F.dp_overlap("plain", N_mb, N_loop, 1)
+
+
+def test_batch_size_overhead_worked_example():
+    """Sec. 3.5: a 3 M-token batch against a 10 M-token critical batch size costs about 30 % more samples;
+    Eq. time_cost_tradeoff: at fixed batch per GPU more GPUs cost more but finish sooner."""
+    assert F.batch_overhead(3_000_000, 10_000_000) == Fraction(3, 10)
+    c1, t1 = F.cost_time(1, 1000, 10_000)
+    c2, t2 = F.cost_time(1, 4000, 10_000)
+    assert c2 > c1 and t2 < t1
+    assert c1 == Fraction(11, 10) and t2 == Fraction(14, 10) / 4000
