@@ -181,6 +181,22 @@ struct FragAddr {
   }
 };
 
+// The same interface computing every address on the fly: for kernels that have no 16 registers to spare.
+template <int D>
+struct FragAddrLive {
+  int lane_;
+  __device__ __forceinline__ void init(int lane) { lane_ = lane; }
+  __device__ __forceinline__ bf16x8 frag_k(const bf16_t* tile, int row0, int kk) const { return bf::frag_k<D>(tile, row0, kk, lane_); }
+  __device__ __forceinline__ bf16x8 frag_t(const bf16_t* tile, int rowbase, int dt) const { return bf::frag_t<D>(tile, rowbase, 32 * dt, lane_); }
+};
+
+// Register set that carries tile j+1, from the parity of j: a compile-time constant when the loop
+// is unrolled by two (the parity is an integral_constant), always set 0 with one tile in flight.
+template <int DEPTH, typename P>
+struct NextSetOf { static constexpr int value = 0; };
+template <int DEPTH, int V>
+struct NextSetOf<DEPTH, std::integral_constant<int, V>> { static constexpr int value = (V + 1) % DEPTH; };
+
 // ------------------------------------------------------------------------------ forward
 // ROWS queries per workgroup (one wave per 32): 128 with 4 waves and two workgroups per compute
 // unit, or 256 with 8 waves and one.  The K/V tiles come through registers DEPTH tiles ahead of
@@ -322,21 +338,26 @@ __global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_fwd_kernel
 // ------------------------------------------------------------------- backward, dQ pass
 // Also takes delta[b, head, i] = sum_c dctx[i, c] ctx[i, c] of its queries (each lane already holds
 // half of its query's dctx row) and leaves it in `delta` for the dK/dV pass.
-template <int D>
-__global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ ctx,
-                                                           const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
-                                                           float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S_seq,
-                                                           int N_heads, int S_mb, int causal, float scale) {
+// ROWS queries per workgroup and K/V tiles DEPTH tiles ahead, as in the forward kernel.
+template <int D, int ROWS>
+__global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx,
+    const float* __restrict__ lse, float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb,
+    int causal, float scale) {
+  constexpr int NT = 2 * ROWS, DEPTH = ROWS == 128 ? 1 : 2;
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];  // double-buffered, one barrier per tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nhb = N_heads * S_mb;
-  const int qblk = S_seq / WG_ROWS - 1 - blockIdx.x / nhb;  // longest query blocks of every head first
+  const int qblk = S_seq / ROWS - 1 - blockIdx.x / nhb;  // longest query blocks of every head first
   const int head = (blockIdx.x % nhb) % N_heads, b = (blockIdx.x % nhb) / N_heads;
   const int h = N_heads * D;
   const size_t ld = 3 * (size_t)h;
   const bf16_t* base = qkv + (size_t)b * S_seq * ld + head * D;
-  const int q0 = qblk * WG_ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
+  const int q0 = qblk * ROWS, qw = q0 + 32 * w, q = qw + (lane & 31);
 
+  // precomputed offsets where the registers allow (the 128-query form at S_head 128 would spill)
+  typename std::conditional<(ROWS == 256 || D == 64), FragAddr<D>, FragAddrLive<D>>::type fa;
+  fa.init(lane);
   bf16x8 qf[D / 16], dof[D / 16];
   load_rowfrags<D>(base + (size_t)q * ld, lane, qf);
   load_rowfrags<D>(dctx + ((size_t)b * S_seq + q) * h + head * D, lane, dof);
@@ -357,30 +378,34 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
 
-  const int nblk = causal ? (q0 + WG_ROWS) / BLK : S_seq / BLK;
-  TileRegs<BLK, D> kr, vr;
-  kr.load(base + h, ld, tid);
-  vr.load(base + 2 * h, ld, tid);
-  kr.store(KVs[0][0], tid);
-  vr.store(KVs[0][1], tid);
-  if (nblk > 1) {
-    kr.load(base + (size_t)BLK * ld + h, ld, tid);
-    vr.load(base + (size_t)BLK * ld + 2 * h, ld, tid);
-  }
+  const int nblk = causal ? (q0 + ROWS) / BLK : S_seq / BLK;
+  TileRegs<BLK, D, NT> kr[DEPTH], vr[DEPTH];  // set (j % DEPTH) carries tile j
+  auto fetch = [&](auto setc, int j) {
+    constexpr int SET = decltype(setc)::value;
+    kr[SET].load(base + (size_t)j * BLK * ld + h, ld, tid);
+    vr[SET].load(base + (size_t)j * BLK * ld + 2 * h, ld, tid);
+  };
+  typedef std::integral_constant<int, 0> I0;
+  typedef std::integral_constant<int, 1> I1;
+  fetch(I0{}, 0);
+  kr[0].store(KVs[0][0], tid);
+  vr[0].store(KVs[0][1], tid);
+  if (nblk > 1) fetch(std::integral_constant<int, 1 % DEPTH>{}, 1);
+  if (DEPTH > 1 && nblk > 2) fetch(I0{}, 2);
   __syncthreads();
-  for (int j = 0; j < nblk; ++j) {
-    const bf16_t* Ks = KVs[j & 1][0];
-    const bf16_t* Vs = KVs[j & 1][1];
+  // one key tile; par = j & 1 selects the LDS stage
+  auto body = [&](int j, auto par) {
+    typedef std::integral_constant<int, NextSetOf<DEPTH, decltype(par)>::value> NextSet;
+    const int p = par;
+    const bf16_t* Ks = KVs[p][0];
+    const bf16_t* Vs = KVs[p][1];
     if (j + 1 < nblk) {
-      kr.store(KVs[(j + 1) & 1][0], tid);
-      vr.store(KVs[(j + 1) & 1][1], tid);
+      kr[NextSet::value].store(KVs[p ^ 1][0], tid);
+      vr[NextSet::value].store(KVs[p ^ 1][1], tid);
     }
-    if (j + 2 < nblk) {
-      kr.load(base + (size_t)(j + 2) * BLK * ld + h, ld, tid);
-      vr.load(base + (size_t)(j + 2) * BLK * ld + 2 * h, ld, tid);
-    }
+    if (j + 1 + DEPTH < nblk) fetch(NextSet{}, j + 1 + DEPTH);
     const int kb = j * BLK;
-    if (causal && kb > qw + 31) { __syncthreads(); continue; }
+    if (causal && kb > qw + 31) { __syncthreads(); return; }
     const bool diag = causal && kb + BLK - 1 > qw;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -388,8 +413,8 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Ks, 32 * t, kk, lane), qf[kk], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k<D>(Vs, 32 * t, kk, lane), dof[kk], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.frag_k(Ks, 32 * t, kk), qf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.frag_k(Vs, 32 * t, kk), dof[kk], dp, 0, 0, 0);
       }
       mfma_lds_pipeline<2 * (D / 16), 1, 4>();
       // p = exp(s/sqrt(d) - lse); dS = p (dP - delta) (the factor 1/sqrt(d) is applied once, to dQ)
@@ -406,10 +431,20 @@ __global__ __launch_bounds__(NTHR, 2) void attn_bwd_dq_kernel(const bf16_t* __re
       for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
-          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_t<D>(Ks, 32 * t + 16 * k2, 32 * dt, lane), dsb[k2], dq[dt], 0, 0, 0);
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.frag_t(Ks, 32 * t + 16 * k2, dt), dsb[k2], dq[dt], 0, 0, 0);
       mfma_lds_pipeline<2 * (D / 32), 2, 4>();
     }
     __syncthreads();
+  };
+  if constexpr (ROWS == 256 || D == 64) {
+    // unrolled by two: the LDS stage (and with it every fragment address) is a compile-time constant
+    for (int j = 0; j < nblk; j += 2) {
+      body(j, I0{});
+      if (j + 1 < nblk) body(j + 1, I1{});
+    }
+  } else {
+    static_assert(DEPTH == 1, "a run-time stage goes with one tile in flight");
+    for (int j = 0; j < nblk; ++j) body(j, j & 1);
   }
   store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, scale);
 }
@@ -567,7 +602,10 @@ bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, c
                 const void* dctx, void* dqkv, float* delta, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
-  attn_bwd_dq_kernel<D><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+  if (S_seq % 256 == 0)  // measured faster than the 128-query form also on grids that do not fill the chip
+    attn_bwd_dq_kernel<D, 256><<<grid / 2, 512, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+  else
+    attn_bwd_dq_kernel<D, 128><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
   attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
