@@ -584,8 +584,8 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
 
 template <int D>
 bf_status fwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, void* ctx, float* lse, hipStream_t st) {
-  // the 256-query form when there are enough (head, block) pairs to give every compute unit two
-  if (S_seq % 256 == 0 && (long)(S_seq / 256) * N_heads * S_mb >= 512) {
+  // the 256-query form when there are enough (head, block) pairs to give every compute unit one
+  if (S_seq % 256 == 0 && (long)(S_seq / 256) * N_heads * S_mb >= 256) {
     const unsigned grid = (unsigned)(S_seq / 256) * N_heads * S_mb;
     attn_fwd_kernel<D, 256><<<grid, 512, 0, st>>>((const bf16_t*)qkv, (bf16_t*)ctx, lse, S_seq, N_heads, S_mb, causal, 1.0f / sqrtf((float)D));
   } else {
