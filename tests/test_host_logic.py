@@ -42,6 +42,19 @@ def test_config_validation_without_a_device():
     none = bf.make_config(512, 4, 2048, 256, 4, 8, 1, ckpt_mode=bf.BF_CKPT_NONE)
     ck = bf.make_config(512, 4, 2048, 256, 4, 8, 1, ckpt_mode=bf.BF_CKPT_LAYER)
     assert bf.bf_workspace_bytes(ck) < bf.bf_workspace_bytes(none)
+    # fully sharded weights: bf16 only; two stage-sized halves instead of every layer's bf16 copy
+    assert bf.bf_workspace_bytes(bf.make_config(256, 4, 1024, 128, 4, 4, 1, dtype=bf.BF_FP32, dp_fs=1)) == 0
+    assert "dp_fs" in bf.binding.last_error()
+    res = bf.make_config(512, 4, 2048, 256, 8, 8, 1, N_loop_min=8)
+    fs = bf.make_config(512, 4, 2048, 256, 8, 8, 1, N_loop_min=8, dp_fs=1)
+    P = bf.bf_param_count(res)
+    assert 0 < bf.bf_workspace_bytes(res) - bf.bf_workspace_bytes(fs) <= 2 * P
+    assert bf.bf_workspace_bytes(res) - bf.bf_workspace_bytes(fs) >= 2 * P - 2 * 2 * (P // 8) - 4096
+    # input / output layers: two [S_voc, S_hidden] matrices, the position table and the final LayerNorm
+    voc = bf.make_config(256, 4, 1024, 128, 4, 4, 1, dtype=bf.BF_FP32, S_voc=1000)
+    assert bf.bf_param_count(voc) - bf.bf_param_count(good) == 2 * 1000 * 256 + 128 * 256 + 2 * 256
+    assert bf.bf_workspace_bytes(voc) > bf.bf_workspace_bytes(good)
+    assert bf.bf_workspace_bytes(bf.make_config(256, 4, 1024, 128, 4, 4, 1, S_voc=-1)) == 0
 
 
 @pytest.mark.parametrize("kind,code", [("BF", bf.BF_SCHED_BF), ("DF", bf.BF_SCHED_DF)])
