@@ -31,13 +31,12 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int BK = 64;
 // measured throughput of a compute unit on the smaller tiles relative to the 256 x 256 tile
-constexpr double TILE_RATE_MID = 0.88, TILE_RATE_SMALL = 0.75;
+constexpr double TILE_RATE_MID = 0.84, TILE_RATE_SMALL = 0.68;
 constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
 
 template <int BM_, int BN_, int WM_, int WN_>
@@ -461,7 +460,10 @@ inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
 
 // Tile choice: the grid runs in rounds over the chip's workgroup slots, so the estimated time of a
 // tile shape is rounds x tile area / (throughput of a slot relative to a compute unit running the
-// 256 x 256 tile).  Larger tiles reuse more per LDS byte; smaller ones fill the last round.
+// 256 x 256 tile).  Larger tiles reuse more per LDS byte; smaller ones fill the last round.  A
+// partly filled last round counts as (1 + fill) / 2 of a round: the chip runs at its power limit,
+// and the compute units that do work clock higher when the others idle (measured: 384 large tiles
+// beat 768 of 256 x 128, 128 large tiles lose to 256 of them).
 // 0: 256 x 256 (one per compute unit), 1: 256 x 128 (one), 2: 128 x 128 (two).
 inline int choose_tile(int M, int N) {
   static const int forced = [] {
@@ -476,8 +478,9 @@ inline int choose_tile(int M, int N) {
   for (int i = 0; i < 3; ++i) {
     if (M % bm[i] || N % bn[i]) continue;
     if (i == forced) return i;
-    const long tiles = (long)(M / bm[i]) * (N / bn[i]), rounds = (tiles + slots[i] - 1) / slots[i];
-    const double t = (double)rounds * bm[i] * bn[i] / rate[i];
+    const long tiles = (long)(M / bm[i]) * (N / bn[i]), full = tiles / slots[i], rest = tiles % slots[i];
+    const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / slots[i] : 0.0);
+    const double t = rounds * bm[i] * bn[i] / rate[i];
     if (best < 0 || t < best_t) { best = i; best_t = t; }
   }
   return best;
