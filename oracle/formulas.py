@@ -92,6 +92,22 @@ def intensity_tp(S_hidden, N_TP):
     return Fraction(2 * S_hidden, N_TP)
 
 
+def tp_overhead(S_hidden, N_TP, I_hw):
+    """App. A.3.3: two thirds of the tensor-parallel traffic cannot be overlapped, so the expected
+    overhead is (2/3) T_net / T_comp = (2/3) I_hw / I_TP (App. A.3: T_comp / T_net ~ I_op / I_hw)."""
+    return Fraction(2, 3) * Fraction(I_hw) / intensity_tp(S_hidden, N_TP)
+
+
+def dp_efficient(kind, N_mb, S_mb, S_seq, I_hw, N_PP=1, sharded=False):
+    """App. A.3.1, the overlapped branch of the efficiency requirements: the reduction (and, fully
+    sharded, the reconstruction) hides behind the computation it can overlap with when that
+    computation's intensity reaches the hardware intensity.  Non-looped / plain accumulation overlaps
+    with one micro-batch, depth-first with N_PP of them, breadth-first with the whole batch."""
+    n = {"plain": 1, "DF": N_PP, "BF": N_mb}[kind]
+    i_op = Fraction(2 * n * S_mb * S_seq, 3) if sharded else n * S_mb * S_seq
+    return i_op >= I_hw
+
+
 def intensity_dp(N_mb, S_mb, S_seq):
     """App. A.3.1: I_DP0 ~ I_DP_PS = N_mb S_mb S_seq."""
     return N_mb * S_mb * S_seq

@@ -85,3 +85,27 @@ def test_fs_intensities():
     assert F.intensity_fs("plain", 8, 1, 2048) == Fraction(2 * 2048, 3)
     assert F.intensity_fs("DF", 8, 1, 2048, N_PP=4) == 4 * F.intensity_fs("plain", 8, 1, 2048)
     assert F.intensity_fs("BF", 8, 1, 2048) == 8 * F.intensity_fs("plain", 8, 1, 2048)
+
+
+def test_tensor_parallel_overhead_worked_examples():
+    g, t = G["models"]["gpt3"], G["models"]["1t"]
+    nv = G["hw_intensity"]["nvlink"]
+    assert round(float(F.tp_overhead(g["S_hidden"], 8, nv)) * 100) == G["tp_overhead_percent"]["gpt3"]
+    assert round(float(F.tp_overhead(t["S_hidden"], 8, nv)) * 100) == G["tp_overhead_percent"]["1t"]
+
+
+def test_data_parallel_efficiency_requirements():
+    """App. A.3.1 on the worked hardware (I_IB = 6240, S_seq = 2048): beta_net = 4 sequences must be
+    overlapped.  Plain accumulation needs them in one micro-batch, depth-first reaches them with
+    N_PP = 4 micro-batches of one, breadth-first with any 4 micro-batches; fully sharded the bar
+    rises by 3/2 and the micro-batch count stops helping everything but breadth-first."""
+    ib = G["hw_intensity"]["ib"]
+    assert not F.dp_efficient("plain", 8, 1, 2048, ib) and F.dp_efficient("plain", 1, 4, 2048, ib)
+    assert F.dp_efficient("DF", 8, 1, 2048, ib, N_PP=4) and not F.dp_efficient("DF", 8, 1, 2048, ib, N_PP=2)
+    assert F.dp_efficient("BF", 4, 1, 2048, ib) and not F.dp_efficient("BF", 3, 1, 2048, ib)
+    assert not F.dp_efficient("BF", 4, 1, 2048, ib, sharded=True) and F.dp_efficient("BF", 5, 1, 2048, ib, sharded=True)
+    assert not F.dp_efficient("plain", 64, 4, 2048, ib, sharded=True) and F.dp_efficient("plain", 1, 5, 2048, ib, sharded=True)
+    # the threshold is where the intensity of App. A.3.1 crosses I_hw
+    for n in range(1, 9):
+        assert F.dp_efficient("BF", n, 1, 2048, ib) == (F.intensity_dp(n, 1, 2048) >= ib)
+        assert F.dp_efficient("BF", n, 1, 2048, ib, sharded=True) == (F.intensity_fs("BF", n, 1, 2048) >= ib)
