@@ -91,6 +91,32 @@ def cpu_baseline(w, causal=True):
                       "fp64 numpy" % (Lyr * N_mb, dt)}
 
 
+def power_check(bf, h):
+    """One weight-gradient-shaped product (h x h over 2 h tokens) timed on normally distributed and on
+    all-zero operands.  The kernel, the shape and the launch are the same, only the switching activity
+    differs: the gap between the two rates is what the socket power limit takes."""
+    import torch
+    M, N, Kd = h, h, 2 * h
+    out = {"product": "weight-gradient layout, %d x %d x %d, bf16 operands, fp32 result" % (M, N, Kd)}
+    C = torch.empty(M, N, device="cuda:0", dtype=torch.float32)
+    for name in ("randn", "zeros"):
+        mk = (lambda *sh: torch.randn(*sh, device="cuda:0").bfloat16()) if name == "randn" else \
+             (lambda *sh: torch.zeros(*sh, device="cuda:0", dtype=torch.bfloat16))
+        A, B = mk(Kd, M), mk(Kd, N)
+        run = lambda: bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_TN, bf.BF_EPI_ACCUM, M, N, Kd, A, B, C, None, None, None, 0)
+        for _ in range(3):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_tflops"] = 2.0 * M * N * Kd * 20 / (e0.elapsed_time(e1) * 1e9)
+        del A, B
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +129,8 @@ def main():
                     help="accumulate weight gradients per micro-batch in BF order too (default: one product per stage)")
     ap.add_argument("--no-dp-fs", action="store_true",
                     help="skip the fully-sharded (dp_fs = 1) BF and DF steps reported under \"dp_fs\"")
+    ap.add_argument("--no-power-check", action="store_true",
+                    help="skip the product timed on random and on zero operands reported under \"power_check\"")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run a 1 GiB device copy (known HBM traffic) so that FETCH_SIZE / WRITE_SIZE "
                          "readings of a rocprofv3 --pmc run of this command can be scaled")
@@ -226,6 +254,8 @@ def main():
         del fs
     del x, dy, y, dx
     torch.cuda.empty_cache()
+    if b16 and not args.no_power_check and h % 256 == 0:
+        line["power_check"] = power_check(bf, h)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, causal=bool(EXTRA.get(args.workload, {}).get("causal", 1)))
     print(json.dumps(line))
