@@ -363,3 +363,84 @@ def test_rank_step_argument_errors():
         st.bf_run_rank_step(bf.BF_SCHED_BF, 4, 0, 2, 2, 1, x, x)      # breadth-first needs N_mb >= N_PP
     st.bf_run_rank_step(bf.BF_SCHED_BF, 2, 1, 2, 4, 1, x, x)
     st.close()
+
+
+def _random_cases(n, seed):
+    """Seeded draw of step configurations: ragged fp32 shapes on the generic kernels, tile-aligned
+    bf16 shapes on the MFMA kernels, every flag of the configuration that changes the path."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        b16 = bool(i % 2)
+        if b16:
+            d = int(rng.choice([64, 128]))
+            a = int(rng.choice([1, 2, 4]))
+            h = a * d
+            if h % 128:
+                a, h = 2, 2 * d
+            f = int(rng.choice([2, 4])) * h
+            S_seq = int(rng.choice([128, 256, 384]))
+            S_mb = int(rng.choice([1, 2]))
+        else:
+            a = int(rng.choice([1, 2, 3]))
+            h = a * int(rng.choice([8, 20, 24]))
+            f = int(rng.integers(h, 4 * h))
+            S_seq = int(rng.integers(5, 70))
+            S_mb = int(rng.choice([1, 2, 3]))
+        N_loop = int(rng.choice([1, 2, 3, 4]))
+        Lyr = N_loop * int(rng.choice([1, 2]))
+        N_mb = int(rng.integers(1, 6))
+        cases.append(dict(b16=b16, h=h, a=a, f=f, S_seq=S_seq, S_mb=S_mb, Lyr=Lyr, N_loop=N_loop, N_mb=N_mb,
+                          ckpt=int(rng.choice([bf.BF_CKPT_NONE, bf.BF_CKPT_LAYER])), fuse=int(rng.integers(0, 2)),
+                          fs=int(rng.integers(0, 2)) if b16 else 0, causal=int(rng.integers(0, 2)),
+                          hint=int(rng.integers(0, 2)), seed=100 + i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_cases(14, 20221105), ids=lambda c: "h%d_a%d_f%d_S%d_b%d_L%d_l%d_m%d_%s" % (
+    c["h"], c["a"], c["f"], c["S_seq"], c["S_mb"], c["Lyr"], c["N_loop"], c["N_mb"], "bf16" if c["b16"] else "fp32"))
+def test_randomly_drawn_configurations(c):
+    """Both orders on configurations nobody picked by hand: outputs, input gradients and every
+    main-grad against the oracle; the two orders bit-identical in y and dx."""
+    mode, dtype = ("bf16", bf.BF_BF16) if c["b16"] else ("fp32", bf.BF_FP32)
+    params = bf_inputs.make_params(c["seed"], c["Lyr"], c["h"], c["f"], bf16=c["b16"])
+    x, dy = bf_inputs.make_batch(c["seed"], c["N_mb"], c["S_mb"], c["S_seq"], c["h"], bf16=c["b16"])
+    cfg = bf.make_config(c["h"], c["a"], c["f"], c["S_seq"], c["Lyr"], c["N_mb"], c["S_mb"], dtype=dtype, ckpt_mode=c["ckpt"],
+                         fuse_wgrad=c["fuse"], dp_fs=c["fs"], causal=c["causal"], N_loop_min=c["N_loop"] if c["hint"] else 0)
+    ref = _oracle(params, x, dy, K.SCHED_BF, c["N_loop"], c["a"], causal=bool(c["causal"]))
+    g_bf = _run_gpu(cfg, params, x, dy, bf.BF_SCHED_BF, c["N_loop"], c["N_mb"], c["S_mb"])
+    g_df = _run_gpu(cfg, params, x, dy, bf.BF_SCHED_DF, c["N_loop"], c["N_mb"], c["S_mb"])
+    _compare(g_bf, ref, TOL[mode], c["Lyr"])
+    _compare(g_df, ref, TOL[mode], c["Lyr"])
+    assert np.array_equal(g_bf["y"], g_df["y"]) and np.array_equal(g_bf["dx"], g_df["dx"])
+    assert g_bf["report"].peak_ckpt_count == F.ckpt_count("BF", c["N_mb"], c["Lyr"], 1)
+    assert g_df["report"].peak_ckpt_count == F.ckpt_count("DF", c["N_mb"], c["Lyr"], 1)
+
+
+def _random_rank_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        b16 = bool(i % 2)
+        N_PP = int(rng.choice([1, 2, 3, 4]))
+        rank = int(rng.integers(0, N_PP))
+        N_loop = int(rng.choice([1, 2, 3]))
+        Lyr = N_loop * int(rng.choice([1, 2]))
+        N_mb = N_PP * int(rng.integers(1, 4))       # depth-first runs sequences of N_PP
+        if b16:
+            h, a, f, S_seq, S_mb = 256, int(rng.choice([2, 4])), 1024, int(rng.choice([128, 256])), 1
+        else:
+            a = int(rng.choice([1, 2, 3]))
+            h, S_seq, S_mb = a * int(rng.choice([8, 24])), int(rng.integers(5, 50)), int(rng.choice([1, 2]))
+            f = int(rng.integers(h, 3 * h))
+        cases.append((("bf16", bf.BF_BF16) if b16 else ("fp32", bf.BF_FP32)) + (
+            N_PP, rank, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, int(rng.integers(0, 2)),
+            int(rng.choice([bf.BF_CKPT_NONE, bf.BF_CKPT_LAYER])), int(rng.integers(0, 2)) if b16 else 0))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_rank_cases(10, 5953), ids=lambda c: "%s_pp%d_r%d_L%d_l%d_h%d_S%d_m%d" % (
+    c[0], c[2], c[3], c[4], c[5], c[6], c[9], c[11]))
+def test_randomly_drawn_pipeline_ranks(c):
+    """The checks of the rank-step test on drawn pipeline depths, ranks, loop counts and flags."""
+    test_rank_of_a_deeper_pipeline_matches_oracle(*c)
