@@ -199,6 +199,10 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *                on it (unless timing != 0); the library's side stream joins it before returning
  *                control of the stream to later work.
  *   report       may be NULL
+ * With timing = 0 and cfg.queue_depth = 0 the call enqueues kernel launches and event record / wait
+ * only (no allocation, no memset or copy, no host synchronisation) and may be recorded into a HIP
+ * graph by stream capture; the optimizer's step count is kept on the device and advanced by the step
+ * itself, so replays are successive steps.  The host-side trace and report describe the recorded call.
  * Main-grads stay readable until the next step starts.  x, dy, y, dx must not alias the workspace.
  * BF_EINVAL: N_layers % N_loop != 0, sizes out of range, null x / dy, unknown schedule. */
 bf_status bf_run_step(bf_stack* s, int schedule, int N_loop, int N_mb, int S_mb,

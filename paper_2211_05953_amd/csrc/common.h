@@ -99,8 +99,10 @@ bf_status ce_loss(int dtype, int n_rows, int S_voc, void* z, const int32_t* labe
                   float* loss_out, hipStream_t st);
 
 // Fused Adam over n contiguous parameters; w_lp (bf16 copy) may be null.
-bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t,
-                    float lr, float beta1, float beta2, float eps, float wd, hipStream_t st);
+// t_dev: device step counter read by the kernel (then t is ignored), or null for the host value t
+bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t, const int* t_dev, float lr,
+                    float beta1, float beta2, float eps, float wd, hipStream_t st);
+bf_status bump_step(int* t_dev, hipStream_t st);
 bf_status cast_f32_to_bf16(size_t n, const float* src, bf16_t* dst, hipStream_t st);
 bf_status fill_f32(size_t n, float* dst, float value, hipStream_t st);
 // N(0, std) from a counter-based hash of (seed, index)

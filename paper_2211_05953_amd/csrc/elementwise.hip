@@ -338,11 +338,20 @@ void launch_col_reduce(const void* dY, const void* x, const float* stats, float*
 
 // ------------------------------------------------------------------------- fused Adam
 // One pass: m, v, w updated in fp32; bf16 copy of w rewritten (mixed precision, App. A.1).
+// The bias corrections c1 = 1 / (1 - beta1^t), c2 = 1 / (1 - beta2^t) come from the host, or, when
+// t_dev is given, are taken in double from the step count stored on the device: a launch recorded
+// in a HIP graph then follows the counter from replay to replay.
 template <int VEC>
 __global__ __launch_bounds__(256) void adam_kernel(size_t n, float* __restrict__ w, float* __restrict__ m,
                                                    float* __restrict__ v, const float* __restrict__ g,
                                                    bf16_t* __restrict__ w_lp, float lr, float beta1, float beta2,
-                                                   float eps, float wd, float c1, float c2, float omb1, float omb2) {
+                                                   float eps, float wd, float c1, float c2, float omb1, float omb2,
+                                                   const int* __restrict__ t_dev) {
+  if (t_dev) {
+    const double t = (double)*t_dev;
+    c1 = (float)(1.0 / (1.0 - pow((double)beta1, t)));
+    c2 = (float)(1.0 / (1.0 - pow((double)beta2, t)));
+  }
   const size_t stride = (size_t)gridDim.x * blockDim.x * VEC;
   for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < n; i += stride) {
     float ww[VEC], mm[VEC], vv[VEC], gg[VEC];
@@ -478,18 +487,27 @@ bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumu
   return BF_OK;
 }
 
-bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t, float lr, float beta1,
-                    float beta2, float eps, float wd, hipStream_t st) {
+__global__ void bump_step_kernel(int* t) { *t += 1; }
+
+bf_status bump_step(int* t_dev, hipStream_t st) {
+  bump_step_kernel<<<1, 1, 0, st>>>(t_dev);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
+bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16_t* w_lp, int t, const int* t_dev, float lr,
+                    float beta1, float beta2, float eps, float wd, hipStream_t st) {
   if (n == 0) return BF_OK;
-  if (!w || !m || !v || !g || t < 1) { set_error("adam_step: bad argument"); return BF_EINVAL; }
-  // bias corrections in double on the host, applied as multipliers
-  const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
-  const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+  if (!w || !m || !v || !g || (!t_dev && t < 1)) { set_error("adam_step: bad argument"); return BF_EINVAL; }
+  // bias corrections in double, applied as multipliers: here for a step count given by value, in the
+  // kernel for one kept on the device
+  const float c1 = t_dev ? 0.f : (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
+  const float c2 = t_dev ? 0.f : (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
   const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
   const bool vec = n % 4 == 0 && aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
                    (!w_lp || ((uintptr_t)w_lp & 7) == 0);
-  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2);
-  else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2);
+  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2, t_dev);
+  else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2, t_dev);
   BF_LAUNCH_CHECK();
   return BF_OK;
 }

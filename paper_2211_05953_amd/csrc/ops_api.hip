@@ -78,7 +78,7 @@ bf_status bf_op_ce_loss(int dtype, int n_rows, int S_voc, void* z, const int32_t
 
 bf_status bf_op_adam(size_t n, float* w, float* m, float* v, const float* g, void* w_lp, int t, float lr, float beta1,
                      float beta2, float adam_eps, float weight_decay, void* stream) {
-  return adam_step(n, w, m, v, g, (bf16_t*)w_lp, t, lr, beta1, beta2, adam_eps, weight_decay, (hipStream_t)stream);
+  return adam_step(n, w, m, v, g, (bf16_t*)w_lp, t, nullptr, lr, beta1, beta2, adam_eps, weight_decay, (hipStream_t)stream);
 }
 
 }  // extern "C"

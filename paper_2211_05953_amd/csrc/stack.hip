@@ -121,6 +121,7 @@ struct WsLayout {
   size_t grec_bytes;
   size_t off_wrec;         // with checkpointing: as many records {a, ctx, c, g}, the recomputed wgrad operands
   size_t wrec_bytes;
+  size_t off_step;         // optimizer step count (one int)
   size_t off_bhand;        // 2 x N_mb_max [T, h] (two sets, alternating by stage)
   size_t off_scratch_out;  // [T, h] x 2: discarded outputs / ping-pong
   size_t total;
@@ -214,6 +215,7 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
   Lo->off_lm = off;
   Lo->logits_bytes = up(T * (size_t)(c.S_voc > 0 ? c.S_voc : 0) * es);
   if (c.S_voc > 0) off += (2 * (size_t)c.N_mb_max + 3) * Lo->y_bytes + up(T * 8) + Lo->logits_bytes + up(T * 4);
+  Lo->off_step = off; off += ALIGN;
   Lo->total = off;
 }
 
@@ -246,7 +248,9 @@ struct bf_stack {
   std::vector<hipEvent_t> prof_ev;
   struct ProfRec { int cls; double flops, bytes; };
   std::vector<ProfRec> prof_rec;
-  int step;               // optimizer step counter
+  int step;               // optimizer step counter (host mirror; the kernels read d_step)
+  int* d_step;            // the same count on the device, bumped by a one-thread kernel at the start of an
+                          // optimizer step: a step recorded in a HIP graph keeps counting when replayed
   bool have_grads;
   int device;
 };
@@ -569,6 +573,7 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->fs_cur = 0;
   s->fs_cur_l0 = 0;
   s->step = 0;
+  s->d_step = (int*)(s->ws + s->Lo.off_step);
   s->have_grads = false;
   s->prof_on = false;
   s->side = nullptr;
@@ -602,7 +607,8 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   const size_t P = s->Lo.P_total;
   bf_status r;
   if ((r = fill_f32(P, s->w32, 0.f, st)) != BF_OK || (r = fill_f32(P, s->m, 0.f, st)) != BF_OK ||
-      (r = fill_f32(P, s->v, 0.f, st)) != BF_OK || (r = fill_f32(P, s->g32, 0.f, st)) != BF_OK)
+      (r = fill_f32(P, s->v, 0.f, st)) != BF_OK || (r = fill_f32(P, s->g32, 0.f, st)) != BF_OK ||
+      (r = fill_f32(1, (float*)s->d_step, 0.f, st)) != BF_OK)  // integer 0 has the bit pattern of 0.f
     return fail(r);
   for (int l = 0; l < cfg->N_layers; ++l) {
     const int wt[4] = {BF_W_QKV, BF_W_O, BF_W_FC1, BF_W_FC2};
@@ -703,6 +709,7 @@ bf_status bf_reset_optimizer(bf_stack* s) {
   BF_HIP_CHECK(hipDeviceSynchronize());
   BF_TRY(fill_f32(s->Lo.P_total, s->m, 0.f, nullptr));
   BF_TRY(fill_f32(s->Lo.P_total, s->v, 0.f, nullptr));
+  BF_TRY(fill_f32(1, (float*)s->d_step, 0.f, nullptr));  // the bit pattern of integer 0
   BF_HIP_CHECK(hipDeviceSynchronize());
   s->step = 0;
   return BF_OK;
@@ -848,7 +855,10 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   s->have_grads = false;
   s->prof_on = timing == 2;
   s->prof_rec.clear();
-  if (apply_optimizer) s->step += 1;
+  if (apply_optimizer) {
+    s->step += 1;
+    BF_TRY(bump_step(s->d_step, st));
+  }
   int live = 0;
   int64_t peak_live = 0;
   size_t n_adam = 0, qi = 0;
@@ -973,7 +983,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam], as));
         BF_TRY(timed(s, BF_K_ADAM, 0.0, (double)n * (s->wlp ? 30.0 : 28.0), as, [&] {
           return adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
-                           c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as);
+                           s->d_step, c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay, as);
         }));
         if (lm) {
           // the input layer steps with the first stage, the output layer with the last
@@ -981,7 +991,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
             const size_t o = s->Lo.P_layers + s->D.voc_off[first - BF_E_TOK];
             const size_t cnt = s->D.voc_off[last - BF_E_TOK] + s->D.voc_elems[last - BF_E_TOK] - s->D.voc_off[first - BF_E_TOK];
             return timed(s, BF_K_ADAM, 0.0, (double)cnt * (lp_ptr(s, o) ? 30.0 : 28.0), as, [&] {
-              return adam_step(cnt, s->w32 + o, s->m + o, s->v + o, s->g32 + o, lp_ptr(s, o), s->step, c.lr, c.beta1, c.beta2,
+              return adam_step(cnt, s->w32 + o, s->m + o, s->v + o, s->g32 + o, lp_ptr(s, o), s->step, s->d_step, c.lr, c.beta1, c.beta2,
                                c.adam_eps, c.weight_decay, as);
             });
           };

@@ -444,3 +444,90 @@ def _random_rank_cases(n, seed):
 def test_randomly_drawn_pipeline_ranks(c):
     """The checks of the rank-step test on drawn pipeline depths, ranks, loop counts and flags."""
     test_rank_of_a_deeper_pipeline_matches_oracle(*c)
+
+
+@pytest.mark.parametrize("schedule", [bf.BF_SCHED_BF, bf.BF_SCHED_DF])
+def test_gradient_step_replays_from_a_hip_graph(schedule):
+    """With timing = 0 and queue_depth = 0 a step is kernel launches and event record / wait only
+    (everything pre-allocated, App. D.2; buffers cleared by fill kernels): it can be captured into a HIP graph.
+    Three replays, with unrelated eager work and synchronisations in between, each bit-identical to the
+    eager step."""
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 3
+    params = bf_inputs.make_params(29, Lyr, h, f, bf16=True)
+    x, dy = bf_inputs.make_batch(29, N_mb, S_mb, S_seq, h, bf16=True)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=0)
+    st = bf.Stack(cfg)
+    for l, p in enumerate(params):
+        for name, tid in bf.TENSOR_IDS.items():
+            st.bf_set_params(l, tid, p[name].reshape(-1))
+    dX, dDY = to_dev(x, True), to_dev(dy, True)
+    y, dx = torch.empty_like(dX), torch.empty_like(dX)
+    run = lambda: st.bf_run_step(schedule, N_loop, N_mb, S_mb, dX, dDY, y, dx, apply_optimizer=0, timing=0)
+    run()
+    torch.cuda.synchronize()
+    want = dict(y=y.clone(), dx=dx.clone(),
+                grads=[{n: st.bf_get_grads(l, t) for n, t in bf.TENSOR_IDS.items()} for l in range(Lyr)])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for replay in range(3):
+        y.zero_()
+        dx.zero_()
+        noise = torch.randn(1 << 20, device="cuda").cumsum(0).sum().item()   # eager work and a synchronisation
+        assert np.isfinite(noise)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want["y"]) and torch.equal(dx, want["dx"]), replay
+        for l in range(Lyr):
+            for n, t in bf.TENSOR_IDS.items():
+                assert np.array_equal(st.bf_get_grads(l, t), want["grads"][l][n]), (replay, l, n)
+    del graph
+    st.close()
+
+
+def test_optimizer_steps_replay_from_a_hip_graph():
+    """The optimizer's step count lives on the device and is advanced by the step itself, so a recorded
+    training step (breadth-first, Adam per stage on the side stream) keeps its bias corrections right
+    from replay to replay: eager step 1, then the graph replayed as steps 2 and 3, equals three eager steps."""
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 2
+    params = bf_inputs.make_params(31, Lyr, h, f, bf16=True)
+    x, dy = bf_inputs.make_batch(31, N_mb, S_mb, S_seq, h, bf16=True)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=0, lr=1e-3,
+                         weight_decay=0.01)
+    dX, dDY = to_dev(x, True), to_dev(dy, True)
+
+    def fresh():
+        st = bf.Stack(cfg)
+        for l, p in enumerate(params):
+            for name, tid in bf.TENSOR_IDS.items():
+                st.bf_set_params(l, tid, p[name].reshape(-1))
+        y, dx = torch.empty_like(dX), torch.empty_like(dX)
+        return st, y, dx, (lambda: st.bf_run_step(bf.BF_SCHED_BF, N_loop, N_mb, S_mb, dX, dDY, y, dx, apply_optimizer=1, timing=0))
+
+    def state(st):
+        torch.cuda.synchronize()
+        return [(st.bf_get_params(l, t), st.bf_get_moments(l, t, 0), st.bf_get_moments(l, t, 1))
+                for l in range(Lyr) for t in bf.TENSOR_IDS.values()]
+
+    st, y, dx, run = fresh()
+    for _ in range(3):
+        run()
+    want, want_y = state(st), y.clone()
+    st.close()
+
+    st, y, dx, run = fresh()
+    run()                                   # step 1, eager
+    snap = state(st)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):           # records step 2 (capture does not execute it)
+        run()
+    assert all(np.array_equal(a, b) for s0, s1 in zip(snap, state(st)) for a, b in zip(s0, s1)), "capture ran the step"
+    for _ in range(2):                      # steps 2 and 3
+        assert np.isfinite(torch.randn(1 << 18, device="cuda").sum().item())
+        graph.replay()
+    got = state(st)
+    assert torch.equal(y, want_y)
+    for (pw, mw, vw), (pg, mg, vg) in zip(want, got):
+        assert np.array_equal(pw, pg) and np.array_equal(mw, mg) and np.array_equal(vw, vg)
+    del graph
+    st.close()
