@@ -177,7 +177,9 @@ def main():
         dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
         y, dx = torch.empty_like(x), torch.empty_like(x)
 
-    sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 2)
+    # The timed region: the step as it runs in production (Adam of a finished stage on the side stream,
+    # under the backward of the next), with HIP events around the matrix products only (timing 3).
+    sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 3)
     r = rep_bf[-1]
     out_df = None
     if not args.no_df:
@@ -186,20 +188,28 @@ def main():
         out_df = {"ms_per_step": sec_df * 1e3, "model_tflops": rd.flops_model / sec_df / 1e12,
                   "peak_ckpt_count": rd.peak_ckpt_count, "peak_ckpt_bytes": rd.peak_ckpt_bytes,
                   "peak_act_bytes": rd.peak_act_bytes}
-    # one plain-timed BF step to show what the per-launch events cost
+    # one plain-timed BF step (no per-launch events at all), and two fully instrumented ones (events around
+    # every launch, Adam in line on the main stream so that nothing is timed together with it) for the
+    # classes that are not matrix products
     sec_plain, _ = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 1, 0, 1)
+    sec_instr, rep_instr = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 2, 0, 2)
 
-    # per-kernel-class figures, averaged over the timed BF steps
-    kern = {}
-    for i, name in enumerate(bf.binding.KERNEL_CLASSES):
-        ms = sum(rp.kernel_ms[i] for rp in rep_bf) / len(rep_bf)
-        n = sum(rp.kernel_launches[i] for rp in rep_bf) / len(rep_bf)
-        fl = sum(rp.kernel_flops[i] for rp in rep_bf) / len(rep_bf)
-        by = sum(rp.kernel_bytes[i] for rp in rep_bf) / len(rep_bf)
-        if n:
-            kern[name] = {"ms_per_step": ms, "launches": n, "avg_launch_ms": ms / n,
-                          "tflops": fl / ms / 1e9 if fl else None, "gbs": by / ms / 1e6 if by else None}
-    dom = max((k for k in kern if k.startswith("gemm")), key=lambda k: kern[k]["ms_per_step"])
+    def classes(reps):
+        out = {}
+        for i, name in enumerate(bf.binding.KERNEL_CLASSES):
+            ms = sum(rp.kernel_ms[i] for rp in reps) / len(reps)
+            n = sum(rp.kernel_launches[i] for rp in reps) / len(reps)
+            fl = sum(rp.kernel_flops[i] for rp in reps) / len(reps)
+            by = sum(rp.kernel_bytes[i] for rp in reps) / len(reps)
+            if n:
+                out[name] = {"ms_per_step": ms, "launches": n, "avg_launch_ms": ms / n,
+                             "tflops": fl / ms / 1e9 if fl else None, "gbs": by / ms / 1e6 if by else None}
+        return out
+    kern = classes(rep_instr)          # every class, from the instrumented steps
+    kern.update(classes(rep_bf))       # the matrix products, from the timed region itself
+    # the dominant kernel: one instantiation, the fused weight-gradient product (the forward class is
+    # three instantiations of similar total)
+    dom = "gemm_wgrad" if "gemm_wgrad" in kern else max((k for k in kern if k.startswith("gemm")), key=lambda k: kern[k]["ms_per_step"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kern[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
                 "flops_per_launch": kern[dom]["tflops"] * 1e9 * kern[dom]["avg_launch_ms"],
@@ -225,7 +235,8 @@ def main():
         "tokens_per_s": N_mb * S_mb * S_seq / sec_bf,
         "bf": {"peak_ckpt_count": r.peak_ckpt_count, "peak_ckpt_bytes": r.peak_ckpt_bytes,
                "peak_act_bytes": r.peak_act_bytes, "state_bytes": r.state_bytes, "adam_ms": r.adam_ms,
-               "ms_per_step_without_launch_events": sec_plain * 1e3},
+               "ms_per_step_without_launch_events": sec_plain * 1e3,
+               "ms_per_step_with_events_on_every_launch": sec_instr * 1e3},
         "df": out_df,
         "kernels": kern,
         "roofline": roofline,
@@ -242,7 +253,10 @@ def main():
         for name, sched, k in (("bf", bf.BF_SCHED_BF, min(args.steps, 3)), ("df", bf.BF_SCHED_DF, min(args.steps, 2))):
             if name == "df" and args.no_df:
                 continue
-            sec, reps = time_steps(fs, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, k, 1, 2)
+            # timed as it runs (reconstruction on the side stream under the compute of the other half);
+            # one instrumented step afterwards for the time the reconstruction kernels take by themselves
+            sec, _ = time_steps(fs, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, k, 1, 1)
+            _, reps = time_steps(fs, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, 1, 0, 2)
             rp = reps[-1]
             i = bf.binding.KERNEL_CLASSES.index("reconstruct")
             out_fs[name] = {"ms_per_step": sec * 1e3, "model_tflops": rp.flops_model / sec / 1e12,

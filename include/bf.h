@@ -107,7 +107,7 @@ typedef struct {
  * event, the count of Eq. mem_ckpt. */
 typedef struct { int32_t op, stage, mb, live_ckpt; } bf_event;
 
-/* Kernel classes of the per-launch timing (bf_run_step with timing == 2). */
+/* Kernel classes of the per-launch timing (bf_run_step with timing == 2 or 3). */
 typedef enum {
   BF_K_GEMM_FWD = 0,   /* Y = X W           (QKV, out-proj, FC1, FC2) */
   BF_K_GEMM_DGRAD = 1, /* dX = dY W^T */
@@ -131,8 +131,8 @@ typedef struct {
   int64_t state_bytes;      /* weights, Adam moments, main-grads, low-precision weights */
   int32_t n_events;
   int32_t timed;            /* 1 if gpu_ms / adam_ms are valid (bf_run_step ... timing != 0) */
-  /* timing == 2 only: per kernel class, summed over the step's launches: device time between
-   * events recorded around each launch on its stream, launch count, algorithmic flops
+  /* timing == 2 (every class) or 3 (the three matrix-product classes): per kernel class, summed over
+   * the step's launches: device time between events recorded around each launch on its stream, launch count, algorithmic flops
    * (2 M N K per product; attention with the causal half; backward attention 2.5 x forward) and
    * algorithmic HBM bytes (every operand read once, every result written once). */
   double kernel_ms[BF_N_KERNEL_CLASSES];
@@ -194,7 +194,9 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *   apply_optimizer  0: gradients only; 1: fused Adam per stage when its gradient is final
  *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end);
  *                2: as 1, plus an event pair around every kernel launch -> report->kernel_* (the optimizer
- *                   then runs on the caller's stream, so that no launch is timed together with it)
+ *                   then runs on the caller's stream, so that no launch is timed together with it);
+ *                3: as 1, plus event pairs around the matrix products only (all of them on the caller's
+ *                   stream); the optimizer stays on the side stream, i.e. the step runs as with timing 1
  *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
  *                on it (unless timing != 0); the library's side stream joins it before returning
  *                control of the stream to later work.

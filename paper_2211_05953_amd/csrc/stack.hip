@@ -243,8 +243,10 @@ struct bf_stack {
   std::vector<hipEvent_t> adam_ev;   // pairs of events per stage for timing
   std::vector<hipEvent_t> queue_ev;  // ring for the bounded launch queue
   std::vector<bf_event> trace;
-  // per-kernel-class timing (timing == 2): event pairs around every launch of a step
+  // per-kernel-class timing: event pairs around the launches of a step, every class (timing == 2) or
+  // the matrix products only (timing == 3); prof_mask has one bit per class
   bool prof_on;
+  unsigned prof_mask;
   std::vector<hipEvent_t> prof_ev;
   struct ProfRec { int cls; double flops, bytes; };
   std::vector<ProfRec> prof_rec;
@@ -341,7 +343,7 @@ Tmp tmp_of(bf_stack* s) {
 // Runs one kernel launcher; with profiling on, brackets it with a pair of events on its stream.
 template <typename F>
 bf_status timed(bf_stack* s, int cls, double flops, double bytes, hipStream_t st, F&& call) {
-  if (!s->prof_on) return call();
+  if (!s->prof_on || !((s->prof_mask >> cls) & 1u)) return call();
   const size_t i = s->prof_rec.size();
   while (s->prof_ev.size() < 2 * (i + 1)) {
     hipEvent_t e;
@@ -576,6 +578,7 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->d_step = (int*)(s->ws + s->Lo.off_step);
   s->have_grads = false;
   s->prof_on = false;
+  s->prof_mask = 0;
   s->side = nullptr;
   s->ev_grad_ready = s->ev_side_done = s->ev_t0 = s->ev_t1 = nullptr;
   hipStream_t st = (hipStream_t)stream;
@@ -761,6 +764,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   if (!s) { set_error("bf_run_step: null stack"); return BF_EINVAL; }
   const bf_config& c = s->cfg;
   if (schedule != BF_SCHED_BF && schedule != BF_SCHED_DF) { set_error("bf_run_step: unknown schedule %d", schedule); return BF_EINVAL; }
+  if (timing < 0 || timing > 3) { set_error("bf_run_step: timing %d outside 0..3", timing); return BF_EINVAL; }
   if (N_loop < 1 || c.N_layers % N_loop) { set_error("bf_run_step: N_loop = %d must divide N_layers = %d", N_loop, c.N_layers); return BF_EINVAL; }
   if (N_mb < 1 || N_mb > c.N_mb_max) { set_error("bf_run_step: N_mb = %d outside 1..%d", N_mb, c.N_mb_max); return BF_EINVAL; }
   if (S_mb < 1 || S_mb > c.S_mb_max) { set_error("bf_run_step: S_mb = %d outside 1..%d", S_mb, c.S_mb_max); return BF_EINVAL; }
@@ -853,7 +857,8 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
 
   s->trace.clear();
   s->have_grads = false;
-  s->prof_on = timing == 2;
+  s->prof_on = timing == 2 || timing == 3;
+  s->prof_mask = timing == 2 ? ~0u : (1u << BF_K_GEMM_FWD) | (1u << BF_K_GEMM_DGRAD) | (1u << BF_K_GEMM_WGRAD);
   s->prof_rec.clear();
   if (apply_optimizer) {
     s->step += 1;
