@@ -531,3 +531,47 @@ def test_optimizer_steps_replay_from_a_hip_graph():
         assert np.array_equal(pw, pg) and np.array_equal(mw, mg) and np.array_equal(vw, vg)
     del graph
     st.close()
+
+
+def test_timing_modes_fill_the_report_and_leave_the_numbers_alone():
+    """timing 1: step time; 2: an event pair around every launch, per-class sums in the report; 3: around
+    the matrix products only.  Launch counts follow from the layer structure (4 forward, 4 dgrad and 4
+    weight-gradient products, 2 LayerNorms each way, 1 attention each way per layer and micro-batch; one
+    fused weight-gradient product per weight and stage); the results do not depend on the mode."""
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 3
+    params = bf_inputs.make_params(37, Lyr, h, f, bf16=True)
+    x, dy = bf_inputs.make_batch(37, N_mb, S_mb, S_seq, h, bf16=True)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1)
+    st = bf.Stack(cfg)
+    for l, p in enumerate(params):
+        for name, tid in bf.TENSOR_IDS.items():
+            st.bf_set_params(l, tid, p[name].reshape(-1))
+    dX, dDY = to_dev(x, True), to_dev(dy, True)
+    y, dx = torch.empty_like(dX), torch.empty_like(dX)
+    K_ = {n: i for i, n in enumerate(bf.binding.KERNEL_CLASSES)}
+    outs = []
+    for timing in (0, 1, 2, 3):
+        rep = st.bf_run_step(bf.BF_SCHED_BF, N_loop, N_mb, S_mb, dX, dDY, y, dx, apply_optimizer=0, timing=timing)
+        torch.cuda.synchronize()
+        outs.append((y.clone(), dx.clone(), st.bf_get_grads(1, bf.TENSOR_IDS["w_fc1"])))
+        n = lambda cls: int(rep.kernel_launches[K_[cls]])
+        lm = Lyr * N_mb
+        if timing == 0:
+            assert rep.timed == 0
+        else:
+            assert rep.timed == 1 and rep.gpu_ms > 0
+        if timing in (2, 3):
+            assert (n("gemm_fwd"), n("gemm_dgrad"), n("gemm_wgrad")) == (4 * lm, 4 * lm, 4 * Lyr)
+            assert all(rep.kernel_ms[K_[c]] > 0 and rep.kernel_flops[K_[c]] > 0 for c in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
+            assert rep.kernel_flops[K_["gemm_fwd"]] == rep.kernel_flops[K_["gemm_dgrad"]] == rep.kernel_flops[K_["gemm_wgrad"]]
+        if timing == 2:
+            assert (n("attn_fwd"), n("attn_bwd"), n("ln_fwd"), n("ln_bwd"), n("colsum")) == (lm, lm, 2 * lm, 2 * lm, 4 * lm)
+        if timing in (0, 1):
+            assert sum(int(v) for v in rep.kernel_launches) == 0
+        if timing == 3:
+            assert n("attn_fwd") == n("ln_fwd") == n("colsum") == n("adam") == 0
+    for yy, dd, gg in outs[1:]:
+        assert torch.equal(yy, outs[0][0]) and torch.equal(dd, outs[0][1]) and np.array_equal(gg, outs[0][2])
+    with pytest.raises(bf.BfError):
+        st.bf_run_step(bf.BF_SCHED_BF, N_loop, N_mb, S_mb, dX, dDY, y, dx, timing=4)
+    st.close()
