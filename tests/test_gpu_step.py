@@ -575,3 +575,26 @@ def test_timing_modes_fill_the_report_and_leave_the_numbers_alone():
     with pytest.raises(bf.BfError):
         st.bf_run_step(bf.BF_SCHED_BF, N_loop, N_mb, S_mb, dX, dDY, y, dx, timing=4)
     st.close()
+
+
+@pytest.mark.parametrize("depth", [1, 3, 64])
+def test_bounded_launch_queue_changes_nothing_but_the_host_pace(depth):
+    """queue_depth > 0: the host waits for the op issued `depth` ops earlier before issuing the next one
+    (pre-allocation with a bounded kernel queue, App. D.2).  Same launches in the same order: outputs
+    and main-grads bit-identical to the unbounded queue, in both orders, optimizer on."""
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 3
+    params = bf_inputs.make_params(41, Lyr, h, f, bf16=True)
+    x, dy = bf_inputs.make_batch(41, N_mb, S_mb, S_seq, h, bf16=True)
+    got = {}
+    for qd in (0, depth):
+        cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=qd, lr=1e-3)
+        for code in (bf.BF_SCHED_BF, bf.BF_SCHED_DF):
+            got[qd, code] = _run_gpu(cfg, params, x, dy, code, N_loop, N_mb, S_mb, apply_optimizer=1, steps=2)
+    for code in (bf.BF_SCHED_BF, bf.BF_SCHED_DF):
+        a0, a1 = got[0, code], got[depth, code]
+        assert np.array_equal(a0["y"], a1["y"]) and np.array_equal(a0["dx"], a1["dx"])
+        assert a0["trace"] == a1["trace"]
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                assert np.array_equal(a0["grads"][l][name], a1["grads"][l][name]), (l, name)
+                assert np.array_equal(a0["params"][l][name], a1["params"][l][name]), (l, name)
