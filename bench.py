@@ -117,6 +117,44 @@ def power_check(bf, h):
     return out
 
 
+def sweep(bf, w, extra, which):
+    """The workload in both orders over the micro-batch count (1 .. N_mb, powers of two) or over the
+    loop count (the divisors of N_layers): one-GPU counterparts of the paper's sweeps of Fig. 5 and
+    Fig. 6.  Untimed launches (timing 0), optimizer on, wall clock between device synchronisations."""
+    import torch
+    Lyr, N_loop0, h, a, f, S_seq, S_mb, N_mb0, dtype, ckpt = w
+    b16 = dtype == "bf16"
+    td = torch.bfloat16 if b16 else torch.float32
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x221105953)
+    X = torch.randn((N_mb0, S_mb, S_seq, h), generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+    DY = torch.randn((N_mb0, S_mb, S_seq, h), generator=gen, device="cuda:0", dtype=torch.float32).to(td)
+    if which == "N_mb":
+        points = [(N_loop0, n) for n in (1, 2, 4, 8, 16, 32, 64) if n <= N_mb0]
+    else:
+        points = [(n, N_mb0) for n in range(1, Lyr + 1) if Lyr % n == 0]
+    out, st, made_for = [], None, None
+    for N_loop, N_mb in points:
+        if made_for != N_loop:
+            if st is not None:
+                st.close()
+                del st
+                torch.cuda.empty_cache()
+            cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb0, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
+                                 ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
+                                 fuse_wgrad=1, N_loop_min=N_loop, **extra)
+            st, made_for = bf.Stack(cfg, device="cuda:0"), N_loop
+        x, dy = X[:N_mb].contiguous(), DY[:N_mb].contiguous()
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        p = {"N_loop": N_loop, "N_mb": N_mb, "workspace_bytes": int(bf.bf_workspace_bytes(cfg))}
+        for name, sched in (("bf", bf.BF_SCHED_BF), ("df", bf.BF_SCHED_DF)):
+            sec, reps = time_steps(st, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, 3 if N_mb >= 4 else 8, 1, 0)
+            p[name] = {"ms_per_step": sec * 1e3, "model_tflops": reps[-1].flops_model / sec / 1e12}
+        out.append(p)
+    st.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +169,8 @@ def main():
                     help="skip the fully-sharded (dp_fs = 1) BF and DF steps reported under \"dp_fs\"")
     ap.add_argument("--no-power-check", action="store_true",
                     help="skip the product timed on random and on zero operands reported under \"power_check\"")
+    ap.add_argument("--sweep", choices=["N_mb", "N_loop"],
+                    help="instead of the benchmark line: both orders over the micro-batch count or the loop count")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run a 1 GiB device copy (known HBM traffic) so that FETCH_SIZE / WRITE_SIZE "
                          "readings of a rocprofv3 --pmc run of this command can be scaled")
@@ -152,6 +192,14 @@ def main():
                          fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop, **EXTRA.get(args.workload, {}))
     S_voc = cfg.S_voc
     torch.cuda.set_device(0)
+    if args.sweep:
+        if S_voc:
+            print("bench.py: --sweep runs the stack on activations (workloads without S_voc)", file=sys.stderr)
+            sys.exit(2)
+        print(json.dumps({"sweep": args.sweep, "workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]),
+                          "unit": "model TFLOP/s", "data": "synthetic",
+                          "points": sweep(bf, w, EXTRA.get(args.workload, {}), args.sweep)}))
+        return
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
