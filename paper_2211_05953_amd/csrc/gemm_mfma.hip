@@ -111,20 +111,43 @@ struct Stager {
   }
 };
 
+// Lane part of a K-contiguous fragment address, per k-step: the XOR key only has row bits 1-3, which
+// come from the lane (fragments start at multiples of 16 rows), so a fragment's address is this
+// offset plus a compile-time multiple of 16 rows and every read takes an immediate.
+struct KFragLane {
+  int o[2];
+  __device__ __forceinline__ void init(int lane) {
+    const int l15 = lane & 15;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) o[kk] = l15 * BK + (((kk * 4 + (lane >> 4)) ^ kswz(l15)) << 3);
+  }
+};
+
+// The same for a transposed tile of R columns.  The key (16 columns) depends on the lane's 16-lane
+// group only; XORed into the column it moves a fragment that starts at an even multiple of 16
+// columns up and one that starts at an odd multiple down, hence one offset per parity.
+template <int R>
+struct TFragLane {
+  int o[2];
+  __device__ __forceinline__ void init(int lane) {
+    const int t = lane & 15, blk = lane >> 4;
+    const int k = 8 * blk + (t >> 2), c4 = 4 * (t & 3);
+#pragma unroll
+    for (int par = 0; par < 2; ++par) o[par] = k * (R + TPAD) + (((16 * par + c4) ^ (tkey(k) << 3)) - 16 * par);
+  }
+};
+
 // ---- LDS -> MFMA fragment: 8 consecutive k of row/column (r16 + lane % 16), k-step kk (32 wide)
+// r16: first row / column of the fragment relative to lds, a multiple of 16 (lds itself starts at a
+// multiple of 32 rows / columns of the tile)
 template <bool KCONTIG, int R>
-__device__ __forceinline__ bf16x8 load_frag(const bf16_t* lds, int r16, int kk, int lane) {
+__device__ __forceinline__ bf16x8 load_frag(const bf16_t* lds, int r16, int kk, const KFragLane& kl, const TFragLane<R>& tl) {
   if (KCONTIG) {
-    const int row = r16 + (lane & 15);
-    const int kc = kk * 4 + (lane >> 4);
-    return *reinterpret_cast<const bf16x8*>(lds + row * BK + ((kc ^ kswz(row)) << 3));
+    return *reinterpret_cast<const bf16x8*>(lds + r16 * BK + kl.o[kk]);
   } else {
     // one transpose load: the 16 lanes of a group read 4 k-rows x 16 columns, 4 columns each, and
     // every lane receives the 4 k of its own column; two of them give the lane its 8 k
-    const int t = lane & 15, blk = lane >> 4;
-    const int k = kk * 32 + 8 * blk + (t >> 2);
-    const int col = r16 + 4 * (t & 3);
-    const bf16_t* p = lds + k * (R + TPAD) + (col ^ (tkey(k) << 3));
+    const bf16_t* p = lds + kk * 32 * (R + TPAD) + r16 + tl.o[(r16 >> 4) & 1];
     typedef s16x4 __attribute__((address_space(3))) * lds_v4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * (R + TPAD)));  // k + 4: same key
@@ -236,16 +259,23 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     // no LDS latency is exposed behind the barrier.  Within a phase the scheduler is told to
     // alternate one MFMA with one LDS/global access.
     constexpr int MH = MI / 2;
+    static_assert(TL::TM % 32 == 0 && TL::TN % 32 == 0, "a wave's sub-tile starts at a multiple of 32");
+    KFragLane kl;
+    TFragLane<BM> tla;
+    TFragLane<BN> tlb;
+    kl.init(lane);
+    tla.init(lane);
+    tlb.init(lane);
     constexpr int NRA = AK ? MH : 2 * MH, NRB = BKC ? NI : 2 * NI;  // LDS reads of an A half / of B
     constexpr int NMMA = MH * NI;
     bf16x8 af[2][MH], bfr[2][NI];
     auto ldA = [&](int buf, const bf16_t* as, int kk, int half) {
 #pragma unroll
-      for (int i = 0; i < MH; ++i) af[buf][i] = load_frag<AK, BM>(as, wm * TL::TM + (half * MH + i) * 16, kk, lane);
+      for (int i = 0; i < MH; ++i) af[buf][i] = load_frag<AK, BM>(as + wm * TL::TM * (AK ? BK : 1), (half * MH + i) * 16, kk, kl, tla);
     };
     auto ldB = [&](int buf, const bf16_t* bs, int kk) {
 #pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[buf][j] = load_frag<BKC, BN>(bs, wn * TL::TN + j * 16, kk, lane);
+      for (int j = 0; j < NI; ++j) bfr[buf][j] = load_frag<BKC, BN>(bs + wn * TL::TN * (BKC ? BK : 1), j * 16, kk, kl, tlb);
     };
     auto mma = [&](int abuf, int bbuf, auto half) {
       constexpr int H = decltype(half)::value;
