@@ -299,10 +299,11 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
       }
       __builtin_amdgcn_sched_barrier(0);  // nothing moves across the end of a phase
     };
-    constexpr int NCH = Stager<AK, BM, NT>::CHUNKS + Stager<BKC, BN, NT>::CHUNKS;
     typedef std::integral_constant<int, 0x200> MW;
     typedef std::integral_constant<int, 0x020> MG;
-    typedef std::integral_constant<int, NCH> NC;
+    constexpr bool SPLIT = AK;  // staging of A in phase 2 instead of phase 0
+    typedef std::integral_constant<int, (SPLIT ? 0 : Stager<AK, BM, NT>::CHUNKS) + Stager<BKC, BN, NT>::CHUNKS> NC0;
+    typedef std::integral_constant<int, Stager<AK, BM, NT>::CHUNKS> NC2;
     typedef std::integral_constant<int, 0> N0;
     typedef std::integral_constant<int, NRA> RA;
     typedef std::integral_constant<int, NRA + NRB> RAB;
@@ -326,21 +327,25 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
       const bf16_t* bs = as + A_ST;
       const bf16_t* an = smem + (cur ^ 1) * STAGE;
       const bf16_t* bn2 = an + A_ST;
-      // phase 0: tile kt+1 (in registers since the previous iteration) goes to the other stage
+      // phase 0: tile kt+1 (in registers since the previous iteration) goes to the other stage.  With
+      // a K-contiguous A (forward, dgrad) only its B part: the A part follows in phase 2, the phase with
+      // the fewest fragment reads, so that the phases issue about the same number of memory
+      // instructions beside their MFMAs (+2-6 % on the forward products; the weight-gradient layout,
+      // all transpose loads, is 2 % faster with everything in phase 0).
       ldA(1, as, 0, 1);
       if constexpr (decltype(do_store)::value) {
-        sa.store(smem + (cur ^ 1) * STAGE);
+        if constexpr (!SPLIT) sa.store(smem + (cur ^ 1) * STAGE);
         sb.store(smem + (cur ^ 1) * STAGE + A_ST);
       }
+      // the registers are free again as soon as their LDS store has issued: the loads of tile kt+2
+      // follow at once, a full k-tile ahead of their use
       if constexpr (decltype(do_load)::value) {
-        // the registers are free again as soon as their LDS store has issued: the loads of tile kt+2
-        // follow at once, a full k-tile ahead of their use
-        sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
+        if constexpr (!SPLIT) sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
         sb.load(seg_b_of(kt + 2), ldb, n0, k0_of(kt + 2));
       }
       mma(0, 0, H0{});
-      if constexpr (decltype(do_load)::value) interleave2(RA{}, MW{}, NC{}, MG{}, NC{});
-      else if constexpr (decltype(do_store)::value) interleave2(RA{}, MW{}, NC{}, MW{}, N0{});
+      if constexpr (decltype(do_load)::value) interleave2(RA{}, MW{}, NC0{}, MG{}, NC0{});
+      else if constexpr (decltype(do_store)::value) interleave2(RA{}, MW{}, NC0{}, MW{}, N0{});
       else interleave2(RA{}, MW{}, N0{}, MW{}, N0{});
       // phase 1
       ldA(0, as, 1, 0);
@@ -349,8 +354,12 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
       interleave2(RAB{}, MW{}, N0{}, MW{}, N0{});
       // phase 2
       ldA(1, as, 1, 1);
+      if constexpr (SPLIT && decltype(do_store)::value) sa.store(smem + (cur ^ 1) * STAGE);
+      if constexpr (SPLIT && decltype(do_load)::value) sa.load(seg_a_of(kt + 2), lda, m0, k0_of(kt + 2));
       mma(0, 1, H0{});
-      interleave2(RA{}, MW{}, N0{}, MW{}, N0{});
+      if constexpr (SPLIT && decltype(do_load)::value) interleave2(RA{}, MW{}, NC2{}, MG{}, NC2{});
+      else if constexpr (SPLIT && decltype(do_store)::value) interleave2(RA{}, MW{}, NC2{}, MW{}, N0{});
+      else interleave2(RA{}, MW{}, N0{}, MW{}, N0{});
       __syncthreads();
       // phase 3, overlapped with the fetch of the next stage's first fragments
       ldA(0, an, 0, 0);
