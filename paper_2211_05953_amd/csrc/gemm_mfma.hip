@@ -246,9 +246,11 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
   };
   const int nk_seg = K / BK, nk = nk_seg * n_seg;
   // k-tile kt lives in segment kt / nk_seg (one segment unless this is a multi-micro-batch weight gradient)
-  auto seg_a_of = [&](int kt) { return A + (size_t)(kt / nk_seg) * seg_a; };
-  auto seg_b_of = [&](int kt) { return B + (size_t)(kt / nk_seg) * seg_b; };
-  auto k0_of = [&](int kt) { return (kt % nk_seg) * BK; };
+  // (only the weight-gradient product is launched with segments: the others skip the division)
+  constexpr bool SEGS = EPI == E_ACCUM;
+  auto seg_a_of = [&](int kt) { return SEGS ? A + (size_t)(kt / nk_seg) * seg_a : A; };
+  auto seg_b_of = [&](int kt) { return SEGS ? B + (size_t)(kt / nk_seg) * seg_b : B; };
+  auto k0_of = [&](int kt) { return SEGS ? (kt % nk_seg) * BK : kt * BK; };
   {
     // A k-tile is two k-steps of 32; a k-step runs in two phases, one per half of the wave's A
     // fragments (MI / 2 x NI MFMAs each), so that only half of them are live at a time.  Phase p uses
