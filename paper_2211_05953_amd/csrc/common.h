@@ -40,6 +40,10 @@ struct GemmArgs {
   // micro-batches of a stage.  n_seg <= 1 means a single segment.
   int n_seg = 1;
   size_t seg_stride_a = 0, seg_stride_b = 0;
+  // Weight-gradient layout only: when not null, the column sums of B over all K rows of all
+  // segments (the bias gradient that goes with the weight gradient) are written to colsum[N], fp32,
+  // overwritten or added to as `accumulate` says.
+  float* colsum = nullptr;
 };
 
 void set_error(const char* fmt, ...);

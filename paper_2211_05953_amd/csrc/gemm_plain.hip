@@ -126,13 +126,26 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 }
 
 bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st) {
+  if (a.colsum && layout != L_TN) { set_error("gemm: column sums go with the weight-gradient layout"); return BF_EINVAL; }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
+  bf_status s;
   if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
-    bf_status s = gemm_check(layout, epi, a);
-    if (s != BF_OK) return s;
-    return gemm_mfma(layout, epi, a, st);
+    s = gemm_check(layout, epi, a);
+    if (s == BF_OK) s = gemm_mfma(layout, epi, a, st);
+  } else {
+    s = gemm_plain(dtype, layout, epi, a, st);
   }
-  return gemm_plain(dtype, layout, epi, a, st);
+  if (s != BF_OK || !a.colsum) return s;
+  // The bias gradient beside the weight gradient: one pass of the column-reduction kernel per
+  // segment.  (Taking the sums inside the MFMA product, as ones^T B on a few workgroups, was
+  // measured: those workgroups run 10 % longer and end up as the stragglers of their rounds, which
+  // costs the product 2 % and gains the step 0.1 %.)
+  const size_t es = dtype == BF_BF16 ? 2 : 4;
+  for (int i = 0; i < (a.n_seg > 1 ? a.n_seg : 1); ++i) {
+    s = colsum(dtype, a.K, a.N, (const char*)a.B + (size_t)i * a.seg_stride_b * es, a.colsum, i > 0 ? 1 : a.accumulate, st);
+    if (s != BF_OK) return s;
+  }
+  return BF_OK;
 }
 
 }  // namespace bf

@@ -21,6 +21,18 @@ bf_status bf_op_gemm(int dtype, int kernels, int layout, int epilogue, int M, in
   return gemm(dtype, kernels, layout, epilogue, a, (hipStream_t)stream);
 }
 
+bf_status bf_op_wgrad(int dtype, int kernels, int M, int N, int K, int n_seg, const void* X, size_t stride_x,
+                      const void* dY, size_t stride_dy, float* G, float* db, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (n_seg < 1) { set_error("bf_op_wgrad: n_seg must be at least 1"); return BF_EINVAL; }
+  GemmArgs a{M, N, K, X, dY, G, nullptr, nullptr, nullptr, accumulate};
+  a.n_seg = n_seg;
+  a.seg_stride_a = stride_x;
+  a.seg_stride_b = stride_dy;
+  a.colsum = db;
+  return gemm(dtype, kernels, L_TN, E_ACCUM, a, (hipStream_t)stream);
+}
+
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K) {
   return gemm_mfma_supported(layout, epilogue, M, N, K) ? 1 : 0;
 }

@@ -154,6 +154,36 @@ def test_gemm_mfma_large_tile(M, N, K):
     assert rel_err(to_host(G), 2 * acc) <= 1e-5   # bf16 products are exact in fp32; only the summation order differs
 
 
+@pytest.mark.parametrize("mode,dtype,kernels", [("fp32", bf.BF_FP32, bf.BF_KERNELS_AUTO), ("bf16", bf.BF_BF16, bf.BF_KERNELS_PLAIN),
+                                                ("bf16", bf.BF_BF16, bf.BF_KERNELS_AUTO)])
+@pytest.mark.parametrize("M,N,K,n_seg,gap", [(256, 512, 128, 3, 0), (1024, 768, 128, 2, 64), (128, 384, 64, 2, 8), (512, 256, 192, 4, 0),
+                                             (768, 128, 64, 1, 0), (200, 136, 72, 3, 16)])
+def test_wgrad_over_the_micro_batches_of_a_stage(mode, dtype, kernels, M, N, K, n_seg, gap):
+    """G = sum_i X_i^T dY_i and db = sum_i colsum(dY_i) in one call (Sec. 4.2: the gradient of a stage
+    is needed only after all its micro-batches); segments lie `gap` elements apart beyond their size."""
+    b16 = dtype == bf.BF_BF16
+    sx, sy = K * M + gap, K * N + gap
+    X = bf_inputs.normal(9, 0, (n_seg * sx,), bf16=b16)
+    dY = bf_inputs.normal(9, 1, (n_seg * sy,), 0.3, bf16=b16)
+    G_ref, db_ref = np.zeros((M, N)), np.zeros(N)
+    for i in range(n_seg):
+        Xi = X[i * sx:i * sx + K * M].reshape(K, M).astype(np.float64)
+        dYi = dY[i * sy:i * sy + K * N].reshape(K, N).astype(np.float64)
+        G_ref += Xi.T @ dYi
+        db_ref += dYi.sum(0)
+    dX, ddY = to_dev(X, b16), to_dev(dY, b16)
+    G = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    bf.bf_op_wgrad(dtype, kernels, M, N, K, n_seg, dX, sx, ddY, sy, G, db, accumulate=0)
+    assert rel_err(to_host(G), G_ref) <= 1e-5 and rel_err(to_host(db), db_ref) <= 1e-5
+    bf.bf_op_wgrad(dtype, kernels, M, N, K, n_seg, dX, sx, ddY, sy, G, db, accumulate=1)
+    assert rel_err(to_host(G), 2 * G_ref) <= 1e-5 and rel_err(to_host(db), 2 * db_ref) <= 1e-5
+    # without the bias gradient: db is left alone
+    keep = to_host(db).copy()
+    bf.bf_op_wgrad(dtype, kernels, M, N, K, n_seg, dX, sx, ddY, sy, G, None, accumulate=0)
+    assert rel_err(to_host(G), G_ref) <= 1e-5 and np.array_equal(to_host(db), keep)
+
+
 @pytest.mark.parametrize("n", [1, 1000, 4096 * 33 + 4])
 def test_adam_kernel(n):
     rng = np.random.default_rng(4)
