@@ -415,6 +415,16 @@ inline int grid_for(size_t n, int per_block) {
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// Compute units of the current device (256 on MI355X).
+inline int compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1) cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
 }  // namespace
 
 #define BF_LAUNCH_CHECK()                                 \
@@ -506,7 +516,10 @@ bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16
   const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
   const bool vec = n % 4 == 0 && aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
                    (!w_lp || ((uintptr_t)w_lp & 7) == 0);
-  if (vec) adam_kernel<4><<<grid_for(n, 1024), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2, t_dev);
+  // One workgroup of four waves per compute unit streams fastest (measured on 1.6e9 parameters: 5.2 TB/s
+  // against 4.8 with 16 workgroups per unit, 5.0 with two, 3.5 with half a workgroup's threads).
+  const int grid4 = grid_for(n, 1024) < compute_units() ? grid_for(n, 1024) : compute_units();
+  if (vec) adam_kernel<4><<<grid4, 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2, t_dev);
   else adam_kernel<1><<<grid_for(n, 256), 256, 0, st>>>(n, w, m, v, g, w_lp, lr, beta1, beta2, eps, wd, c1, c2, omb1, omb2, t_dev);
   BF_LAUNCH_CHECK();
   return BF_OK;
