@@ -244,22 +244,38 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_reg_kernel(const T* __r
   }
 }
 
+// Compute units of the current device (256 on MI355X).
+inline int compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1) cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
 // ---------------------------------------------------- column reductions (fixed order)
 // Workgroup = CG column groups x RG row groups (CG * RG = 256); thread (cx, ry) owns VEC adjacent
 // columns and rows ry, ry + RG, ...  Partial sums meet in LDS and are added in ascending ry.
 // A workgroup covers CG * VEC columns: narrow enough that the few thousand columns of a bias
 // or LayerNorm gradient still spread over all compute units, wide enough (>= 128 bytes per
-// row) to keep the row reads in whole cache lines.
+// row) to keep the row reads in whole cache lines.  When that gives fewer workgroups than compute
+// units the launcher halves the width (CG = 4: two workgroups share each 128-byte line) and sets
+// `pair`: workgroups go to the 8 XCDs round-robin, so the two halves of a line are given to
+// workgroups b and b + 8, which share an XCD and its L2.
 // MODE 0: out[c] = sum_t dY[t,c]
 // MODE 1: dg[c] = sum_t dY[t,c] * xhat[t,c],  db[c] = sum_t dY[t,c]
 template <typename T, int VEC, int MODE, int CG>
 __global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ dY, const T* __restrict__ x,
                                                          const float* __restrict__ stats, float* __restrict__ out0,
-                                                         float* __restrict__ out1, int T_rows, int N, int accumulate) {
+                                                         float* __restrict__ out1, int T_rows, int N, int accumulate,
+                                                         int pair) {
   constexpr int RG = 256 / CG;
   __shared__ float part[MODE == 1 ? 2 : 1][RG][CG * VEC + 1];
   const int cx = threadIdx.x % CG, ry = threadIdx.x / CG;
-  const int c0 = (blockIdx.x * CG + cx) * VEC;
+  const int b = blockIdx.x;
+  const int blk = pair ? (b & 7) * 2 + ((b >> 3) & 1) + (b >> 4) * 16 : b;  // a bijection on every 16 workgroups
+  const int c0 = (blk * CG + cx) * VEC;
   float a0[VEC], a1[VEC];
 #pragma unroll
   for (int j = 0; j < VEC; ++j) a0[j] = a1[j] = 0.f;
@@ -315,7 +331,7 @@ __global__ __launch_bounds__(256) void col_reduce_kernel(const T* __restrict__ d
   }
   __syncthreads();
   for (int c = threadIdx.x; c < CG * VEC; c += 256) {
-    const int col = blockIdx.x * CG * VEC + c;
+    const int col = blk * CG * VEC + c;
     if (col >= N) continue;
     float s0 = 0.f, s1 = 0.f;
 #pragma unroll 8
@@ -333,7 +349,12 @@ void launch_col_reduce(const void* dY, const void* x, const float* stats, float*
                        int accumulate, hipStream_t st) {
   constexpr int CG = 8;  // 8 x VEC columns per workgroup, 32 row groups
   const int blocks = (N + CG * VEC - 1) / (CG * VEC);
-  col_reduce_kernel<T, VEC, MODE, CG><<<blocks, 256, 0, st>>>((const T*)dY, (const T*)x, stats, out0, out1, T_rows, N, accumulate);
+  if (VEC >= 4 && blocks < compute_units()) {
+    const int nb = (N + 4 * VEC - 1) / (4 * VEC);
+    col_reduce_kernel<T, VEC, MODE, 4><<<nb, 256, 0, st>>>((const T*)dY, (const T*)x, stats, out0, out1, T_rows, N, accumulate, nb % 16 == 0);
+    return;
+  }
+  col_reduce_kernel<T, VEC, MODE, CG><<<blocks, 256, 0, st>>>((const T*)dY, (const T*)x, stats, out0, out1, T_rows, N, accumulate, 0);
 }
 
 // ------------------------------------------------------------------------- fused Adam
@@ -414,16 +435,6 @@ inline int grid_for(size_t n, int per_block) {
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-
-// Compute units of the current device (256 on MI355X).
-inline int compute_units() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1) cu = 256;
-    return cu;
-  }();
-  return n;
-}
 
 }  // namespace
 
