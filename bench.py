@@ -225,8 +225,9 @@ def main():
         dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(td)
         y, dx = torch.empty_like(x), torch.empty_like(x)
 
-    # The timed region: the step as it runs in production (Adam of a finished stage on the side stream,
-    # under the backward of the next), with HIP events around the matrix products only (timing 3).
+    # The timed region: the step as it runs in production (Adam of a stage as soon as its gradient is
+    # final), with HIP events around the weight-gradient products only, the
+    # class with the most time (timing 3: 64 events per step at C3 instead of 2000 and more).
     sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 3)
     r = rep_bf[-1]
     out_df = None
@@ -238,7 +239,7 @@ def main():
                   "peak_act_bytes": rd.peak_act_bytes}
     # one plain-timed BF step (no per-launch events at all), and two fully instrumented ones (events around
     # every launch, Adam in line on the main stream so that nothing is timed together with it) for the
-    # classes that are not matrix products
+    # other classes
     sec_plain, _ = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 1, 0, 1)
     sec_instr, rep_instr = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 2, 0, 2)
 
@@ -254,7 +255,7 @@ def main():
                              "tflops": fl / ms / 1e9 if fl else None, "gbs": by / ms / 1e6 if by else None}
         return out
     kern = classes(rep_instr)          # every class, from the instrumented steps
-    kern.update(classes(rep_bf))       # the matrix products, from the timed region itself
+    kern.update(classes(rep_bf))       # the weight-gradient products, from the timed region itself
     # the dominant kernel: one instantiation, the fused weight-gradient product (the forward class is
     # three instantiations of similar total)
     dom = "gemm_wgrad" if "gemm_wgrad" in kern else max((k for k in kern if k.startswith("gemm")), key=lambda k: kern[k]["ms_per_step"])

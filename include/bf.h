@@ -121,7 +121,7 @@ typedef enum {
 
 typedef struct {
   double gpu_ms;            /* whole step on the device (events on the caller's stream) */
-  double adam_ms;           /* sum of the fused Adam launches (side stream in BF) */
+  double adam_ms;           /* sum of the fused Adam launches */
   double flops_model;       /* 3 x forward (linears + full attention), per step */
   double flops_paper;       /* Eq. compute x S_seq: 4 x forward */
   double flops_executed;    /* what the kernels ran: causal half, in-kernel recompute, checkpoint recompute */
@@ -131,7 +131,7 @@ typedef struct {
   int64_t state_bytes;      /* weights, Adam moments, main-grads, low-precision weights */
   int32_t n_events;
   int32_t timed;            /* 1 if gpu_ms / adam_ms are valid (bf_run_step ... timing != 0) */
-  /* timing == 2 (every class) or 3 (the three matrix-product classes): per kernel class, summed over
+  /* timing == 2 (every class) or 3 (the weight-gradient products): per kernel class, summed over
    * the step's launches: device time between events recorded around each launch on its stream, launch count, algorithmic flops
    * (2 M N K per product; attention with the causal half; backward attention 2.5 x forward) and
    * algorithmic HBM bytes (every operand read once, every result written once). */
@@ -193,13 +193,13 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *   y, dx        device outputs, same shape/dtype; either may be NULL
  *   apply_optimizer  0: gradients only; 1: fused Adam per stage when its gradient is final
  *   timing       0: no events; 1: fill report->gpu_ms / adam_ms (synchronises at the end);
- *                2: as 1, plus an event pair around every kernel launch -> report->kernel_* (the optimizer
- *                   then runs on the caller's stream, so that no launch is timed together with it);
- *                3: as 1, plus event pairs around the matrix products only (all of them on the caller's
- *                   stream); the optimizer stays on the side stream, i.e. the step runs as with timing 1
+ *                2: as 1, plus an event pair around every kernel launch -> report->kernel_*;
+ *                3: as 1, plus event pairs around the weight-gradient products only (the class with
+ *                   the most time): a few dozen to a few hundred events per step instead of thousands
  *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
- *                on it (unless timing != 0); the library's side stream joins it before returning
- *                control of the stream to later work.
+ *                on it (unless timing != 0); the library's side stream (dp_fs reconstructions) joins
+ *                it before returning control of the stream to later work.  The optimizer runs on
+ *                the caller's stream.
  *   report       may be NULL
  * With timing = 0 and cfg.queue_depth = 0 the call enqueues kernel launches and event record / wait
  * only (no allocation, no memset or copy, no host synchronisation) and may be recorded into a HIP
