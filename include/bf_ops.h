@@ -49,8 +49,8 @@ int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
  * before the gradient is needed, Sec. 4.2; fp32 main-grads, App. D):
  *   G[M,N]  = (accumulate ? G  : 0) + sum_{i < n_seg} X_i[K,M]^T dY_i[K,N]
  *   db[N]   = (accumulate ? db : 0) + sum_{i < n_seg} sum_k dY_i[k,:]          (db may be NULL)
- * X_i = X + i * stride_x and dY_i = dY + i * stride_dy (strides in elements; multiples of 8 in
- * bf16 for the MFMA kernel), both in the activation dtype, device memory; G and db fp32, device
+ * X_i = X + i * stride_x and dY_i = dY + i * stride_dy (strides in elements; the MFMA kernel takes
+ * bf16 segments that are 16-byte aligned, others go to the plain kernel), both in the activation dtype, device memory; G and db fp32, device
  * memory, owned by the caller.  BF_EINVAL for bad sizes, null X / dY / G or n_seg < 1. */
 bf_status bf_op_wgrad(int dtype, int kernels, int M, int N, int K, int n_seg, const void* X, size_t stride_x,
                       const void* dY, size_t stride_dy, float* G, float* db, int accumulate, void* stream);

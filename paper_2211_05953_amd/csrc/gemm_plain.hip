@@ -129,7 +129,8 @@ bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, h
   if (a.colsum && layout != L_TN) { set_error("gemm: column sums go with the weight-gradient layout"); return BF_EINVAL; }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   bf_status s;
-  if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
+  const bool seg_ok = a.n_seg <= 1 || ((a.seg_stride_a | a.seg_stride_b) & 7) == 0;  // 16-byte aligned segments
+  if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && seg_ok && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
     s = gemm_check(layout, epi, a);
     if (s == BF_OK) s = gemm_mfma(layout, epi, a, st);
   } else {

@@ -157,7 +157,7 @@ def test_gemm_mfma_large_tile(M, N, K):
 @pytest.mark.parametrize("mode,dtype,kernels", [("fp32", bf.BF_FP32, bf.BF_KERNELS_AUTO), ("bf16", bf.BF_BF16, bf.BF_KERNELS_PLAIN),
                                                 ("bf16", bf.BF_BF16, bf.BF_KERNELS_AUTO)])
 @pytest.mark.parametrize("M,N,K,n_seg,gap", [(256, 512, 128, 3, 0), (1024, 768, 128, 2, 64), (128, 384, 64, 2, 8), (512, 256, 192, 4, 0),
-                                             (768, 128, 64, 1, 0), (200, 136, 72, 3, 16)])
+                                             (768, 128, 64, 1, 0), (200, 136, 72, 3, 16), (256, 256, 64, 2, 4)])
 def test_wgrad_over_the_micro_batches_of_a_stage(mode, dtype, kernels, M, N, K, n_seg, gap):
     """G = sum_i X_i^T dY_i and db = sum_i colsum(dY_i) in one call (Sec. 4.2: the gradient of a stage
     is needed only after all its micro-batches); segments lie `gap` elements apart beyond their size."""
