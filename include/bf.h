@@ -127,7 +127,7 @@ typedef struct {
   double flops_executed;    /* what the kernels ran: causal half, in-kernel recompute, checkpoint recompute */
   int64_t peak_ckpt_count;  /* Eq. mem_ckpt first factor as executed */
   int64_t peak_ckpt_bytes;  /* peak_ckpt_count x bytes of one [S_mb, S_seq, S_hidden] tensor */
-  int64_t peak_act_bytes;   /* peak bytes of live stored activations (checkpoints included) */
+  int64_t peak_act_bytes;   /* peak bytes of live stored activations (checkpoints and fused_wgrad_bytes included) */
   int64_t state_bytes;      /* weights, Adam moments, main-grads, low-precision weights */
   int32_t n_events;
   int32_t timed;            /* 1 if gpu_ms / adam_ms are valid (bf_run_step ... timing != 0) */
@@ -147,6 +147,10 @@ typedef struct {
   int64_t n_reconstruct;
   int64_t reconstruct_bytes;
   int64_t weight_buffer_bytes;
+  /* fuse_wgrad = 1 in breadth-first order (else 0): bytes of the per-micro-batch gradients (with
+   * BF_CKPT_LAYER also the recomputed operands) of one stage that are kept until the stage's
+   * weight-gradient products have run; part of peak_act_bytes. */
+  int64_t fused_wgrad_bytes;
 } bf_step_report;
 
 typedef struct {

@@ -143,7 +143,54 @@ def batch_overhead(B, B_crit):
     return Fraction(B) / Fraction(B_crit)
 
 
-def cost_time(beta, N_gpu, B_crit):
-    """Eq. time_cost_tradeoff: (cost, time) up to a common factor, at a fixed batch size per GPU beta."""
-    cost = 1 + Fraction(beta) * N_gpu / Fraction(B_crit)
+def cost_time(beta, N_gpu, B_crit, efficiency=1):
+    """Eq. time_cost_tradeoff: (cost, time) up to a common factor, at a fixed batch size per GPU beta
+    (cost is proportional to the samples processed, Eq. critical_batch, over the utilisation)."""
+    cost = (1 + Fraction(beta) * N_gpu / Fraction(B_crit)) / Fraction(efficiency)
     return cost, cost / N_gpu
+
+
+# ------------------------------------------------------------------ efficiency model (Fig. 2)
+def dp_network(kind, N_mb, N_PP=1, sharded=False):
+    """Table 4.1, column "DP network": volume per GPU in units of the model size.  A reduction plus a
+    reconstruction is 2; fully sharded it is 3 (Sec. 3.1: at least 50 % more), repeated for every
+    micro-batch without looping, for every sequence of N_PP micro-batches depth-first (Sec. 4.2), and
+    not repeated breadth-first.  A pipeline rank holds 1 / N_PP of the model.  (The table prints the
+    sharded 1F1B entry without the 1 / N_PP; it is taken with it, like every other pipeline row.)"""
+    if not sharded:
+        return Fraction(2, N_PP)
+    reps = {"plain": N_mb, "GPIPE": N_mb, "1F1B": N_mb, "DF": Fraction(N_mb, N_PP), "BF": 1}[kind]
+    return Fraction(3, N_PP) * reps
+
+
+def efficiency(kind, N_mb, S_mb, beta_net, N_PP=1, N_loop=1, N_TP=1, N_layers=None, sharded=False, overlap=True):
+    """Theoretical efficiency behind Fig. 2, from the paper's own proportionalities.
+
+    Footnote to Eq. ddp_efficiency: with plain data parallelism T_net / T_comp = beta_net / (N_mb S_mb).
+    Other methods scale the network volume by Table 4.1's "DP network" column relative to its plain
+    entry and the computation by 1 / N_PP.  Eq. efficiency: an overlapped operation costs what exceeds
+    the computation it can hide under (Table 4.1, "DP overlap"; a repeated sharded operation hides under
+    its own micro-batches each time, so under the whole pass in total); a non-overlapped one costs
+    all of T_net.  The bubble of Eq. bubble / Eq. bubble_looped adds idle time.  Pipeline-parallel
+    transfers are left out (the paper calls them mostly negligible and gives no figure).
+    Returns dict(beta, bubble, net_ratio, overlap_share, net_overhead, efficiency) of Fractions."""
+    beta_net = Fraction(beta_net)
+    n_stage_for_tail = N_layers if N_layers else None
+    t_comp = Fraction(N_mb * S_mb, N_PP)
+    t_net = dp_network(kind, N_mb, N_PP, sharded) / dp_network("plain", 1) * beta_net
+    net_ratio = t_net / t_comp
+    if not overlap:
+        share = Fraction(0)
+    else:
+        tail = 1 - Fraction(N_PP, n_stage_for_tail) if n_stage_for_tail else Fraction(1)
+        if sharded:
+            share = tail
+        elif n_stage_for_tail:
+            share = dp_overlap(kind, N_mb, n_stage_for_tail, N_PP)
+        else:
+            share = {"plain": Fraction(1, N_mb), "GPIPE": Fraction(1, N_mb), "1F1B": Fraction(1, N_mb),
+                     "DF": Fraction(N_PP, N_mb), "BF": Fraction(1)}[kind]
+    over = max(Fraction(0), net_ratio - share)
+    b = bubble(N_PP, N_mb, N_loop)
+    return dict(beta=Fraction(N_mb * S_mb, N_PP * N_TP), bubble=b, net_ratio=net_ratio, overlap_share=share,
+                net_overhead=over, efficiency=1 / (1 + b + over))

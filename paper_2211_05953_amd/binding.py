@@ -6,8 +6,6 @@ import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbf.so")
-if os.environ.get("BF_LIBRARY"):   # another build of the same library (A/B timing of kernel variants)
-    LIB_PATH = os.environ["BF_LIBRARY"]
 
 BF_OK, BF_EINVAL, BF_ENOMEM, BF_ESTATE, BF_EDEVICE = 0, -1, -2, -3, -4
 BF_SCHED_BF, BF_SCHED_DF = 0, 1
@@ -39,11 +37,24 @@ class bf_step_report(C.Structure):
                [("n_events", C.c_int32), ("timed", C.c_int32)] + \
                [("kernel_ms", C.c_double * 11), ("kernel_flops", C.c_double * 11), ("kernel_bytes", C.c_double * 11),
                 ("kernel_launches", C.c_int64 * 11)] + \
-               [(n, C.c_int64) for n in ("n_weight_intervals", "n_reconstruct", "reconstruct_bytes", "weight_buffer_bytes")]
+               [(n, C.c_int64) for n in ("n_weight_intervals", "n_reconstruct", "reconstruct_bytes", "weight_buffer_bytes",
+                                         "fused_wgrad_bytes")]
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam",
                   "reconstruct", "vocab")
+
+
+BF_METHOD_NO_PIPELINE, BF_METHOD_NON_LOOPED, BF_METHOD_DEPTH_FIRST, BF_METHOD_BREADTH_FIRST = range(4)
+
+
+class bf_calc_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("method", "N_PP", "N_loop", "N_TP", "N_layers", "N_mb", "S_mb", "sharded",
+                                         "overlap")] + [("beta_net", C.c_double)]
+
+
+class bf_calc_point(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("beta", "bubble", "net_ratio", "overlap_share", "net_overhead", "efficiency")]
 
 
 class bf_sched_stats(C.Structure):
@@ -72,6 +83,11 @@ _SIGNATURES = {
     "bf_schedule_trace": (C.c_int, [C.c_int] * 7 + [C.POINTER(bf_event), C.c_size_t, C.POINTER(C.c_size_t),
                                                     C.POINTER(bf_sched_stats)]),
     "bf_param_count": (C.c_int64, [C.POINTER(bf_config)]),
+    "bf_calc_efficiency": (C.c_int, [C.POINTER(bf_calc_config), C.POINTER(bf_calc_point)]),
+    "bf_calc_efficiency_curve": (C.c_int, [C.POINTER(bf_calc_config), C.POINTER(C.c_int32), C.c_size_t,
+                                           C.POINTER(bf_calc_point)]),
+    "bf_calc_beta_threshold": (C.c_int, [C.POINTER(bf_calc_config), C.POINTER(C.c_double)]),
+    "bf_calc_cost_time": (C.c_int, [C.c_double] * 4 + [C.POINTER(C.c_double)] * 2),
     "bf_last_error": (C.c_char_p, []),
     "bf_op_gemm": (C.c_int, [C.c_int] * 7 + [_P] * 6 + [C.c_int, _P]),
     "bf_op_gemm_uses_mfma": (C.c_int, [C.c_int] * 5),
@@ -244,6 +260,39 @@ def bf_schedule_trace(schedule, N_PP, N_loop, N_mb, rank, t_fwd=1, t_bwd=2):
     st = bf_sched_stats()
     check(lib.bf_schedule_trace(schedule, N_PP, N_loop, N_mb, rank, t_fwd, t_bwd, buf, n.value, C.byref(n), C.byref(st)))
     return [(e.op, e.stage, e.mb, e.live_ckpt) for e in buf[:n.value]], st
+
+
+# ---- analytical calculators (include/bf_calc.h); host arithmetic only ------------------------
+def _point(p):
+    return {n: getattr(p, n) for n, _ in bf_calc_point._fields_}
+
+
+def bf_calc_efficiency(method, N_PP, N_loop, N_TP, N_layers, N_mb, S_mb, sharded, overlap, beta_net):
+    cfg = bf_calc_config(method, N_PP, N_loop, N_TP, N_layers, N_mb, S_mb, sharded, overlap, beta_net)
+    out = bf_calc_point()
+    check(load().bf_calc_efficiency(C.byref(cfg), C.byref(out)))
+    return _point(out)
+
+
+def bf_calc_efficiency_curve(method, N_PP, N_loop, N_TP, N_layers, S_mb, sharded, overlap, beta_net, n_mb):
+    cfg = bf_calc_config(method, N_PP, N_loop, N_TP, N_layers, 1, S_mb, sharded, overlap, beta_net)
+    counts = (C.c_int32 * len(n_mb))(*n_mb)
+    out = (bf_calc_point * max(1, len(n_mb)))()
+    check(load().bf_calc_efficiency_curve(C.byref(cfg), counts, len(n_mb), out))
+    return [_point(p) for p in out[:len(n_mb)]]
+
+
+def bf_calc_beta_threshold(method, N_PP, N_loop, N_TP, N_layers, N_mb, S_mb, sharded, overlap, beta_net):
+    cfg = bf_calc_config(method, N_PP, N_loop, N_TP, N_layers, N_mb, S_mb, sharded, overlap, beta_net)
+    out = C.c_double(0.0)
+    check(load().bf_calc_beta_threshold(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def bf_calc_cost_time(beta, N_gpu, B_crit, efficiency=1.0):
+    cost, time = C.c_double(0.0), C.c_double(0.0)
+    check(load().bf_calc_cost_time(beta, N_gpu, B_crit, efficiency, C.byref(cost), C.byref(time)))
+    return cost.value, time.value
 
 
 # ---- single kernels (include/bf_ops.h); tensors are torch CUDA tensors ----------------------

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbf.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["stack.hip", "schedule.cpp", "ops_api.hip", "elementwise.hip", "gemm_plain.hip", "gemm_mfma.hip",
+SOURCES = ["stack.hip", "schedule.cpp", "calc.cpp", "ops_api.hip", "elementwise.hip", "gemm_plain.hip", "gemm_mfma.hip",
            "attention_plain.hip", "attention_mfma.hip", "vocab.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -16,10 +16,8 @@
 // row (l / 16) * 4 + r, column l % 16.  The 16 x 16 x 32 form is used because the step runs at the
 // socket power limit: in a register-only loop on random operands it sustains 2.00 PFLOP/s where
 // the 32 x 32 x 16 form sustains 1.81 (both reach 2.48 on zeros).
+#include <atomic>
 #include <type_traits>
-
-#include <stdlib.h>
-#include <string.h>
 
 #include "common.h"
 #include "epilogue.h"
@@ -473,11 +471,16 @@ bf_status launch(const GemmArgs& a, hipStream_t st) {
   }
   auto kern = gemm_mfma_kernel<TL, AK, BKC, EPI, TO, SEG_POW2>;
   constexpr size_t lds = lds_bytes<TL, AK, BKC>();
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
+  // The LDS reservation is a per-device attribute of the kernel: one bit per device and instantiation,
+  // set after the call has succeeded (two threads racing here both make the call, which is harmless).
+  static std::atomic<uint64_t> attr_set{0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { set_error("gemm_mfma: no current device"); return BF_EDEVICE; }
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev >= 64 || !(attr_set.load(std::memory_order_acquire) & bit)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) { set_error("gemm_mfma: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e)); return BF_EDEVICE; }
-    attr_set = true;
+    if (dev < 64) attr_set.fetch_or(bit, std::memory_order_release);
   }
   const int tiles_m = a.M / TL::BM, tiles_n = a.N / TL::BN;
   const int remap = (tiles_m * tiles_n) % 8 == 0 ? 1 : 0;
@@ -521,10 +524,6 @@ inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
 // beat 768 of 256 x 128, 128 large tiles lose to 256 of them).
 // 0: 256 x 256 (one per compute unit), 1: 256 x 128 (one), 2: 128 x 128 (two).
 inline int choose_tile(int M, int N) {
-  static const int forced = [] {
-    const char* e = getenv("BF_GEMM_TILE");  // tuning override: "big", "mid", "small"
-    return !e ? -1 : !strcmp(e, "big") ? 0 : !strcmp(e, "mid") ? 1 : !strcmp(e, "small") ? 2 : -1;
-  }();
   const int bm[3] = {256, 256, 128}, bn[3] = {256, 128, 128};
   const long slots[3] = {256, 256, 512};
   const double rate[3] = {1.0, TILE_RATE_MID, TILE_RATE_SMALL / 2};
@@ -532,7 +531,6 @@ inline int choose_tile(int M, int N) {
   double best_t = 0;
   for (int i = 0; i < 3; ++i) {
     if (M % bm[i] || N % bn[i]) continue;
-    if (i == forced) return i;
     const long tiles = (long)(M / bm[i]) * (N / bn[i]), full = tiles / slots[i], rest = tiles % slots[i];
     const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / slots[i] : 0.0);
     const double t = rounds * bm[i] * bn[i] / rate[i];

@@ -1036,12 +1036,20 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     report->flops_executed = exec * lm_ + 3.0 * head;
     report->peak_ckpt_count = peak_live;
     report->peak_ckpt_bytes = peak_live * (int64_t)mb_bytes;
-    RecSizes rs = rec_sizes(c);
-    (void)rs;
     const double frac = (double)S_mb / c.S_mb_max;
     const int64_t rec_live = (int64_t)((double)(s->Lo.rec_bytes) * frac) + (int64_t)mb_bytes;
     report->peak_act_bytes = c.ckpt_mode == BF_CKPT_NONE ? peak_live * rec_live
                                                          : peak_live * (int64_t)mb_bytes + (int64_t)((double)s->Lo.rec_bytes * frac);
+    // The fused weight gradient keeps, per layer of the stage and micro-batch, the gradients {dy, du, dx1, dqkv}
+    // (with checkpointing also the recomputed operands {a, ctx, c, g}) until the stage's products have run.  The
+    // last stage's set is complete while every stored activation of the step is still alive, so it adds to the peak.
+    int64_t kept = 0;
+    if (fuse) {
+      kept = (int64_t)per_stage * N_mb * (int64_t)((double)s->Lo.grec_bytes * frac);
+      if (c.ckpt_mode == BF_CKPT_LAYER) kept += (int64_t)per_stage * N_mb * (int64_t)((double)s->Lo.wrec_bytes * frac);
+    }
+    report->fused_wgrad_bytes = kept;
+    report->peak_act_bytes += kept;
     report->state_bytes = (int64_t)s->Lo.P_total * (c.dtype == BF_BF16 && !c.dp_fs ? 18 : 16) +
                           (c.dp_fs ? 2 * (int64_t)s->Lo.half_bytes : 0);
     report->n_weight_intervals = (int64_t)ivs.size();

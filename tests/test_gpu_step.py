@@ -9,7 +9,7 @@ import bf_inputs
 import paper_2211_05953_amd as bf
 from oracle import formulas as F
 from oracle import stack as K
-from util import TOL, rel_err, to_dev, to_host
+from util import TOL, TOL_RMS, rel_err, rms_err, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -46,12 +46,16 @@ def _oracle(params, x, dy, schedule, N_loop, N_heads, causal=True, adam=None, st
 
 
 def _compare(gpu, ref, tol, N_layers):
+    tol_rms = TOL_RMS["fp32" if tol == TOL["fp32"] else "bf16"]
     assert rel_err(gpu["y"], ref["y"]) <= tol
     assert rel_err(gpu["dx"], ref["dx"]) <= tol
+    assert rms_err(gpu["dx"], ref["dx"]) <= tol_rms
     for l in range(N_layers):
         for name in bf.TENSOR_IDS:
             e = rel_err(gpu["grads"][l][name], ref["grads"][l][name].reshape(-1))
             assert e <= tol, (l, name, e)
+            e = rms_err(gpu["grads"][l][name], ref["grads"][l][name].reshape(-1))
+            assert e <= tol_rms, (l, name, "rms", e)
 
 
 CASES = [
@@ -600,3 +604,31 @@ def test_bounded_launch_queue_changes_nothing_but_the_host_pace(depth):
             for name in bf.TENSOR_IDS:
                 assert np.array_equal(a0["grads"][l][name], a1["grads"][l][name]), (l, name)
                 assert np.array_equal(a0["params"][l][name], a1["params"][l][name]), (l, name)
+
+
+@pytest.mark.parametrize("ckpt", [bf.BF_CKPT_NONE, bf.BF_CKPT_LAYER])
+def test_activation_bytes_count_what_the_fused_weight_gradient_keeps(ckpt):
+    """peak_act_bytes from the sizes of the stored tensors (bf16, S_mlp = 4 S_hidden: 32 S_hidden T bytes per layer
+    and micro-batch without checkpointing, the input alone with, App. A.2.1 / A.2.2 less the dropout masks and the
+    attention scores), plus what fuse_wgrad keeps per layer of a stage and micro-batch until the stage completes:
+    the gradients dy, du, dx1, dqkv (18 S_hidden T bytes) and, with checkpointing, the recomputed a, ctx, c, g (14)."""
+    Lyr, N_loop, h, a, S_seq, S_mb, N_mb = 4, 2, 256, 2, 128, 2, 3
+    f, T, per_stage = 4 * h, S_mb * S_seq, Lyr // N_loop
+    x, dy = bf_inputs.make_batch(3, N_mb, S_mb, S_seq, h, bf16=True)
+    dX, dDY = to_dev(x, True), to_dev(dy, True)
+    stats = 2 * (T * 2 * 4) + S_mb * a * S_seq * 4            # LayerNorm statistics twice, log-sum-exp
+    record = 30 * h * T + stats                               # a, qkv, ctx, x1, c, u, g
+    for fuse in (0, 1):
+        st = bf.Stack(bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, ckpt_mode=ckpt, fuse_wgrad=fuse, N_loop_min=N_loop))
+        for sched in (bf.BF_SCHED_BF, bf.BF_SCHED_DF):
+            rep = st.bf_run_step(sched, N_loop, N_mb, S_mb, dX, dDY)
+            torch.cuda.synchronize()
+            live = rep.peak_ckpt_count
+            assert live == (Lyr * N_mb if sched == bf.BF_SCHED_BF else Lyr)
+            kept = 0
+            if fuse and sched == bf.BF_SCHED_BF:
+                kept = per_stage * N_mb * (18 + (14 if ckpt == bf.BF_CKPT_LAYER else 0)) * h * T
+            assert rep.fused_wgrad_bytes == kept
+            stored = live * (record + 2 * h * T) if ckpt == bf.BF_CKPT_NONE else live * 2 * h * T + record
+            assert rep.peak_act_bytes == stored + kept, (fuse, sched, rep.peak_act_bytes, stored, kept)
+        st.close()

@@ -17,7 +17,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     lib = bf.load()
     declared = set()
-    for hdr in ("bf.h", "bf_ops.h"):
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert {"bf.h", "bf_ops.h", "bf_calc.h"} <= set(headers)
+    for hdr in headers:
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         declared |= set(re.findall(r"\b(bf_[a-z_0-9]+)\s*\(", text))

@@ -109,3 +109,84 @@ def test_data_parallel_efficiency_requirements():
     for n in range(1, 9):
         assert F.dp_efficient("BF", n, 1, 2048, ib) == (F.intensity_dp(n, 1, 2048) >= ib)
         assert F.dp_efficient("BF", n, 1, 2048, ib, sharded=True) == (F.intensity_fs("BF", n, 1, 2048) >= ib)
+
+
+def test_batch_size_overhead_and_cost_worked_examples():
+    """Eq. critical_batch / Eq. time_cost_tradeoff against the overheads the paper prints: GPT-3's batch of
+    3 M tokens at a critical batch size of 10 M (Sec. 3.5), and a batch of 1024 at the critical batch
+    sizes of the two evaluated models (Sec. 5.4).  cost - 1 of Eq. time_cost_tradeoff at beta N_gpu = B is
+    that same overhead, however B is split into beta and N_gpu; time is cost / N_gpu."""
+    for name in ("gpt3", "52b", "6.6b"):
+        e = G["batch_overhead"][name]
+        assert round(float(F.batch_overhead(e["B"], e["B_crit"])) * 100) == e["percent"], name
+        for n_gpu in (64, 512, 4096):
+            cost, time = F.cost_time(Fraction(e["B"], n_gpu), n_gpu, e["B_crit"])
+            assert round(float(cost - 1) * 100) == e["percent"]
+            assert time * n_gpu == cost
+    # at a fixed batch size per GPU more GPUs cost more and finish sooner; a lower utilisation costs in proportion
+    c1, t1 = F.cost_time(1, 1000, 10_000)
+    c2, t2 = F.cost_time(1, 4000, 10_000)
+    assert c2 > c1 and t2 < t1
+    assert F.cost_time(1, 1000, 10_000, Fraction(1, 2))[0] == 2 * c1
+
+
+def _eff(kind, N_mb, S_mb, beta_net, **kw):
+    return F.efficiency(kind, N_mb, S_mb, beta_net, **kw)
+
+
+def test_efficiency_model_thresholds_are_the_papers_conditions():
+    """The network overhead of the overlapped model vanishes exactly where the paper's efficiency conditions
+    hold: beta >= N_mb beta_net / (N_PP N_TP) without looping (Eq. ddp_efficiency, Eq. pipeline_efficiency_3d),
+    beta >= beta_net / (N_PP N_TP) breadth-first (Eq. pipeline_efficiency_bf), N_PP micro-batches' worth
+    depth-first (Sec. 4.2); fully sharded the bar is 3/2 higher (Sec. 3.1) and, except breadth-first, no longer
+    helped by more micro-batches."""
+    bn = G["efficiency_thresholds"]["beta_net_example"]
+    fs = Fraction(*G["efficiency_thresholds"]["sharded_factor"])
+    for N_PP, N_TP in [(1, 1), (4, 1), (4, 2), (8, 8)]:
+        for N_mb in (N_PP, 2 * N_PP, 8 * N_PP):
+            for S_mb in range(1, 13):
+                beta = Fraction(N_mb * S_mb, N_PP * N_TP)
+                kinds = ["plain"] if N_PP == 1 else ["GPIPE", "DF", "BF"]
+                for kind in kinds:
+                    e = _eff(kind, N_mb, S_mb, bn, N_PP=N_PP, N_TP=N_TP, N_loop=1 if kind in ("plain", "GPIPE") else 2)
+                    assert e["beta"] == beta
+                    bar = {"plain": N_mb * bn, "GPIPE": N_mb * bn, "DF": Fraction(N_mb, N_PP) * bn, "BF": bn}[kind]
+                    assert (e["net_overhead"] == 0) == (beta >= Fraction(bar, N_PP * N_TP)), (kind, N_PP, N_mb, S_mb)
+                    assert e["efficiency"] == 1 / (1 + e["bubble"] + e["net_overhead"])
+                    s = _eff(kind, N_mb, S_mb, bn, N_PP=N_PP, N_TP=N_TP, sharded=True)
+                    bar_s = {"plain": N_mb, "GPIPE": N_mb, "DF": Fraction(N_mb, N_PP), "BF": 1}[kind] * fs * bn
+                    assert (s["net_overhead"] == 0) == (beta >= Fraction(bar_s, N_PP * N_TP)), (kind, "sharded")
+    # lower bound on N_PP for efficient breadth-first training at beta_min = 1 / N_TP (Sec. 4.2): N_PP >= beta_net / beta_min
+    for N_TP in (1, 2):
+        for N_PP in range(1, 12):
+            e = _eff("BF", N_PP, 1, bn, N_PP=N_PP, N_TP=N_TP, N_loop=4)     # N_mb = N_PP, S_mb = 1: beta = beta_min
+            assert e["beta"] == Fraction(1, N_TP)
+            assert (e["net_overhead"] == 0) == (N_PP >= bn)
+
+
+def test_efficiency_model_limits_and_ordering():
+    """Fig. 2, qualitatively: at equal batch size per GPU breadth-first >= depth-first >= non-looped once looped;
+    without overlap the network time is paid in full (Eq. efficiency, second branch) and decays as 1 / beta;
+    the bubble is Eq. bubble_looped; with the share of Table 4.1's overlap column the last stage's part is lost."""
+    bn = G["efficiency_thresholds"]["beta_net_fig2"]
+    N_PP = 4
+    for N_mb in (4, 8, 16, 64):
+        g = _eff("GPIPE", N_mb, 1, bn, N_PP=N_PP)
+        d = _eff("DF", N_mb, 1, bn, N_PP=N_PP, N_loop=4)
+        b = _eff("BF", N_mb, 1, bn, N_PP=N_PP, N_loop=4)
+        assert b["efficiency"] >= d["efficiency"] >= g["efficiency"]
+        assert b["bubble"] == d["bubble"] == F.bubble(N_PP, N_mb, 4) and g["bubble"] == F.bubble(N_PP, N_mb)
+        # beta = N_mb / 4 < beta_net / N_PP = 1.5 only for N_mb = 4: breadth-first hides the reduction from N_mb = 6 on
+        assert (b["net_overhead"] == 0) == (N_mb >= bn)
+        for kind, e in (("GPIPE", g), ("DF", d), ("BF", b)):
+            n = _eff(kind, N_mb, 1, bn, N_PP=N_PP, N_loop=1 if kind == "GPIPE" else 4, overlap=False)
+            assert n["net_overhead"] == n["net_ratio"] == Fraction(bn, N_mb) and n["efficiency"] <= e["efficiency"]
+    # Table 4.1, column "DP overlap", with a finite number of layers
+    e = _eff("BF", 8, 1, 16, N_PP=4, N_loop=2, N_layers=16)
+    assert e["overlap_share"] == F.dp_overlap("BF", 8, 16, 4) == Fraction(3, 4)
+    assert e["net_overhead"] == Fraction(16, 8) - Fraction(3, 4)
+    e = _eff("DF", 8, 1, 16, N_PP=4, N_loop=2, N_layers=16)
+    assert e["overlap_share"] == Fraction(3, 4) * Fraction(4, 8)
+    # network volume column: 2 / N_PP, fully sharded 3 / N_PP times the repetitions
+    assert F.dp_network("BF", 8, 4) == Fraction(2, 4) and F.dp_network("BF", 8, 4, sharded=True) == Fraction(3, 4)
+    assert F.dp_network("DF", 8, 4, sharded=True) == Fraction(3, 4) * 2 and F.dp_network("plain", 8, 1, sharded=True) == 24

@@ -171,13 +171,3 @@ def test_gradient_reduction_overlap_matches_the_method_table():
             rest = sum(1 for e in full[first_opt:] if e[0] == K.OP_B)
             assert Fraction(rest, N_loop * N_mb) == F.dp_overlap(kind, N_mb, N_loop, 1)
         assert F.dp_overlap("DF", N_mb, N_loop, 1) == F.dp_overlap("plain", N_mb, N_loop, 1)
-
-
-def test_batch_size_overhead_worked_example():
-    """Sec. 3.5: a 3 M-token batch against a 10 M-token critical batch size costs about 30 % more samples;
-    Eq. time_cost_tradeoff: at fixed batch per GPU more GPUs cost more but finish sooner."""
-    assert F.batch_overhead(3_000_000, 10_000_000) == Fraction(3, 10)
-    c1, t1 = F.cost_time(1, 1000, 10_000)
-    c2, t2 = F.cost_time(1, 4000, 10_000)
-    assert c2 > c1 and t2 < t1
-    assert c1 == Fraction(11, 10) and t2 == Fraction(14, 10) / 4000
