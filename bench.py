@@ -8,6 +8,10 @@ S_mlp 32768, S_seq 2048, N_mb 16, bf16 with fp32 main-grads), seeded synthetic i
 resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline]
+
+Protocol of the committed figures (App. E: 50 batches, the first 10 dropped): --warmup 10 --steps 40, which
+are the defaults.  `value` is flops / wall-clock mean over the timed steps between device synchronisations;
+the median and the minimum of the per-step device times (HIP events around each step) stand beside it.
 """
 import argparse
 import json
@@ -65,30 +69,36 @@ def time_steps(st, bf, schedule, N_loop, N_mb, S_mb, x, dy, y, dx, steps, warmup
 
 
 def cpu_baseline(w, causal=True):
-    """The CPU oracle, as it stands, on one layer and one micro-batch of the same workload
-    (forward + backward), timed on the host cores."""
+    """The CPU oracle, as it stands, timed on the host cores on a reduced shape of the same workload: the same
+    S_hidden / N_heads / S_seq / S_mb (so the same products), 2 layers as 2 stages, one micro-batch, forward +
+    backward in breadth-first order.  The rate is flops of the sample / its time; what the whole step would take
+    at that rate is an extrapolation by the exact flop ratio, and labelled so."""
     import numpy as np
 
     import bf_inputs
     from oracle import formulas as F
     from oracle import stack as K
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, _ = w
-    params = bf_inputs.make_params(1, 1, h, f, bf16=dtype == "bf16")
-    p64 = [{k: v.astype(np.float64) for k, v in params[0].items()}]
+    lyr_s, loop_s, mb_s = min(2, Lyr), min(2, Lyr), 1
+    params = bf_inputs.make_params(1, lyr_s, h, f, bf16=dtype == "bf16")
+    p64 = [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
     del params
-    x, dy = bf_inputs.make_batch(1, 1, S_mb, S_seq, h, bf16=dtype == "bf16")
+    x, dy = bf_inputs.make_batch(1, mb_s, S_mb, S_seq, h, bf16=dtype == "bf16")
     t0 = time.perf_counter()
-    K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), K.SCHED_BF, 1, a, causal=causal)
+    K.run_step(p64, x.astype(np.float64), dy.astype(np.float64), K.SCHED_BF, loop_s, a, causal=causal)
     dt = time.perf_counter() - t0
-    flops = 3.0 * float(F.fwd_flops_layer_mb(h, S_seq, S_mb)) if f == 4 * h else None
+    per_layer_mb = 3.0 * float(F.fwd_flops_layer_mb(h, S_seq, S_mb)) if f == 4 * h else None
+    flops = per_layer_mb * lyr_s * mb_s
+    ratio = (Lyr * N_mb) / float(lyr_s * mb_s)
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
     return {"value": flops / dt / 1e12, "unit": "model TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": "1 layer x 1 micro-batch of %d (same S_hidden/S_seq/S_mb), forward+backward, %.1f s; "
-                      "fp64 numpy" % (Lyr * N_mb, dt)}
+            "sample": "%d layers as %d stages x %d micro-batch of the workload's %d x %d (same S_hidden / N_heads / S_seq / "
+                      "S_mb), forward+backward, %.1f s; fp64 numpy" % (lyr_s, loop_s, mb_s, Lyr, N_mb, dt),
+            "extrapolated": True, "flop_ratio_step_to_sample": ratio, "extrapolated_step_s": dt * ratio}
 
 
 def power_check(bf, h):
@@ -114,6 +124,48 @@ def power_check(bf, h):
         torch.cuda.synchronize()
         out[name + "_tflops"] = 2.0 * M * N * Kd * 20 / (e0.elapsed_time(e1) * 1e9)
         del A, B
+    return out
+
+
+def step_stats(reports):
+    """Median, minimum and maximum of the per-step device times (events around each step on its stream)."""
+    ms = sorted(rp.gpu_ms for rp in reports if rp.timed)
+    if not ms:
+        return None
+    n = len(ms)
+    return {"median": 0.5 * (ms[(n - 1) // 2] + ms[n // 2]), "min": ms[0], "max": ms[-1], "n": n}
+
+
+def other_workload(bf, name, steps=3, warmup=1):
+    """One of the other configurations, BF and DF, a few timed steps after one warm-up: model and executed
+    TFLOP/s, step time, peak checkpoints and activation bytes.  The stack is built and freed here."""
+    import torch
+    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, ckpt = WORKLOADS[name]
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16,
+                         ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
+                         fuse_wgrad=1, N_loop_min=N_loop, **EXTRA.get(name, {}))
+    st = bf.Stack(cfg, device="cuda:0")
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x221105953)
+    shape = (N_mb, S_mb, S_seq, h)
+    x = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    dy = torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    out = {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]), "N_layers": Lyr, "N_loop": N_loop, "S_hidden": h, "S_mb": S_mb,
+           "N_mb": N_mb, "ckpt": ckpt, "steps": steps, "warmup": warmup, "workspace_bytes": int(bf.bf_workspace_bytes(cfg))}
+    for tag, sched in (("bf", bf.BF_SCHED_BF), ("df", bf.BF_SCHED_DF)):
+        sec, reps = time_steps(st, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, steps, warmup, 1)
+        rp = reps[-1]
+        out[tag] = {"ms_per_step": sec * 1e3, "gpu_ms": step_stats(reps), "model_tflops": rp.flops_model / sec / 1e12,
+                    "frac_bf16_mfma_peak": rp.flops_model / sec / 1e12 / PEAK_BF16_TFLOPS,
+                    "executed_tflops": rp.flops_executed / sec / 1e12,
+                    "executed_frac_bf16_mfma_peak": rp.flops_executed / sec / 1e12 / PEAK_BF16_TFLOPS,
+                    "tokens_per_s": N_mb * S_mb * S_seq / sec,
+                    "peak_ckpt_count": rp.peak_ckpt_count, "peak_ckpt_bytes": rp.peak_ckpt_bytes,
+                    "peak_act_bytes": rp.peak_act_bytes, "fused_wgrad_bytes": rp.fused_wgrad_bytes}
+    st.close()
+    del st, x, dy, y, dx
+    torch.cuda.empty_cache()
     return out
 
 
@@ -158,8 +210,8 @@ def sweep(bf, w, extra, which):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-df", action="store_true")
@@ -171,9 +223,8 @@ def main():
                     help="skip the product timed on random and on zero operands reported under \"power_check\"")
     ap.add_argument("--sweep", choices=["N_mb", "N_loop"],
                     help="instead of the benchmark line: both orders over the micro-batch count or the loop count")
-    ap.add_argument("--pmc-calibration", action="store_true",
-                    help="first run a 1 GiB device copy (known HBM traffic) so that FETCH_SIZE / WRITE_SIZE "
-                         "readings of a rocprofv3 --pmc run of this command can be scaled")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the c2 / c4 / c5 steps (BF and DF) reported under \"other_workloads\" of the default workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one pipeline rank's share of the step); "
@@ -200,14 +251,15 @@ def main():
                           "unit": "model TFLOP/s", "data": "synthetic",
                           "points": sweep(bf, w, EXTRA.get(args.workload, {}), args.sweep)}))
         return
-    if args.pmc_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written per copy
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
+    # A 1 GiB device copy of known traffic (1 GiB read, 1 GiB written) opens every run: a rocprofv3 --pmc
+    # collection of this command scales its FETCH_SIZE / WRITE_SIZE readings by what they read for it.
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+    torch.cuda.empty_cache()
     st = bf.Stack(cfg, device="cuda:0")
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x221105953)
@@ -232,9 +284,12 @@ def main():
     r = rep_bf[-1]
     out_df = None
     if not args.no_df:
-        sec_df, rep_df = time_steps(st, bf, bf.BF_SCHED_DF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, 1, 1)
+        # the other order under the same protocol, at a quarter of the steps (its time is not the headline)
+        k_df, w_df = max(3, args.steps // 4), max(1, args.warmup // 4)
+        sec_df, rep_df = time_steps(st, bf, bf.BF_SCHED_DF, N_loop, N_mb, S_mb, x, dy, y, dx, k_df, w_df, 1)
         rd = rep_df[-1]
-        out_df = {"ms_per_step": sec_df * 1e3, "model_tflops": rd.flops_model / sec_df / 1e12,
+        out_df = {"ms_per_step": sec_df * 1e3, "steps": k_df, "warmup": w_df, "gpu_ms": step_stats(rep_df),
+                  "model_tflops": rd.flops_model / sec_df / 1e12,
                   "peak_ckpt_count": rd.peak_ckpt_count, "peak_ckpt_bytes": rd.peak_ckpt_bytes,
                   "peak_act_bytes": rd.peak_act_bytes}
     # one plain-timed BF step (no per-launch events at all), and two fully instrumented ones (events around
@@ -263,17 +318,27 @@ def main():
                 "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
                 "flops_per_launch": kern[dom]["tflops"] * 1e9 * kern[dom]["avg_launch_ms"],
                 "avg_launch_ms": kern[dom]["avg_launch_ms"]}
+    # HBM-side bytes per launch of that kernel.  `traffic` is not measured in this run: it is read from
+    # profiles/traffic.json, which holds what two rocprofv3 --pmc collections (FETCH_SIZE, WRITE_SIZE, scaled by
+    # the opening copy's readings) gave for this command.  The algorithmic bytes (every operand read once,
+    # the result written once) stand beside it.
+    roofline["traffic_algorithmic"] = sum(rp.kernel_bytes[bf.binding.KERNEL_CLASSES.index(dom)] for rp in rep_bf) / \
+        max(1, sum(rp.kernel_launches[bf.binding.KERNEL_CLASSES.index(dom)] for rp in rep_bf))
+    roofline["traffic_source"] = None
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         t = json.load(open(traffic_file)).get(args.workload, {}).get(dom)
         if t:
             roofline["traffic"] = t
+            roofline["traffic_source"] = "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, " \
+                                         "a committed constant, not measured in this run)"
 
     value = r.flops_model / sec_bf / 1e12
     line = {
         "metric": "model TFLOP/s per training step at S_mb=1, BF order (3x forward flops, full attention)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": sec_bf * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": sec_bf * 1e3, "gpu_ms": step_stats(rep_bf),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "N_layers": Lyr, "N_loop": N_loop,
                    "S_hidden": h, "N_heads": a, "S_mlp": f, "S_seq": S_seq, "S_mb": S_mb, "N_mb": N_mb,
@@ -283,7 +348,8 @@ def main():
         "executed_tflops": r.flops_executed / sec_bf / 1e12,
         "tokens_per_s": N_mb * S_mb * S_seq / sec_bf,
         "bf": {"peak_ckpt_count": r.peak_ckpt_count, "peak_ckpt_bytes": r.peak_ckpt_bytes,
-               "peak_act_bytes": r.peak_act_bytes, "state_bytes": r.state_bytes, "adam_ms": r.adam_ms,
+               "peak_act_bytes": r.peak_act_bytes, "fused_wgrad_bytes": r.fused_wgrad_bytes,
+               "state_bytes": r.state_bytes, "adam_ms": r.adam_ms,
                "ms_per_step_without_launch_events": sec_plain * 1e3,
                "ms_per_step_with_events_on_every_launch": sec_instr * 1e3},
         "df": out_df,
@@ -317,6 +383,8 @@ def main():
         del fs
     del x, dy, y, dx
     torch.cuda.empty_cache()
+    if args.workload == "c3" and not args.no_other_workloads:
+        line["other_workloads"] = {name: other_workload(bf, name) for name in ("c2", "c4", "c5")}
     if b16 and not args.no_power_check and h % 256 == 0:
         line["power_check"] = power_check(bf, h)
     if not args.no_cpu_baseline:

@@ -41,6 +41,15 @@ typedef enum { BF_EPI_NONE = 0, BF_EPI_BIAS = 1, BF_EPI_BIAS_RES = 2, BF_EPI_BIA
 bf_status bf_op_gemm(int dtype, int kernels, int layout, int epilogue, int M, int N, int K,
                      const void* A, const void* B, void* C, const float* bias, const void* R, void* C2,
                      int accumulate, void* stream);
+/* The dgrad product in front of a GeLU with the bias gradient of the linear layer below it (App. A.1: the first
+ * linear layer of the MLP) taken on the way:
+ *   C[M,N] = (A[M,K] Bt[N,K]^T) * gelu_tanh'(R[M,N])            (BF_NT with BF_EPI_GELU_BWD)
+ *   db[N]  = (accumulate ? db : 0) + sum_m C[m,:]                of the stored (rounded) C
+ * part: device fp32 scratch of ceil(M / 128) * N elements, owned by the caller: with it the MFMA kernel takes the
+ * sums in its epilogue (one row of partial sums per row of tiles, added up in a fixed order by a small kernel);
+ * NULL, or a problem that goes to the plain kernel: a second pass over C takes them.  db: device fp32 [N]. */
+bf_status bf_op_gemm_gelu_bwd_colsum(int dtype, int kernels, int M, int N, int K, const void* A, const void* Bt, void* C,
+                                     const void* R, float* db, float* part, int accumulate, void* stream);
 /* 1 if the MFMA kernel takes this problem in bf16 mode, 0 if the plain kernel would run. */
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
 

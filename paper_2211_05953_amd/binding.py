@@ -90,6 +90,7 @@ _SIGNATURES = {
     "bf_calc_cost_time": (C.c_int, [C.c_double] * 4 + [C.POINTER(C.c_double)] * 2),
     "bf_last_error": (C.c_char_p, []),
     "bf_op_gemm": (C.c_int, [C.c_int] * 7 + [_P] * 6 + [C.c_int, _P]),
+    "bf_op_gemm_gelu_bwd_colsum": (C.c_int, [C.c_int] * 5 + [_P] * 6 + [C.c_int, _P]),
     "bf_op_gemm_uses_mfma": (C.c_int, [C.c_int] * 5),
     "bf_op_wgrad": (C.c_int, [C.c_int] * 6 + [_P, C.c_size_t, _P, C.c_size_t, _P, _P, C.c_int, _P]),
     "bf_op_layernorm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
@@ -304,6 +305,11 @@ def bf_op_gemm(dtype, kernels, layout, epilogue, M, N, K, A, B, Cout, bias=None,
 def bf_op_wgrad(dtype, kernels, M, N, K, n_seg, X, stride_x, dY, stride_dy, G, db=None, accumulate=0):
     check(load().bf_op_wgrad(dtype, kernels, M, N, K, n_seg, _ptr(X), stride_x, _ptr(dY), stride_dy, _ptr(G), _ptr(db),
                              accumulate, _stream()))
+
+
+def bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, A, Bt, Cout, R, db, part=None, accumulate=0):
+    check(load().bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, _ptr(A), _ptr(Bt), _ptr(Cout), _ptr(R), _ptr(db),
+                                            _ptr(part), accumulate, _stream()))
 
 
 def bf_op_gemm_uses_mfma(layout, epilogue, M, N, K):

@@ -44,6 +44,13 @@ struct GemmArgs {
   // segments (the bias gradient that goes with the weight gradient) are written to colsum[N], fp32,
   // overwritten or added to as `accumulate` says.
   float* colsum = nullptr;
+  // Other layouts, epilogue E_GELU_BWD: colsum[N] receives the column sums of the stored output C (the bias
+  // gradient of the layer whose pre-activation gradient C is).  With colsum_part, fp32 scratch of
+  // ceil(M / 128) * N elements, the MFMA kernel takes them in its epilogue, one row of partial sums per row of
+  // tiles, and a small kernel adds the rows up in a fixed order; without it (or on the plain kernel) a second
+  // pass over C does.  colsum_rows: set by the MFMA launcher to the rows of partial sums written.
+  float* colsum_part = nullptr;
+  int* colsum_rows = nullptr;
 };
 
 void set_error(const char* fmt, ...);
@@ -72,6 +79,8 @@ bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, 
                         const float* stats, const void* dres, void* dx, float* dg, float* db,
                         int accumulate, hipStream_t st);
 bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, hipStream_t st);
+// out[n] = (accumulate ? out[n] : 0) + sum_{r < rows} part[r * N + n], rows added in ascending order
+bf_status colsum_finish(const float* part, int rows, int N, float* out, int accumulate, hipStream_t st);
 
 bf_status attention_fwd_plain(int dtype, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                               const void* qkv, void* ctx, float* lse, hipStream_t st);

@@ -508,6 +508,22 @@ bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumu
   return BF_OK;
 }
 
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ part, int rows, int N, float* __restrict__ out,
+                                                            int accumulate) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float t = accumulate ? out[n] : 0.f;
+  for (int r = 0; r < rows; ++r) t += part[(size_t)r * N + n];
+  out[n] = t;
+}
+
+bf_status colsum_finish(const float* part, int rows, int N, float* out, int accumulate, hipStream_t st) {
+  if (!part || !out || rows < 1 || N < 1) { set_error("colsum_finish: bad argument"); return BF_EINVAL; }
+  colsum_finish_kernel<<<(N + 255) / 256, 256, 0, st>>>(part, rows, N, out, accumulate);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
 __global__ void bump_step_kernel(int* t) { *t += 1; }
 
 bf_status bump_step(int* t_dev, hipStream_t st) {

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
                                                            const bf16_t* __restrict__ B, TO* __restrict__ C,
                                                            const float* __restrict__ bias, const TO* __restrict__ R,
                                                            TO* __restrict__ C2, int accumulate, int tiles_m, int remap,
-                                                           int n_seg, size_t seg_a, size_t seg_b) {
+                                                           int n_seg, size_t seg_a, size_t seg_b, float* __restrict__ colpart) {
   constexpr int BM = TL::BM, BN = TL::BN, NT = TL::NT, MI = TL::MI, NI = TL::NI;
   constexpr int A_ST = stage_elems<AK, BM>(), B_ST = stage_elems<BKC, BN>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -405,6 +405,10 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
     constexpr int LDC = BN + 4;
     float* cs = reinterpret_cast<float*>(smem_raw);
     static_assert((size_t)PR * LDC * 4 <= 2 * (size_t)STAGE * sizeof(bf16_t), "epilogue staging does not fit");
+    // E_GELU_BWD with colpart: the column sums of this tile's (rounded) outputs, i.e. the tile's share of the bias
+    // gradient of the linear layer whose pre-activation gradient is being written; a thread keeps the sums of
+    // its 8 columns over its rows, the threads of a column group meet in LDS after the last pass
+    float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int p = 0; p < BM / PR; ++p) {
 #pragma unroll
@@ -438,7 +442,10 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         } else if constexpr (EPI == E_GELU_BWD) {
           const bf16x8 rr = rpre[p][q];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = (__bf16)(v[e] * gelu_grad_f((float)rr[e]));
+          for (int e = 0; e < 8; ++e) {
+            o[e] = (__bf16)(v[e] * gelu_grad_f((float)rr[e]));
+            csum[e] += (float)o[e];
+          }
         } else {
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
@@ -452,6 +459,24 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
         }
       }
       __syncthreads();
+    }
+    if constexpr (EPI == E_GELU_BWD) {
+      if (colpart) {
+        // thread tid owns column group tid % (BN / 8) in every pass (NT is a multiple of BN / 8) and the rows
+        // tid / (BN / 8) + k * RG: RG partial sums per column, added in ascending order
+        constexpr int CGN = BN / 8, RG = NT / CGN;
+        static_assert(NT % CGN == 0 && (size_t)RG * BN * 4 <= 2 * (size_t)STAGE * sizeof(bf16_t), "column-sum staging does not fit");
+        const int g = tid % CGN, rg = tid / CGN;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cs[rg * BN + g * 8 + e] = csum[e];
+        __syncthreads();
+        for (int c = tid; c < BN; c += NT) {
+          float t = 0.f;
+#pragma unroll 8
+          for (int r = 0; r < RG; ++r) t += cs[r * BN + c];
+          colpart[(size_t)bm * N + n0 + c] = t;
+        }
+      }
     }
   }
 }
@@ -486,7 +511,8 @@ bf_status launch(const GemmArgs& a, hipStream_t st) {
   const int remap = (tiles_m * tiles_n) % 8 == 0 ? 1 : 0;
   kern<<<tiles_m * tiles_n, TL::NT, lds, st>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.B, (TO*)a.C, a.bias,
                                                 (const TO*)a.R, (TO*)a.C2, a.accumulate, tiles_m, remap, a.n_seg > 1 ? a.n_seg : 1,
-                                                a.seg_stride_a, a.seg_stride_b);
+                                                a.seg_stride_a, a.seg_stride_b, EPI == E_GELU_BWD ? a.colsum_part : nullptr);
+  if (EPI == E_GELU_BWD && a.colsum_rows) *a.colsum_rows = tiles_m;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("gemm_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;

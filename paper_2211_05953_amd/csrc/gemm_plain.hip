@@ -126,17 +126,33 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 }
 
 bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st) {
-  if (a.colsum && layout != L_TN) { set_error("gemm: column sums go with the weight-gradient layout"); return BF_EINVAL; }
+  if (a.colsum && layout != L_TN && epi != E_GELU_BWD) {
+    set_error("gemm: column sums go with the weight-gradient layout or the GeLU-backward epilogue");
+    return BF_EINVAL;
+  }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   bf_status s;
   const bool seg_ok = a.n_seg <= 1 || ((a.seg_stride_a | a.seg_stride_b) & 7) == 0;  // 16-byte aligned segments
   if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && (al & 15) == 0 && seg_ok && gemm_mfma_supported(layout, epi, a.M, a.N, a.K)) {
     s = gemm_check(layout, epi, a);
-    if (s == BF_OK) s = gemm_mfma(layout, epi, a, st);
+    if (s != BF_OK) return s;
+    if (layout != L_TN && a.colsum && a.colsum_part) {
+      // the epilogue leaves one row of partial column sums per row of tiles; add them up
+      int rows = 0;
+      GemmArgs b = a;
+      b.colsum_rows = &rows;
+      s = gemm_mfma(layout, epi, b, st);
+      if (s != BF_OK) return s;
+      return colsum_finish(a.colsum_part, rows, a.N, a.colsum, a.accumulate, st);
+    }
+    GemmArgs b = a;
+    b.colsum_part = nullptr;
+    s = gemm_mfma(layout, epi, b, st);
   } else {
     s = gemm_plain(dtype, layout, epi, a, st);
   }
   if (s != BF_OK || !a.colsum) return s;
+  if (layout != L_TN) return colsum(dtype, a.M, a.N, a.C, a.colsum, a.accumulate, st);  // second pass over the stored output
   // The bias gradient beside the weight gradient: one pass of the column-reduction kernel per
   // segment.  (Taking the sums inside the MFMA product, as ones^T B on a few workgroups, was
   // measured: those workgroups run 10 % longer and end up as the stragglers of their rounds, which

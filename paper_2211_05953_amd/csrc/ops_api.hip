@@ -33,6 +33,16 @@ bf_status bf_op_wgrad(int dtype, int kernels, int M, int N, int K, int n_seg, co
   return gemm(dtype, kernels, L_TN, E_ACCUM, a, (hipStream_t)stream);
 }
 
+bf_status bf_op_gemm_gelu_bwd_colsum(int dtype, int kernels, int M, int N, int K, const void* A, const void* Bt, void* C,
+                                     const void* R, float* db, float* part, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (!db) { set_error("bf_op_gemm_gelu_bwd_colsum: db is null"); return BF_EINVAL; }
+  GemmArgs a{M, N, K, A, Bt, C, nullptr, R, nullptr, accumulate};
+  a.colsum = db;
+  a.colsum_part = part;
+  return gemm(dtype, kernels, L_NT, E_GELU_BWD, a, (hipStream_t)stream);
+}
+
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K) {
   return gemm_mfma_supported(layout, epilogue, M, N, K) ? 1 : 0;
 }

@@ -140,7 +140,7 @@ RecSizes rec_sizes(const bf_config& c) {
   return r;
 }
 
-struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, total; };
+struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, total; };
 
 TmpSizes tmp_sizes(const bf_config& c) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
@@ -148,7 +148,9 @@ TmpSizes tmp_sizes(const bf_config& c) {
   TmpSizes t;
   t.du = up(T * f * es); t.dc = up(T * h * es); t.dx1 = up(T * h * es); t.dctx = up(T * h * es);
   t.dqkv = up(T * 3 * h * es); t.delta = up((size_t)c.S_mb_max * c.N_heads * c.S_seq * 4); t.ping = up(T * h * es);
-  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping;
+  // partial column sums that a product's epilogue leaves per row of (at least 128-row) tiles: [T / 128][f] fp32
+  t.colpart = up(((T + 127) / 128) * f * 4);
+  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart;
   return t;
 }
 
@@ -309,7 +311,7 @@ Record record_for(bf_stack* s, int layer, int mb) {
   return R;
 }
 
-struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float* delta; };
+struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart; };
 
 // Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
 struct GradRec { char *dy, *du, *dx1, *dqkv; };
@@ -336,7 +338,7 @@ Tmp tmp_of(bf_stack* s) {
   Tmp T;
   char* p = s->ws + s->Lo.off_tmp;
   T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
-  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p;
+  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p;
   return T;
 }
 
@@ -451,14 +453,17 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
     BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
   }
   BF_TRY(p_colsum(s, T, h, dy, G(BF_B_FC2), acc, st));
-  g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), du, nullptr, R.u, nullptr, 0};
+  // du = (dy W_fc2^T) gelu'(u), and on the way the bias gradient of FC1, the column sums of du: taken in the
+  // product's epilogue (per-tile partial sums, then a small fixed-order reduction) instead of a second pass over du
+  g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), du, nullptr, R.u, nullptr, acc};
+  g.colsum = G(BF_B_FC1);
+  g.colsum_part = t.colpart;
   BF_TRY(p_gemm(s, L_NT, E_GELU_BWD, g, st));
   // u = c W_fc1 + b_fc1
   if (!keep) {
     g = GemmArgs{h, f, T, R.c, du, G(BF_W_FC1), nullptr, nullptr, nullptr, acc};
     BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
   }
-  BF_TRY(p_colsum(s, T, f, du, G(BF_B_FC1), acc, st));
   g = GemmArgs{T, h, f, du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // c = LN2(x1); dx1 = dy + LN2'(dc)

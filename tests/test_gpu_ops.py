@@ -61,6 +61,38 @@ def test_gemm_all_layouts_and_epilogues(mode, dtype, kernels, M, N, K):
 
 
 @pytest.mark.parametrize("mode,dtype", MODES)
+@pytest.mark.parametrize("kernels", [bf.BF_KERNELS_PLAIN, bf.BF_KERNELS_AUTO])
+@pytest.mark.parametrize("M,N,K", [(128, 768, 256), (200, 136, 72), (512, 512, 128), (1280, 384, 192), (2048, 256, 512)])
+def test_gelu_backward_product_with_the_bias_gradient_on_the_way(mode, dtype, kernels, M, N, K):
+    """dU = (dY W^T) gelu'(U) and db = column sums of dU: in the MFMA kernel's epilogue (per-tile partial sums in a
+    scratch buffer, then a fixed-order reduction), or as a second pass when there is no scratch or the plain kernel
+    runs; overwriting and accumulating.  Shapes cover the 128-, 256 x 128- and 256 x 256-tile forms, several tile
+    rows, and a ragged one."""
+    b16 = dtype == bf.BF_BF16
+    A = bf_inputs.normal(4, 0, (M, K), bf16=b16)
+    Bt = bf_inputs.normal(4, 1, (N, K), 0.05, bf16=b16)
+    R = bf_inputs.normal(4, 3, (M, N), bf16=b16)
+    ref = (A.astype(np.float64) @ Bt.astype(np.float64).T) * L.gelu_grad(R.astype(np.float64))
+    dA, dBt, dR = to_dev(A, b16), to_dev(Bt, b16), to_dev(R, b16)
+    for with_part in (True, False):
+        out = torch.empty(M, N, dtype=_dt(b16), device="cuda")
+        db = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        part = torch.full(((M + 127) // 128, N), float("nan"), dtype=torch.float32, device="cuda") if with_part else None
+        bf.bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, dA, dBt, out, dR, db, part, accumulate=0)
+        assert rel_err(to_host(out), ref) <= TOL[mode]
+        assert rel_err(to_host(db), ref.sum(axis=0)) <= TOL[mode]
+        # the sums are those of the stored output, up to fp32 summation order
+        assert rel_err(to_host(db), to_host(out).astype(np.float64).sum(axis=0)) <= 1e-5
+        first = to_host(db).copy()
+        bf.bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, dA, dBt, out, dR, db, part, accumulate=1)
+        assert rel_err(to_host(db), 2.0 * first.astype(np.float64)) <= 1e-6
+        # same launch, same bits
+        db2 = torch.empty_like(db)
+        bf.bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, dA, dBt, out, dR, db2, part, accumulate=0)
+        assert np.array_equal(to_host(db2), first)
+
+
+@pytest.mark.parametrize("mode,dtype", MODES)
 @pytest.mark.parametrize("T,h", [(128, 256), (77, 100), (512, 2048), (3, 8200)])
 def test_layernorm_fwd_bwd_and_colsum(mode, dtype, T, h):
     b16 = dtype == bf.BF_BF16
