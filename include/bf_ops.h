@@ -83,6 +83,17 @@ bf_status bf_op_attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N
 bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                               const void* qkv, const void* ctx, const float* lse, const void* dctx,
                               void* dqkv, float* delta, void* stream);
+/* bf_op_attention_bwd for callers that cannot allocate device memory and have no buffer to lend (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the same kernels, with `delta` in an
+ * array built into the library (BF_ATTENTION_BWD_STATIC_MAX floats = 4 MiB, which every GPU the library runs on
+ * holds until the process ends).  Allocates nothing and calls no allocating routine.  BF_EINVAL if
+ * S_mb * N_heads * S_seq exceeds the array.  All calls on one GPU share the array: calls that overlap on one GPU
+ * (different streams or threads) race; calls on one stream do not.  Nothing in the array has to be cleared
+ * between calls (each call writes every element it reads). */
+#define BF_ATTENTION_BWD_STATIC_MAX ((size_t)1 << 20)
+bf_status bf_op_attention_bwd_static(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                                     const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                                     void* dqkv, void* stream);
 int bf_op_attention_uses_mfma(int S_seq, int S_head);
 
 /* Input layer (App. A.1): x[t, :] = e_tok[tokens[t], :] + e_pos[t mod S_seq, :] for n_rows = S_mb * S_seq rows.

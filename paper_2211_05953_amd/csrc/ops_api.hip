@@ -1,4 +1,6 @@
 // C-ABI wrappers of the single kernels (include/bf_ops.h).
+#include <mutex>
+
 #include "../../include/bf_ops.h"
 #include "common.h"
 
@@ -9,6 +11,37 @@ static bool dtype_ok(int dtype, int kernels) {
   if (kernels != BF_KERNELS_AUTO && kernels != BF_KERNELS_PLAIN) { set_error("unknown kernels %d", kernels); return false; }
   return true;
 }
+
+// ---- attention backward without a caller-provided scratch buffer ---------------------------
+// The per-query term delta = rowsum(dctx * ctx), which the first backward kernel writes and the second
+// reads, lives in a file-scope device array instead of an argument.  Every device that loads the
+// library holds its own copy of the array at its own address: the address is looked up once per
+// device, with that device current, and kept; host code never uses the array's name otherwise.
+constexpr size_t STATIC_DELTA_FLOATS = BF_ATTENTION_BWD_STATIC_MAX;  // 4 MiB per device
+static __device__ __align__(256) float scratch[STATIC_DELTA_FLOATS];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[MAX_DEVICES] = {};
+
+bf_status static_delta(float** out) {
+  int dev = -1;
+  BF_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) { set_error("bf_op_attention_bwd_static: device %d outside 0..%d", dev, MAX_DEVICES - 1); return BF_EDEVICE; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    BF_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) { set_error("bf_op_attention_bwd_static: the scratch array has no address on device %d", dev); return BF_EDEVICE; }
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return BF_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -74,6 +107,25 @@ bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N
                               const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
                               float* delta, void* stream) {
   if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  return attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta,
+                       (hipStream_t)stream);
+}
+
+bf_status bf_op_attention_bwd_static(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                                                const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                                                void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (S_mb < 1 || S_seq < 1 || N_heads < 1) { set_error("bf_op_attention_bwd_static: sizes must be >= 1"); return BF_EINVAL; }
+  const size_t need = (size_t)S_mb * (size_t)N_heads * (size_t)S_seq;
+  if (need > STATIC_DELTA_FLOATS) {
+    set_error("bf_op_attention_bwd_static: S_mb * N_heads * S_seq = %zu exceeds the built-in scratch of %zu elements; "
+              "use bf_op_attention_bwd with a buffer of the caller's", need, STATIC_DELTA_FLOATS);
+    return BF_EINVAL;
+  }
+  float* delta = nullptr;
+  bf_status r = static_delta(&delta);
+  if (r != BF_OK) return r;
+  // every element the second kernel reads is written by the first in the same call: nothing has to start at zero
   return attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta,
                        (hipStream_t)stream);
 }
