@@ -71,6 +71,16 @@ bf_status bf_op_layernorm_fwd(int dtype, int T, int h, const void* x, const floa
 bf_status bf_op_layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g,
                               const float* stats, const void* dres, void* dx, float* dg, float* db,
                               int accumulate, void* stream);
+/* The same with everything a LayerNorm needs in the backward pass taken in one pass over dy and x:
+ * dx as above; dg, db as above; dcs[h] (fp32, may be NULL) = or += the column sums of the stored dx, which are the bias
+ * gradient of the linear layer that produced x (x = residual + linear output).
+ * part: device fp32 scratch of bf_op_layernorm_bwd_part_elems(T, h) elements, owned by the caller: with it (and h a
+ * multiple of the vector width, at most 4 x 256 vectors per row) a workgroup walks a run of rows with its column sums in
+ * registers and a second small kernel adds the workgroups' partial sums in a fixed order; NULL: separate passes. */
+bf_status bf_op_layernorm_bwd_fused(int dtype, int T, int h, const void* dy, const void* x, const float* g,
+                                    const float* stats, const void* dres, void* dx, float* dg, float* db, float* dcs,
+                                    float* part, int accumulate, void* stream);
+size_t bf_op_layernorm_bwd_part_elems(int T, int h);
 /* out[N] (fp32) = or += sum over rows of dY[T,N]: the bias gradient. */
 bf_status bf_op_colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, void* stream);
 

@@ -95,6 +95,8 @@ _SIGNATURES = {
     "bf_op_wgrad": (C.c_int, [C.c_int] * 6 + [_P, C.c_size_t, _P, C.c_size_t, _P, _P, C.c_int, _P]),
     "bf_op_layernorm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
     "bf_op_layernorm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int] + [_P] * 8 + [C.c_int, _P]),
+    "bf_op_layernorm_bwd_fused": (C.c_int, [C.c_int, C.c_int, C.c_int] + [_P] * 10 + [C.c_int, _P]),
+    "bf_op_layernorm_bwd_part_elems": (C.c_size_t, [C.c_int, C.c_int]),
     "bf_op_colsum": (C.c_int, [C.c_int, C.c_int, C.c_int, _P, _P, C.c_int, _P]),
     "bf_op_attention_fwd": (C.c_int, [C.c_int] * 7 + [_P] * 4),
     "bf_op_attention_bwd": (C.c_int, [C.c_int] * 7 + [_P] * 7),
@@ -324,6 +326,15 @@ def bf_op_layernorm_fwd(dtype, T, h, x, g, b, eps, y, stats):
 def bf_op_layernorm_bwd(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, accumulate=0):
     check(load().bf_op_layernorm_bwd(dtype, T, h, _ptr(dy), _ptr(x), _ptr(g), _ptr(stats), _ptr(dres), _ptr(dx),
                                      _ptr(dg), _ptr(db), accumulate, _stream()))
+
+
+def bf_op_layernorm_bwd_fused(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, dcs=None, part=None, accumulate=0):
+    check(load().bf_op_layernorm_bwd_fused(dtype, T, h, _ptr(dy), _ptr(x), _ptr(g), _ptr(stats), _ptr(dres), _ptr(dx),
+                                           _ptr(dg), _ptr(db), _ptr(dcs), _ptr(part), accumulate, _stream()))
+
+
+def bf_op_layernorm_bwd_part_elems(T, h):
+    return load().bf_op_layernorm_bwd_part_elems(T, h)
 
 
 def bf_op_colsum(dtype, T, N, dY, out, accumulate=0):

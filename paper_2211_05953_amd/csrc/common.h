@@ -75,9 +75,13 @@ bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, h
 bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps,
                         void* y, float* stats /*[T][2]: mean, rstd*/, hipStream_t st);
 // dx = LN'(dy) (+ dres if non-null);  dg/db (fp32) = or += column sums.
+// dcs (may be null): fp32 [h], = or += the column sums of the stored dx (the bias gradient of the linear layer
+// that produced x).  part (may be null): fp32 scratch of layernorm_bwd_part_elems(T, h) elements; with it, dx and
+// the three column reductions are taken in one pass over dy / x, without it in separate passes.
 bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g,
                         const float* stats, const void* dres, void* dx, float* dg, float* db,
-                        int accumulate, hipStream_t st);
+                        int accumulate, hipStream_t st, float* dcs = nullptr, float* part = nullptr);
+size_t layernorm_bwd_part_elems(int T, int h);
 bf_status colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, hipStream_t st);
 // out[n] = (accumulate ? out[n] : 0) + sum_{r < rows} part[r * N + n], rows added in ascending order
 bf_status colsum_finish(const float* part, int rows, int N, float* out, int accumulate, hipStream_t st);

@@ -244,6 +244,124 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_bwd_dx_reg_kernel(const T* __r
   }
 }
 
+// ------------------------------------------- LayerNorm backward, everything in one pass
+// dx as above, and the three column reductions that go with a LayerNorm in the backward pass
+// (dg = sum_t dy xhat, db = sum_t dy, and the column sums of the stored dx, which are the bias gradient
+// of the linear layer that produced the LayerNorm's input) without reading dy and x a second time:
+// a workgroup walks R consecutive rows, a thread keeps the three sums of its NIT * VEC columns in
+// registers and the workgroup leaves one row of partial sums in `part` ([P][3][h], P = workgroups);
+// ln_bwd_finish_kernel adds the P rows up in ascending order.  The next row's dy / x / dres are
+// requested before the current row's reductions, so the row-to-row chain does not expose HBM latency.
+// Sum over the workgroup of two values at once; `red` holds 8 floats.
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();  // protects `red` against the previous use
+  if ((threadIdx.x & 63) == 0) { red[w] = a; red[4 + w] = b; }
+  __syncthreads();
+  a = red[0] + red[1] + red[2] + red[3];
+  b = red[4] + red[5] + red[6] + red[7];
+}
+
+template <typename T, int VEC, int NIT>
+__global__ __launch_bounds__(ROW_THREADS) void ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                   const float* __restrict__ g, const float* __restrict__ stats,
+                                                                   const T* __restrict__ dres, T* __restrict__ dx,
+                                                                   float* __restrict__ part, int T_rows, int h, int R) {
+  __shared__ float red[8];
+  typedef Vec<T, VEC> V;
+  const int r0 = blockIdx.x * R, r1 = min(r0 + R, T_rows);
+  float gg[NIT][VEC], ag[NIT][VEC], ab[NIT][VEC], ac[NIT][VEC];
+  int col[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    col[it] = (it * ROW_THREADS + (int)threadIdx.x) * VEC;
+    if (col[it] < h) load_vec<float, VEC>(g + col[it], gg[it]);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) ag[it][j] = ab[it][j] = ac[it][j] = 0.f;
+  }
+  V ndy[NIT], nx[NIT], nres[NIT];  // the next row, as it comes from memory
+  auto fetch = [&](int row) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      if (col[it] < h) {
+        ndy[it] = *reinterpret_cast<const V*>(dy + (size_t)row * h + col[it]);
+        nx[it] = *reinterpret_cast<const V*>(x + (size_t)row * h + col[it]);
+        if (dres) nres[it] = *reinterpret_cast<const V*>(dres + (size_t)row * h + col[it]);
+      }
+  };
+  if (r0 < r1) fetch(r0);
+  for (int row = r0; row < r1; ++row) {
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float d[NIT][VEC], xh[NIT][VEC], rr[NIT][VEC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      if (col[it] < h) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          d[it][j] = (float)ndy[it].v[j];
+          xh[it][j] = ((float)nx[it].v[j] - mean) * rstd;
+          rr[it][j] = dres ? (float)nres[it].v[j] : 0.f;
+          const float dh = d[it][j] * gg[it][j];
+          s1 += dh;
+          s2 += dh * xh[it][j];
+        }
+      }
+    if (row + 1 < r1) fetch(row + 1);
+    block_sum2(s1, s2, red);
+    s1 /= (float)h;
+    s2 /= (float)h;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      if (col[it] < h) {
+        V o;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          o.v[j] = (T)(rstd * (d[it][j] * gg[it][j] - s1 - xh[it][j] * s2) + rr[it][j]);
+          ag[it][j] += d[it][j] * xh[it][j];
+          ab[it][j] += d[it][j];
+          ac[it][j] += (float)o.v[j];
+        }
+        *reinterpret_cast<V*>(dx + (size_t)row * h + col[it]) = o;
+      }
+  }
+  float* p = part + (size_t)blockIdx.x * 3 * h;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+    if (col[it] < h) {
+      store_vec<float, VEC>(p + col[it], ag[it]);
+      store_vec<float, VEC>(p + h + col[it], ab[it]);
+      store_vec<float, VEC>(p + 2 * (size_t)h + col[it], ac[it]);
+    }
+}
+
+// out_q[c] = (accumulate ? out_q[c] : 0) + sum_{b < P} part[b][q][c] for q = 0 (dg), 1 (db), 2 (dcs, may be null),
+// rows added in ascending order: 32 columns x 8 row groups per workgroup, the groups meet in LDS in order.
+__global__ __launch_bounds__(256) void ln_bwd_finish_kernel(const float* __restrict__ part, int P, int h, float* __restrict__ dg,
+                                                            float* __restrict__ db, float* __restrict__ dcs, int accumulate) {
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int c3 = blockIdx.x * 32 + cx;  // column of the [3 h] row of partial sums
+  const int per = (P + 7) / 8, b0 = ry * per, b1 = min(b0 + per, P);
+  float t = 0.f;
+  if (c3 < 3 * h)
+    for (int b = b0; b < b1; ++b) t += part[(size_t)b * 3 * h + c3];
+  red[ry][cx] = t;
+  __syncthreads();
+  if (ry == 0 && c3 < 3 * h) {
+    const int q = c3 / h, c = c3 - q * h;
+    float* out = q == 0 ? dg : q == 1 ? db : dcs;
+    if (out) {
+      float v = accumulate ? out[c] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v += red[r][cx];
+      out[c] = v;
+    }
+  }
+}
+
 // Compute units of the current device (256 on MI355X).
 inline int compute_units() {
   static const int n = [] {
@@ -480,10 +598,52 @@ static void launch_ln_bwd(int T_rows, int h, const void* dy, const void* x, cons
   launch_col_reduce<T, VEC, 1>(dy, x, stats, dg, db, T_rows, h, accumulate, st);
 }
 
+size_t layernorm_bwd_part_elems(int T, int h) {
+  const int R = (T + 255) / 256, P = (T + R - 1) / R;
+  return (size_t)P * 3 * (size_t)h;
+}
+
+template <typename T, int VEC>
+static bool launch_ln_bwd_fused(int T_rows, int h, const void* dy, const void* x, const float* g, const float* stats,
+                                const void* dres, void* dx, float* dg, float* db, float* dcs, float* part, int accumulate,
+                                hipStream_t st) {
+  const int nit = (h + ROW_THREADS * VEC - 1) / (ROW_THREADS * VEC);
+  if (nit > 4) return false;
+  // at most 256 workgroups (one per compute unit), each a run of consecutive rows
+  const int R = (T_rows + 255) / 256, P = (T_rows + R - 1) / R;
+#define BF_LN_FUSED(N) ln_bwd_fused_kernel<T, VEC, N><<<P, ROW_THREADS, 0, st>>>((const T*)dy, (const T*)x, g, stats, (const T*)dres, (T*)dx, part, T_rows, h, R)
+  switch (nit) {
+    case 1: BF_LN_FUSED(1); break;
+    case 2: BF_LN_FUSED(2); break;
+    case 3: BF_LN_FUSED(3); break;
+    default: BF_LN_FUSED(4); break;
+  }
+#undef BF_LN_FUSED
+  ln_bwd_finish_kernel<<<(3 * h + 31) / 32, 256, 0, st>>>(part, P, h, dg, db, dcs, accumulate);
+  return true;
+}
+
 bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, const float* g, const float* stats,
-                        const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st) {
+                        const void* dres, void* dx, float* dg, float* db, int accumulate, hipStream_t st, float* dcs,
+                        float* part) {
   if (T < 1 || h < 1 || !dy || !x || !g || !stats || !dx || !dg || !db) { set_error("layernorm_bwd: bad argument"); return BF_EINVAL; }
   const bool al = aligned16(dy) && aligned16(x) && aligned16(g) && aligned16(dx) && (!dres || aligned16(dres));
+  if (part && al && aligned16(part)) {
+    // one pass over dy / x with the column reductions on the way (rows of up to 4 x 256 vectors)
+    bool done = false;
+    if (dtype == BF_BF16 && h % 8 == 0) done = launch_ln_bwd_fused<bf16_t, 8>(T, h, dy, x, g, stats, dres, dx, dg, db, dcs, part, accumulate, st);
+    else if (dtype == BF_FP32 && h % 4 == 0) done = launch_ln_bwd_fused<float, 4>(T, h, dy, x, g, stats, dres, dx, dg, db, dcs, part, accumulate, st);
+    if (done) {
+      BF_LAUNCH_CHECK();
+      return BF_OK;
+    }
+  }
+  if (dcs) {
+    // no scratch or an odd shape: the input gradient first, then its column sums as a pass of their own
+    bf_status r = layernorm_bwd(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st, nullptr, nullptr);
+    if (r != BF_OK) return r;
+    return colsum(dtype, T, h, dx, dcs, accumulate, st);
+  }
   if (dtype == BF_BF16) {
     if (al && h % 8 == 0) launch_ln_bwd<bf16_t, 8>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);
     else launch_ln_bwd<bf16_t, 1>(T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, st);

@@ -92,6 +92,15 @@ bf_status bf_op_layernorm_bwd(int dtype, int T, int h, const void* dy, const voi
   return layernorm_bwd(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, (hipStream_t)stream);
 }
 
+bf_status bf_op_layernorm_bwd_fused(int dtype, int T, int h, const void* dy, const void* x, const float* g,
+                                    const float* stats, const void* dres, void* dx, float* dg, float* db, float* dcs,
+                                    float* part, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, 0)) return BF_EINVAL;
+  return layernorm_bwd(dtype, T, h, dy, x, g, stats, dres, dx, dg, db, accumulate, (hipStream_t)stream, dcs, part);
+}
+
+size_t bf_op_layernorm_bwd_part_elems(int T, int h) { return T > 0 && h > 0 ? layernorm_bwd_part_elems(T, h) : 0; }
+
 bf_status bf_op_colsum(int dtype, int T, int N, const void* dY, float* out, int accumulate, void* stream) {
   if (!dtype_ok(dtype, 0)) return BF_EINVAL;
   return colsum(dtype, T, N, dY, out, accumulate, (hipStream_t)stream);

@@ -140,7 +140,7 @@ RecSizes rec_sizes(const bf_config& c) {
   return r;
 }
 
-struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, total; };
+struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, total; };
 
 TmpSizes tmp_sizes(const bf_config& c) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
@@ -150,7 +150,9 @@ TmpSizes tmp_sizes(const bf_config& c) {
   t.dqkv = up(T * 3 * h * es); t.delta = up((size_t)c.S_mb_max * c.N_heads * c.S_seq * 4); t.ping = up(T * h * es);
   // partial column sums that a product's epilogue leaves per row of (at least 128-row) tiles: [T / 128][f] fp32
   t.colpart = up(((T + 127) / 128) * f * 4);
-  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart;
+  // partial column sums of the one-pass LayerNorm backward: one row of [3][h] per workgroup
+  t.lnpart = up(layernorm_bwd_part_elems((int)T, (int)h) * 4);
+  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart + t.lnpart;
   return t;
 }
 
@@ -311,7 +313,7 @@ Record record_for(bf_stack* s, int layer, int mb) {
   return R;
 }
 
-struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart; };
+struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart, *lnpart; };
 
 // Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
 struct GradRec { char *dy, *du, *dx1, *dqkv; };
@@ -338,7 +340,7 @@ Tmp tmp_of(bf_stack* s) {
   Tmp T;
   char* p = s->ws + s->Lo.off_tmp;
   T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
-  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p;
+  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p; p += t.colpart; T.lnpart = (float*)p;
   return T;
 }
 
@@ -381,11 +383,13 @@ bf_status p_ln_fwd(bf_stack* s, int T, int h, const void* x, const float* g, con
   const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
   return timed(s, BF_K_LN_FWD, 0.0, 2.0 * es * T * h, st, [&] { return layernorm_fwd(s->cfg.dtype, T, h, x, g, b, eps, y, stats, st); });
 }
+// dcs: null, or where the column sums of dx go (the bias gradient of the linear layer that produced x)
 bf_status p_ln_bwd(bf_stack* s, int T, int h, const void* dy, const void* x, const float* g, const float* stats, const void* dres,
-                   void* dx, float* dg, float* db, int acc, hipStream_t st) {
+                   void* dx, float* dg, float* db, float* dcs, int acc, hipStream_t st) {
   const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
-  return timed(s, BF_K_LN_BWD, 0.0, 4.0 * es * T * h, st,
-               [&] { return layernorm_bwd(s->cfg.dtype, T, h, dy, x, g, stats, dres, dx, dg, db, acc, st); });
+  return timed(s, BF_K_LN_BWD, 0.0, 4.0 * es * T * h, st, [&] {
+    return layernorm_bwd(s->cfg.dtype, T, h, dy, x, g, stats, dres, dx, dg, db, acc, st, dcs, tmp_of(s).lnpart);
+  });
 }
 bf_status p_colsum(bf_stack* s, int T, int N, const void* dY, float* out, int acc, hipStream_t st) {
   const double es = s->cfg.dtype == BF_BF16 ? 2 : 4;
@@ -436,8 +440,10 @@ bf_status layer_forward(bf_stack* s, int layer, int S_mb, const void* x, const R
 // acc: 0 for the first micro-batch of the step (main-grads are overwritten), 1 afterwards.
 // keep: null, or where du / dx1 / dqkv are kept for a later weight-gradient product over all the
 // micro-batches of the stage (then no weight-matrix gradient is taken here).
+// dy_summed: the column sums of dy (this layer's FC2 bias gradient) were taken by whoever produced dy.
+// below_b_fc2: null, or the FC2 bias gradient of the layer that dx feeds: its column sums are taken here, on the way.
 bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const Record& R, const void* dy, void* dx,
-                         int acc, const GradRec* keep, hipStream_t st) {
+                         int acc, const GradRec* keep, bool dy_summed, float* below_b_fc2, hipStream_t st) {
   const bf_config& c = s->cfg;
   const int T = S_mb * c.S_seq, h = c.S_hidden, f = c.S_mlp;
   Tmp t = tmp_of(s);
@@ -452,7 +458,7 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
     g = GemmArgs{f, h, T, R.g, dy, G(BF_W_FC2), nullptr, nullptr, nullptr, acc};
     BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
   }
-  BF_TRY(p_colsum(s, T, h, dy, G(BF_B_FC2), acc, st));
+  if (!dy_summed) BF_TRY(p_colsum(s, T, h, dy, G(BF_B_FC2), acc, st));
   // du = (dy W_fc2^T) gelu'(u), and on the way the bias gradient of FC1, the column sums of du: taken in the
   // product's epilogue (per-tile partial sums, then a small fixed-order reduction) instead of a second pass over du
   g = GemmArgs{T, f, h, dy, weight_ptr(s, layer, BF_W_FC2), du, nullptr, R.u, nullptr, acc};
@@ -466,14 +472,13 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
   }
   g = GemmArgs{T, h, f, du, weight_ptr(s, layer, BF_W_FC1), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
-  // c = LN2(x1); dx1 = dy + LN2'(dc)
-  BF_TRY(p_ln_bwd(s, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, dx1, G(BF_LN2_G), G(BF_LN2_B), acc, st));
+  // c = LN2(x1); dx1 = dy + LN2'(dc); the column sums of dx1 are the out-projection's bias gradient
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, R.x1, P(BF_LN2_G), R.ln2, dy, dx1, G(BF_LN2_G), G(BF_LN2_B), G(BF_B_O), acc, st));
   // x1 = x + ctx W_o + b_o
   if (!keep) {
     g = GemmArgs{h, h, T, R.ctx, dx1, G(BF_W_O), nullptr, nullptr, nullptr, acc};
     BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
   }
-  BF_TRY(p_colsum(s, T, h, dx1, G(BF_B_O), acc, st));
   g = GemmArgs{T, h, h, dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, dqkv, t.delta, st));
@@ -485,8 +490,9 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
   BF_TRY(p_colsum(s, T, 3 * h, dqkv, G(BF_B_QKV), acc, st));
   g = GemmArgs{T, h, 3 * h, dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
-  // a = LN1(x); dx = dx1 + LN1'(da)
-  BF_TRY(p_ln_bwd(s, T, h, t.dc, x, P(BF_LN1_G), R.ln1, dx1, dx, G(BF_LN1_G), G(BF_LN1_B), acc, st));
+  // a = LN1(x); dx = dx1 + LN1'(da); dx is the gradient arriving at the layer below, whose FC2 bias gradient is
+  // its column sums
+  BF_TRY(p_ln_bwd(s, T, h, t.dc, x, P(BF_LN1_G), R.ln1, dx1, dx, G(BF_LN1_G), G(BF_LN1_B), below_b_fc2, acc, st));
   return BF_OK;
 }
 
@@ -929,7 +935,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         g = GemmArgs{V, h, T_mb, logits, hn, gw, nullptr, nullptr, nullptr, m > 0};
         BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
         BF_TRY(p_ln_bwd(s, T_mb, h, dhn, y_top, param_ptr(s, s->w32, 0, BF_LNF_G), lnf_stats, nullptr, dy_lm(m),
-                        param_ptr(s, s->g32, 0, BF_LNF_G), param_ptr(s, s->g32, 0, BF_LNF_B), m > 0, st));
+                        param_ptr(s, s->g32, 0, BF_LNF_G), param_ptr(s, s->g32, 0, BF_LNF_B), nullptr, m > 0, st));
       }
     } else {
       for (int l = l1 - 1; l >= l0; --l) {
@@ -951,7 +957,11 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         else dout = fuse ? grad_rec(s, l - 1 - l0, m).dy : tmp.ping[l & 1];
         GradRec keep{};
         if (fuse) keep = grad_rec(s, l - l0, m);
-        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, st));
+        // A layer whose incoming gradient was written by the layer above on this rank (everything but the top of
+        // the chain, or of a stage when the stages do not feed each other) has had its FC2 bias gradient taken there.
+        const bool fed_from_above = !is_top(l);
+        float* below = is_bottom(l) ? nullptr : param_ptr(s, s->g32, l - 1, BF_B_FC2);
+        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, fed_from_above, below, st));
         --live;
       }
       if (lm && l0 == 0) {

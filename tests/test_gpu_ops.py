@@ -93,6 +93,54 @@ def test_gelu_backward_product_with_the_bias_gradient_on_the_way(mode, dtype, ke
 
 
 @pytest.mark.parametrize("mode,dtype", MODES)
+@pytest.mark.parametrize("T,h", [(128, 256), (77, 100), (300, 2048), (1024, 6144), (2048, 8192), (520, 1000), (3, 8200), (64, 16384)])
+def test_layernorm_backward_in_one_pass(mode, dtype, T, h):
+    """bf_op_layernorm_bwd_fused: dx, the gain / bias gradients and the column sums of dx from one pass over dy and x
+    (workgroups of consecutive rows with partial sums in a scratch buffer, then a fixed-order reduction), or in separate
+    passes when there is no scratch or the row does not fit; overwriting and accumulating; row counts that do not
+    divide into equal runs; widths with idle lanes (256), of 3 and 4 vectors per thread, and beyond the one-pass form."""
+    b16 = dtype == bf.BF_BF16
+    x = bf_inputs.normal(6, 0, (T, h), 2.0, bf16=b16) + np.float32(0.5)
+    if b16:
+        x = bf_inputs.round_bf16(x)
+    g = 1 + bf_inputs.normal(6, 1, (h,), 0.2)
+    dy = bf_inputs.normal(6, 3, (T, h), bf16=b16)
+    dres = bf_inputs.normal(6, 4, (T, h), bf16=b16)
+    eps = 1e-5
+    g64 = g.astype(np.float64)
+    _, saved = L.layernorm_fwd(x.astype(np.float64), g64, np.zeros(h), eps)
+    dx_ref, dg_ref, db_ref = L.layernorm_bwd(dy.astype(np.float64), g64, saved)
+    dx_ref = dx_ref + dres.astype(np.float64)
+    dX, dG, dDY, dRES = to_dev(x, b16), to_dev(g, False), to_dev(dy, b16), to_dev(dres, b16)
+    stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
+    bf.bf_op_layernorm_fwd(dtype, T, h, dX, dG, torch.zeros(h, device="cuda"), eps, torch.empty_like(dX), stats)
+    n_part = bf.bf_op_layernorm_bwd_part_elems(T, h)
+    assert n_part == 3 * h * -(-T // -(-T // 256)) and n_part <= 3 * h * 256
+    results = []
+    for with_part in (True, False):
+        part = torch.full((n_part,), float("nan"), dtype=torch.float32, device="cuda") if with_part else None
+        dx = torch.empty_like(dX)
+        dg, db, dcs = (torch.full((h,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3))
+        bf.bf_op_layernorm_bwd_fused(dtype, T, h, dDY, dX, dG, stats, dRES, dx, dg, db, dcs, part, accumulate=0)
+        assert rel_err(to_host(dx), dx_ref) <= TOL[mode]
+        assert rel_err(to_host(dg), dg_ref) <= TOL[mode] and rel_err(to_host(db), db_ref) <= TOL[mode]
+        assert rel_err(to_host(dcs), dx_ref.sum(axis=0)) <= TOL[mode]
+        assert rel_err(to_host(dcs), to_host(dx).astype(np.float64).sum(axis=0)) <= 1e-5   # sums of the stored dx
+        first = [to_host(t).copy() for t in (dg, db, dcs)]
+        bf.bf_op_layernorm_bwd_fused(dtype, T, h, dDY, dX, dG, stats, dRES, dx, dg, db, dcs, part, accumulate=1)
+        for t, f0 in zip((dg, db, dcs), first):
+            assert rel_err(to_host(t), 2.0 * f0.astype(np.float64)) <= 1e-6
+        # without the residual gradient and without the column sums of dx
+        dx2 = torch.empty_like(dX)
+        bf.bf_op_layernorm_bwd_fused(dtype, T, h, dDY, dX, dG, stats, None, dx2, dg, db, None, part, accumulate=0)
+        assert rel_err(to_host(dx2), dx_ref - dres.astype(np.float64)) <= TOL[mode]
+        assert np.array_equal(to_host(dg), first[0]) and np.array_equal(to_host(db), first[1])
+        results.append((to_host(dx), first))
+    # the two forms agree to the rounding of the output (their fused multiply-adds may associate differently)
+    assert rel_err(results[0][0], results[1][0].astype(np.float64)) <= (2.0 ** -8 if b16 else 1e-6)
+
+
+@pytest.mark.parametrize("mode,dtype", MODES)
 @pytest.mark.parametrize("T,h", [(128, 256), (77, 100), (512, 2048), (3, 8200)])
 def test_layernorm_fwd_bwd_and_colsum(mode, dtype, T, h):
     b16 = dtype == bf.BF_BF16
