@@ -208,8 +208,10 @@ struct NextSetOf<DEPTH, std::integral_constant<int, V>> { static constexpr int v
 // S = K Q^T loop (one 1 KB LDS fragment read per MFMA, Q from registers) reaches 44 % of the MFMA
 // rate; without P V 70 % of the full time remains, without the softmax arithmetic 84 %, without the
 // K/V refetch 86 %: no single part dominates, the per-tile chain read -> MFMA -> softmax -> MFMA is
-// what two wavefronts per SIMD cannot hide.  Fewer LDS bytes per MFMA would need 64 queries per
-// wavefront (accumulators in AGPRs, one wavefront per SIMD).
+// what two wavefronts per SIMD cannot hide.  Fewer LDS bytes per MFMA need 64 queries per wavefront
+// (accumulators in AGPRs, one wavefront per SIMD): built and measured level with this form (100 against
+// 98 us at 64 heads of 128, S_seq 2048): a lone wavefront issues in order, so each of its LDS, barrier
+// and softmax waits stops its MFMAs too, and there is no partner on the SIMD to fill the gap.
 template <int D, int ROWS>
 __global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
                                                                                  bf16_t* __restrict__ ctx, float* __restrict__ lse,

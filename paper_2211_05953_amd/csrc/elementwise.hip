@@ -338,26 +338,39 @@ __global__ __launch_bounds__(ROW_THREADS) void ln_bwd_fused_kernel(const T* __re
 }
 
 // out_q[c] = (accumulate ? out_q[c] : 0) + sum_{b < P} part[b][q][c] for q = 0 (dg), 1 (db), 2 (dcs, may be null),
-// rows added in ascending order: 32 columns x 8 row groups per workgroup, the groups meet in LDS in order.
+// rows added in ascending order: 16 threads x 4 columns (256 contiguous bytes of a partial row) by 16 row
+// groups per workgroup, the groups meet in LDS in order.  h is a multiple of 4, so a thread's four columns
+// belong to one output.
 __global__ __launch_bounds__(256) void ln_bwd_finish_kernel(const float* __restrict__ part, int P, int h, float* __restrict__ dg,
                                                             float* __restrict__ db, float* __restrict__ dcs, int accumulate) {
-  __shared__ float red[8][33];
-  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
-  const int c3 = blockIdx.x * 32 + cx;  // column of the [3 h] row of partial sums
-  const int per = (P + 7) / 8, b0 = ry * per, b1 = min(b0 + per, P);
-  float t = 0.f;
-  if (c3 < 3 * h)
-    for (int b = b0; b < b1; ++b) t += part[(size_t)b * 3 * h + c3];
-  red[ry][cx] = t;
+  __shared__ float red[16][16][4];
+  const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
+  const int c3 = (blockIdx.x * 16 + cx) * 4;  // first of the thread's columns of the [3 h] row of partial sums
+  const int per = (P + 15) / 16, b0 = ry * per, b1 = min(b0 + per, P);
+  float t[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c3 < 3 * h) {
+#pragma unroll 4
+    for (int b = b0; b < b1; ++b) {
+      float u[4];
+      load_vec<float, 4>(part + (size_t)b * 3 * h + c3, u);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t[j] += u[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[ry][cx][j] = t[j];
   __syncthreads();
   if (ry == 0 && c3 < 3 * h) {
     const int q = c3 / h, c = c3 - q * h;
     float* out = q == 0 ? dg : q == 1 ? db : dcs;
     if (out) {
-      float v = accumulate ? out[c] : 0.f;
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if (accumulate) load_vec<float, 4>(out + c, v);
 #pragma unroll
-      for (int r = 0; r < 8; ++r) v += red[r][cx];
-      out[c] = v;
+      for (int r = 0; r < 16; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] += red[r][cx][j];
+      store_vec<float, 4>(out + c, v);
     }
   }
 }
@@ -619,7 +632,7 @@ static bool launch_ln_bwd_fused(int T_rows, int h, const void* dy, const void* x
     default: BF_LN_FUSED(4); break;
   }
 #undef BF_LN_FUSED
-  ln_bwd_finish_kernel<<<(3 * h + 31) / 32, 256, 0, st>>>(part, P, h, dg, db, dcs, accumulate);
+  ln_bwd_finish_kernel<<<(3 * h + 63) / 64, 256, 0, st>>>(part, P, h, dg, db, dcs, accumulate);
   return true;
 }
 
@@ -628,7 +641,7 @@ bf_status layernorm_bwd(int dtype, int T, int h, const void* dy, const void* x, 
                         float* part) {
   if (T < 1 || h < 1 || !dy || !x || !g || !stats || !dx || !dg || !db) { set_error("layernorm_bwd: bad argument"); return BF_EINVAL; }
   const bool al = aligned16(dy) && aligned16(x) && aligned16(g) && aligned16(dx) && (!dres || aligned16(dres));
-  if (part && al && aligned16(part)) {
+  if (part && al && aligned16(part) && aligned16(dg) && aligned16(db) && (!dcs || aligned16(dcs))) {
     // one pass over dy / x with the column reductions on the way (rows of up to 4 x 256 vectors)
     bool done = false;
     if (dtype == BF_BF16 && h % 8 == 0) done = launch_ln_bwd_fused<bf16_t, 8>(T, h, dy, x, g, stats, dres, dx, dg, db, dcs, part, accumulate, st);
