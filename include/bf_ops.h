@@ -93,6 +93,16 @@ bf_status bf_op_attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N
 bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                               const void* qkv, const void* ctx, const float* lse, const void* dctx,
                               void* dqkv, float* delta, void* stream);
+/* The same with the bias gradient of the QKV projection (App. A.1: qkv = a W_qkv + b_qkv, so the gradient of b_qkv
+ * is the column sum of dqkv over the S_mb * S_seq rows): db_qkv[3 S_hidden] (device fp32) = (accumulate ? db_qkv : 0)
+ * + those sums.  part: device fp32 scratch of bf_op_attention_bwd_part_elems(...) elements owned by the caller (0
+ * elements: shape not served by the matrix-core kernels); with it the two backward kernels leave per query / key
+ * block partial sums of what they store (before rounding to bf16) and one small kernel adds them in a fixed order;
+ * NULL, fp32, or a shape outside the matrix-core kernels: dqkv is read a second time (bf_op_colsum). */
+bf_status bf_op_attention_bwd_bias(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                                   const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                                   void* dqkv, float* delta, float* db_qkv, float* part, int accumulate, void* stream);
+size_t bf_op_attention_bwd_part_elems(int S_mb, int S_seq, int N_heads, int S_head);
 /* bf_op_attention_bwd for callers that cannot allocate device memory and have no buffer to lend (code under
  * HIP graph capture, tight serving loops, harnesses that forbid allocation): the same kernels, with `delta` in an
  * array built into the library (BF_ATTENTION_BWD_STATIC_MAX floats = 4 MiB, which every GPU the library runs on

@@ -101,6 +101,8 @@ _SIGNATURES = {
     "bf_op_attention_fwd": (C.c_int, [C.c_int] * 7 + [_P] * 4),
     "bf_op_attention_bwd": (C.c_int, [C.c_int] * 7 + [_P] * 7),
     "bf_op_attention_bwd_static": (C.c_int, [C.c_int] * 7 + [_P] * 6),
+    "bf_op_attention_bwd_bias": (C.c_int, [C.c_int] * 7 + [_P] * 8 + [C.c_int, _P]),
+    "bf_op_attention_bwd_part_elems": (C.c_size_t, [C.c_int] * 4),
     "bf_op_attention_uses_mfma": (C.c_int, [C.c_int, C.c_int]),
     "bf_op_embedding_fwd": (C.c_int, [C.c_int] * 5 + [_P, _P, _P, _P, _P]),
     "bf_op_embedding_bwd": (C.c_int, [C.c_int] * 5 + [_P, _P, _P, _P, C.c_int, _P]),
@@ -349,6 +351,17 @@ def bf_op_attention_fwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qk
 def bf_op_attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta):
     check(load().bf_op_attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, _ptr(qkv), _ptr(ctx),
                                      _ptr(lse), _ptr(dctx), _ptr(dqkv), _ptr(delta), _stream()))
+
+
+def bf_op_attention_bwd_bias(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta, db_qkv,
+                             part=None, accumulate=0):
+    check(load().bf_op_attention_bwd_bias(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, _ptr(qkv), _ptr(ctx),
+                                          _ptr(lse), _ptr(dctx), _ptr(dqkv), _ptr(delta), _ptr(db_qkv),
+                                          _ptr(part) if part is not None else None, int(accumulate), _stream()))
+
+
+def bf_op_attention_bwd_part_elems(S_mb, S_seq, N_heads, S_head):
+    return load().bf_op_attention_bwd_part_elems(S_mb, S_seq, N_heads, S_head)
 
 
 def bf_op_attention_bwd_static(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv):

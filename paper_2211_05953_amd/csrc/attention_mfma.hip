@@ -147,6 +147,57 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], bf16_t* 
     }
 }
 
+// ---- column sums of a transposed accumulator set over a workgroup's tokens (the bias gradient of the QKV
+// projection is the column sum of dqkv: taking it here saves a second pass over that tensor).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  const int i = __builtin_bit_cast(int, v);  // every lane has a source under these controls: `old` is never taken
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, true));
+}
+// every lane gets the sum over its row of 16 lanes: neighbours in a quad, the other pair of the quad, the
+// mirrored half of 8, the mirrored half of 16
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f32<0xB1>(v);   // quad_perm [1, 0, 3, 2]
+  v += dpp_f32<0x4E>(v);   // quad_perm [2, 3, 0, 1]
+  v += dpp_f32<0x141>(v);  // row_half_mirror
+  v += dpp_f32<0x140>(v);  // row_mirror
+  return v;
+}
+// acc[dt][r] of lane l is head dimension 32 dt + acc_row(r, l) of token l % 32.  The wave leaves the sums over
+// each of its four rows of 16 lanes in red[row][16 dt + r] (rows 0-1: lanes 0-31, rows 2-3: lanes 32-63).
+template <int D>
+__device__ __forceinline__ void wave_colsum(const f32x16 (&acc)[D / 32], float mul, float* red, int lane) {
+  f32x16 v[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[dt][r] = row16_sum(acc[dt][r] * mul);
+  if ((lane & 15) == 0) {  // one lane per row stores the row's D / 2 sums, 16 bytes at a time
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+    f32x4* dst = reinterpret_cast<f32x4*>(red + (lane >> 4) * (D / 2));
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = v[dt][q4 * 4 + e];
+        dst[dt * 4 + q4] = o;
+      }
+  }
+}
+// head dimension d of the workgroup's column sums: waves w0 .. w0 + nw - 1 of red ([wave][4][D / 2]) in order
+template <int D>
+__device__ __forceinline__ float colsum_of(const float* red, int w0, int nw, int d) {
+  const int dt = d >> 5, rem = d & 31, r = ((rem >> 3) << 2) | (rem & 3), hh = (rem >> 2) & 1;
+  float t = 0.f;
+  for (int w = w0; w < w0 + nw; ++w) {
+    const float* rw = red + (size_t)w * 4 * (D / 2) + dt * 16 + r;
+    t += rw[(2 * hh) * (D / 2)] + rw[(2 * hh + 1) * (D / 2)];
+  }
+  return t;
+}
+
 // Per-lane LDS offsets of the fragment reads.  The XOR swizzle makes an address a non-linear
 // function of (row, chunk), but the key depends on the lane's row modulo 16 only, so a lane has one
 // offset per distinct chunk pattern; tile row blocks of 16 / 32 rows and the LDS stage then enter as
@@ -345,7 +396,7 @@ template <int D, int ROWS>
 __global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx,
     const float* __restrict__ lse, float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb,
-    int causal, float scale) {
+    int causal, float scale, float* __restrict__ colpart) {
   constexpr int NT = 2 * ROWS, DEPTH = ROWS == 128 ? 1 : 2;
   __shared__ __attribute__((aligned(16))) bf16_t KVs[2][2][BLK * D];  // double-buffered, one barrier per tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -449,6 +500,14 @@ __global__ __launch_bounds__(2 * ROWS, ROWS == 128 ? 2 : 1) void attn_bwd_dq_ker
     for (int j = 0; j < nblk; ++j) body(j, j & 1);
   }
   store_rows<D>(dq, dqkv + ((size_t)b * S_seq + q) * ld + head * D, lane, scale);
+  if (colpart) {
+    // row (b, query block) of the partial column sums of dQ, [S_mb * S_seq / ROWS][N_heads * D]; the tile
+    // buffers are free: the loop ended on a barrier
+    float* red = reinterpret_cast<float*>(&KVs[0][0][0]);
+    wave_colsum<D>(dq, scale, red + (size_t)w * 4 * (D / 2), lane);
+    __syncthreads();
+    if (tid < D) colpart[((size_t)b * (S_seq / ROWS) + qblk) * h + head * D + tid] = colsum_of<D>(red, 0, NT / 64, tid);
+  }
 }
 
 // ----------------------------------------------------------------- backward, dK/dV pass
@@ -466,7 +525,7 @@ template <int D>
 __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
                                                                 bf16_t* __restrict__ dqkv, int S_seq, int N_heads, int S_mb, int causal,
-                                                                float scale) {
+                                                                float scale, float* __restrict__ colpart) {
   __shared__ __attribute__((aligned(16))) bf16_t QOs[2][2][BLK * D];  // Q and dO tiles, double-buffered
   __shared__ __attribute__((aligned(16))) float stat_s[2][2][BLK];    // lse * log2(e) and delta of the tile's queries
   __shared__ __attribute__((aligned(16))) bf16_t Ps[2][4][2][64 * 8]; // P of a sub-tile: [sub-tile][key group][register half][lane]
@@ -628,6 +687,16 @@ __global__ __launch_bounds__(NTHR_DKV) void attn_bwd_dkv_kernel(const bf16_t* __
   bf16_t* out = dqkv + ((size_t)b * S_seq + key) * ld + head * D;
   if (dk_role) store_rows<D>(acc, out + h, lane, scale);
   else store_rows<D>(acc, out + 2 * h, lane, 1.0f);
+  if (colpart) {
+    // row (b, key block) of the partial column sums of [dK | dV], [S_mb * S_seq / 128][2 N_heads * D]
+    float* red = reinterpret_cast<float*>(&QOs[0][0][0]);
+    wave_colsum<D>(acc, dk_role ? scale : 1.0f, red + (size_t)w * 4 * (D / 2), lane);
+    __syncthreads();
+    if (tid < 2 * D) {
+      const int dv = tid / D, d = tid - dv * D;  // dK from waves 4-7, dV from waves 0-3
+      colpart[((size_t)b * (S_seq / WG_ROWS) + kblk) * 2 * h + dv * h + head * D + d] = colsum_of<D>(red, dv ? 0 : 4, 4, d);
+    }
+  }
 }
 
 template <int D>
@@ -647,14 +716,16 @@ bf_status fwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, v
 
 template <int D>
 bf_status bwd_d(int S_mb, int S_seq, int N_heads, int causal, const void* qkv, const void* ctx, const float* lse,
-                const void* dctx, void* dqkv, float* delta, hipStream_t st) {
+                const void* dctx, void* dqkv, float* delta, float* part, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
   const unsigned grid = (unsigned)(S_seq / WG_ROWS) * N_heads * S_mb;
+  // partial column sums: dQ's rows first, then those of [dK | dV]
+  float* part_kv = part ? part + attention_bwd_mfma_part_q_rows(S_mb, S_seq) * (size_t)N_heads * D : nullptr;
   if (S_seq % 256 == 0)  // measured faster than the 128-query form also on grids that do not fill the chip
-    attn_bwd_dq_kernel<D, 256><<<grid / 2, 512, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+    attn_bwd_dq_kernel<D, 256><<<grid / 2, 512, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale, part);
   else
-    attn_bwd_dq_kernel<D, 128><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
-  attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale);
+    attn_bwd_dq_kernel<D, 128><<<grid, NTHR, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale, part);
+  attn_bwd_dkv_kernel<D><<<grid, NTHR_DKV, 0, st>>>((const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, S_seq, N_heads, S_mb, causal, scale, part_kv);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("attention_bwd_mfma launch failed: %s", hipGetErrorString(e)); return BF_EDEVICE; }
   return BF_OK;
@@ -680,11 +751,16 @@ bf_status attention_fwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int c
   return fwd_d<64>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, st);
 }
 
+// Rows of partial column sums the two backward kernels leave: one per (micro-batch sequence, query block) for dQ
+// and one per (sequence, block of 128 keys) for [dK | dV].
+size_t attention_bwd_mfma_part_q_rows(int S_mb, int S_seq) { return (size_t)S_mb * (S_seq / (S_seq % 256 == 0 ? 256 : WG_ROWS)); }
+size_t attention_bwd_mfma_part_kv_rows(int S_mb, int S_seq) { return (size_t)S_mb * (S_seq / WG_ROWS); }
+
 bf_status attention_bwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal, const void* qkv, const void* ctx,
-                             const float* lse, const void* dctx, void* dqkv, float* delta, hipStream_t st) {
+                             const float* lse, const void* dctx, void* dqkv, float* delta, hipStream_t st, float* part) {
   if (!args_ok(S_mb, S_seq, N_heads, S_head, qkv, dqkv) || !args_ok(S_mb, S_seq, N_heads, S_head, ctx, dctx)) return BF_EINVAL;
-  if (S_head == 128) return bwd_d<128>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
-  return bwd_d<64>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+  if (S_head == 128) return bwd_d<128>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, part, st);
+  return bwd_d<64>(S_mb, S_seq, N_heads, causal, qkv, ctx, lse, dctx, dqkv, delta, part, st);
 }
 
 }  // namespace bf

@@ -264,14 +264,31 @@ bf_status attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads
   return attention_fwd_plain(dtype, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, st);
 }
 
+size_t attention_bwd_part_elems(int S_mb, int S_seq, int N_heads, int S_head) {
+  if (S_mb < 1 || N_heads < 1 || !attention_mfma_supported(S_seq, S_head)) return 0;
+  const size_t h = (size_t)N_heads * S_head;
+  return attention_bwd_mfma_part_q_rows(S_mb, S_seq) * h + attention_bwd_mfma_part_kv_rows(S_mb, S_seq) * 2 * h;
+}
+
 bf_status attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                         const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv, float* delta,
-                        hipStream_t st) {
+                        hipStream_t st, float* db_qkv, float* part, int accumulate) {
+  const int h = N_heads * S_head;
+  bf_status r;
   if (dtype == BF_BF16 && kernels == BF_KERNELS_AUTO && attention_mfma_supported(S_seq, S_head)) {
     if (!qkv || !ctx || !lse || !dctx || !dqkv || !delta) { set_error("attention_bwd: null pointer"); return BF_EINVAL; }
-    return attention_bwd_mfma(S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+    float* use = db_qkv ? part : nullptr;
+    r = attention_bwd_mfma(S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta, st, use);
+    if (r != BF_OK || !db_qkv) return r;
+    if (use) {
+      const size_t rq = attention_bwd_mfma_part_q_rows(S_mb, S_seq), rkv = attention_bwd_mfma_part_kv_rows(S_mb, S_seq);
+      return attn_bias_finish(use, (int)rq, use + rq * h, (int)rkv, h, db_qkv, accumulate, st);
+    }
+  } else {
+    r = attention_bwd_plain(dtype, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+    if (r != BF_OK || !db_qkv) return r;
   }
-  return attention_bwd_plain(dtype, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+  return colsum(dtype, S_mb * S_seq, 3 * h, dqkv, db_qkv, accumulate, st);
 }
 
 }  // namespace bf

@@ -94,14 +94,28 @@ bf_status attention_bwd_plain(int dtype, int S_mb, int S_seq, int N_heads, int S
 bool attention_mfma_supported(int S_seq, int S_head);
 bf_status attention_fwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal,
                              const void* qkv, void* ctx, float* lse, hipStream_t st);
+// part (may be null): the kernels also leave partial column sums of dqkv, attention_bwd_mfma_part_q_rows rows of
+// [S_hidden] for dQ (one per sequence and query block) followed by attention_bwd_mfma_part_kv_rows rows of
+// [2 S_hidden] for [dK | dV] (one per sequence and block of 128 keys).
 bf_status attention_bwd_mfma(int S_mb, int S_seq, int N_heads, int S_head, int causal,
                              const void* qkv, const void* ctx, const float* lse, const void* dctx,
-                             void* dqkv, float* delta, hipStream_t st);
+                             void* dqkv, float* delta, hipStream_t st, float* part = nullptr);
+size_t attention_bwd_mfma_part_q_rows(int S_mb, int S_seq);
+size_t attention_bwd_mfma_part_kv_rows(int S_mb, int S_seq);
 bf_status attention_fwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                         const void* qkv, void* ctx, float* lse, hipStream_t st);
+// db_qkv (may be null): also db_qkv[3 S_hidden] = (accumulate ? db_qkv : 0) + column sums of dqkv, the bias
+// gradient of the QKV projection.  With `part` (attention_bwd_part_elems floats) the matrix-core kernels take the
+// sums on their way out and a small kernel adds their partial rows in fixed order; without it, or on the plain
+// path, dqkv is read a second time.
 bf_status attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                         const void* qkv, const void* ctx, const float* lse, const void* dctx,
-                        void* dqkv, float* delta, hipStream_t st);
+                        void* dqkv, float* delta, hipStream_t st, float* db_qkv = nullptr, float* part = nullptr,
+                        int accumulate = 0);
+size_t attention_bwd_part_elems(int S_mb, int S_seq, int N_heads, int S_head);
+// out[n] = (accumulate ? out[n] : 0) + sum_r pq[r][n] for n < h, + sum_r pkv[r][n - h] for h <= n < 3 h
+bf_status attn_bias_finish(const float* pq, int rows_q, const float* pkv, int rows_kv, int h, float* out, int accumulate,
+                           hipStream_t st);
 
 // Input layer: x[t, :] = e_tok[tok[t], :] + e_pos[t mod S_seq, :] for n_rows = S_mb * S_seq rows (fp32 tables).
 bf_status embedding_fwd(int dtype, int n_rows, int S_seq, int S_voc, int h, const int32_t* tok, const float* e_tok,

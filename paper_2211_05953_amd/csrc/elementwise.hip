@@ -697,6 +697,26 @@ bf_status colsum_finish(const float* part, int rows, int N, float* out, int accu
   return BF_OK;
 }
 
+__global__ __launch_bounds__(256) void attn_bias_finish_kernel(const float* __restrict__ pq, int rows_q, const float* __restrict__ pkv,
+                                                               int rows_kv, int h, float* __restrict__ out, int accumulate) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= 3 * h) return;
+  float t = accumulate ? out[n] : 0.f;
+  if (n < h)
+    for (int r = 0; r < rows_q; ++r) t += pq[(size_t)r * h + n];
+  else
+    for (int r = 0; r < rows_kv; ++r) t += pkv[(size_t)r * 2 * h + (n - h)];
+  out[n] = t;
+}
+
+bf_status attn_bias_finish(const float* pq, int rows_q, const float* pkv, int rows_kv, int h, float* out, int accumulate,
+                           hipStream_t st) {
+  if (!pq || !pkv || !out || rows_q < 1 || rows_kv < 1 || h < 1) { set_error("attn_bias_finish: bad argument"); return BF_EINVAL; }
+  attn_bias_finish_kernel<<<(3 * h + 255) / 256, 256, 0, st>>>(pq, rows_q, pkv, rows_kv, h, out, accumulate);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
 __global__ void bump_step_kernel(int* t) { *t += 1; }
 
 bf_status bump_step(int* t_dev, hipStream_t st) {

@@ -120,6 +120,19 @@ bf_status bf_op_attention_bwd(int dtype, int kernels, int S_mb, int S_seq, int N
                        (hipStream_t)stream);
 }
 
+bf_status bf_op_attention_bwd_bias(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
+                                   const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                                   float* delta, float* db_qkv, float* part, int accumulate, void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (!db_qkv) { set_error("bf_op_attention_bwd_bias: db_qkv is null"); return BF_EINVAL; }
+  return attention_bwd(dtype, kernels, S_mb, S_seq, N_heads, S_head, causal, qkv, ctx, lse, dctx, dqkv, delta,
+                       (hipStream_t)stream, db_qkv, part, accumulate);
+}
+
+size_t bf_op_attention_bwd_part_elems(int S_mb, int S_seq, int N_heads, int S_head) {
+  return attention_bwd_part_elems(S_mb, S_seq, N_heads, S_head);
+}
+
 bf_status bf_op_attention_bwd_static(int dtype, int kernels, int S_mb, int S_seq, int N_heads, int S_head, int causal,
                                                 const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
                                                 void* stream) {

@@ -140,7 +140,7 @@ RecSizes rec_sizes(const bf_config& c) {
   return r;
 }
 
-struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, total; };
+struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, attnpart, total; };
 
 TmpSizes tmp_sizes(const bf_config& c) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
@@ -152,7 +152,9 @@ TmpSizes tmp_sizes(const bf_config& c) {
   t.colpart = up(((T + 127) / 128) * f * 4);
   // partial column sums of the one-pass LayerNorm backward: one row of [3][h] per workgroup
   t.lnpart = up(layernorm_bwd_part_elems((int)T, (int)h) * 4);
-  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart + t.lnpart;
+  // partial column sums of dqkv that the attention backward kernels leave per query / key block
+  t.attnpart = up(attention_bwd_part_elems(c.S_mb_max, c.S_seq, c.N_heads, c.S_head) * 4);
+  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart + t.lnpart + t.attnpart;
   return t;
 }
 
@@ -313,7 +315,7 @@ Record record_for(bf_stack* s, int layer, int mb) {
   return R;
 }
 
-struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart, *lnpart; };
+struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart, *lnpart, *attnpart; };
 
 // Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
 struct GradRec { char *dy, *du, *dx1, *dqkv; };
@@ -340,7 +342,8 @@ Tmp tmp_of(bf_stack* s) {
   Tmp T;
   char* p = s->ws + s->Lo.off_tmp;
   T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
-  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p; p += t.colpart; T.lnpart = (float*)p;
+  T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p; p += t.colpart; T.lnpart = (float*)p; p += t.lnpart;
+  T.attnpart = t.attnpart ? (float*)p : nullptr;
   return T;
 }
 
@@ -402,13 +405,15 @@ bf_status p_attn_fwd(bf_stack* s, int S_mb, const void* qkv, void* ctx, float* l
     return attention_fwd(c.dtype, c.kernels, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, qkv, ctx, lse, st);
   });
 }
+// db_qkv: the QKV bias gradient (column sums of dqkv), taken on the way when `part` is there
 bf_status p_attn_bwd(bf_stack* s, int S_mb, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
-                     float* delta, hipStream_t st) {
+                     float* delta, float* db_qkv, float* part, int acc, hipStream_t st) {
   const bf_config& c = s->cfg;
   const double full = 4.0 * c.S_seq * (double)S_mb * c.S_seq * c.S_hidden;
   // algorithmic backward = 2.5 x forward (five score-sized products); the two-pass kernels run seven
   return timed(s, BF_K_ATTN_BWD, 2.5 * (c.causal ? full / 2 : full), 0.0, st, [&] {
-    return attention_bwd(c.dtype, c.kernels, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, qkv, ctx, lse, dctx, dqkv, delta, st);
+    return attention_bwd(c.dtype, c.kernels, S_mb, c.S_seq, c.N_heads, c.S_head, c.causal, qkv, ctx, lse, dctx, dqkv, delta, st,
+                         db_qkv, part, acc);
   });
 }
 
@@ -481,13 +486,12 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
   }
   g = GemmArgs{T, h, h, dx1, weight_ptr(s, layer, BF_W_O), t.dctx, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
-  BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, dqkv, t.delta, st));
-  // qkv = a W_qkv + b_qkv
+  // qkv = a W_qkv + b_qkv: the bias gradient is the column sum of dqkv, which the attention kernels take on their way out
+  BF_TRY(p_attn_bwd(s, S_mb, R.qkv, R.ctx, R.lse, t.dctx, dqkv, t.delta, G(BF_B_QKV), t.attnpart, acc, st));
   if (!keep) {
     g = GemmArgs{h, 3 * h, T, R.a, dqkv, G(BF_W_QKV), nullptr, nullptr, nullptr, acc};
     BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
   }
-  BF_TRY(p_colsum(s, T, 3 * h, dqkv, G(BF_B_QKV), acc, st));
   g = GemmArgs{T, h, 3 * h, dqkv, weight_ptr(s, layer, BF_W_QKV), t.dc, nullptr, nullptr, nullptr, 0};
   BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
   // a = LN1(x); dx = dx1 + LN1'(da); dx is the gradient arriving at the layer below, whose FC2 bias gradient is

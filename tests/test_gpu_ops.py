@@ -207,6 +207,30 @@ def test_attention_fwd_bwd(mode, dtype, kernels, causal, S_mb, S_seq, a, d):
     got = to_host(dqkv)
     for i, name in enumerate(("dq", "dk", "dv")):
         assert rel_err(got[..., i * h:(i + 1) * h], dqkv_ref[..., i * h:(i + 1) * h]) <= TOL[mode], name
+    # the same with the QKV bias gradient (column sums of dqkv) on the way: with the scratch for the kernels' partial
+    # sums (where the matrix-core kernels serve the shape) and without it (dqkv read a second time); overwrite, then add
+    n_part = bf.bf_op_attention_bwd_part_elems(S_mb, S_seq, a, d)
+    mfma = bf.bf_op_attention_uses_mfma(S_seq, d)
+    q_rows = S_mb * (S_seq // (256 if S_seq % 256 == 0 else 128)) if mfma else 0
+    assert n_part == (q_rows * h + S_mb * (S_seq // 128) * 2 * h if mfma else 0)
+    db_ref = dqkv_ref.reshape(-1, 3 * h).sum(axis=0)
+    for with_part in (True, False):
+        part = torch.full((max(n_part, 1),), float("nan"), dtype=torch.float32, device="cuda") if with_part and n_part else None
+        dqkv2 = torch.full_like(dqkv, float("nan"))
+        db = torch.full((3 * h,), float("nan"), dtype=torch.float32, device="cuda")
+        bf.bf_op_attention_bwd_bias(dtype, kernels, S_mb, S_seq, a, d, causal, dQKV, ctx, lse, dDC, dqkv2, delta, db, part, 0)
+        assert torch.equal(dqkv2, dqkv)
+        first = to_host(db).copy()
+        # (the K third is zero in exact arithmetic: a softmax row does not move when every score of it is shifted by the
+        # same amount, which is all a key bias does; so the thirds are judged together, on the scale of the whole vector)
+        assert rel_err(first, db_ref) <= TOL[mode]
+        for i, name in ((0, "dq"), (2, "dv")):
+            assert rel_err(first[i * h:(i + 1) * h], db_ref[i * h:(i + 1) * h]) <= TOL[mode], name
+        # against the sums of what was stored: the fused form adds the values before they are rounded to bf16
+        stored = got.astype(np.float64).reshape(-1, 3 * h).sum(axis=0)
+        assert rel_err(first, stored) <= (2.0 ** -8 if b16 else 1e-5)
+        bf.bf_op_attention_bwd_bias(dtype, kernels, S_mb, S_seq, a, d, causal, dQKV, ctx, lse, dDC, dqkv2, delta, db, part, 1)
+        assert rel_err(to_host(db), 2.0 * first.astype(np.float64)) <= 1e-6
 
 
 @pytest.mark.parametrize("M,N,K", [(2048, 4096, 512), (4096, 2048, 192), (512, 16384, 128)])

@@ -571,10 +571,10 @@ def test_timing_modes_fill_the_report_and_leave_the_numbers_alone():
             assert (n("gemm_fwd"), n("gemm_dgrad")) == (4 * lm, 4 * lm)
             assert all(rep.kernel_ms[K_[c]] > 0 and rep.kernel_flops[K_[c]] > 0 for c in ("gemm_fwd", "gemm_dgrad"))
             assert rep.kernel_flops[K_["gemm_fwd"]] == rep.kernel_flops[K_["gemm_dgrad"]] == rep.kernel_flops[K_["gemm_wgrad"]]
-            # one separate column-sum launch per layer backward (the QKV bias gradient) and one per micro-batch for the
-            # top layer's incoming gradient: FC1's bias gradient is taken inside the FC2 dgrad product, the
+            # the only separate column-sum launch left is the one per micro-batch for the top layer's incoming gradient:
+            # FC1's bias gradient is taken inside the FC2 dgrad product, the QKV one inside the attention backward, the
             # out-projection's and the lower layers' FC2 ones inside the LayerNorm backward that writes the tensor
-            assert (n("attn_fwd"), n("attn_bwd"), n("ln_fwd"), n("ln_bwd"), n("colsum")) == (lm, lm, 2 * lm, 2 * lm, lm + N_mb)
+            assert (n("attn_fwd"), n("attn_bwd"), n("ln_fwd"), n("ln_bwd"), n("colsum")) == (lm, lm, 2 * lm, 2 * lm, N_mb)
         if timing in (0, 1):
             assert sum(int(v) for v in rep.kernel_launches) == 0
         if timing == 3:
