@@ -133,31 +133,49 @@ def test_fused_weight_gradient_over_16_micro_batches_on_sampled_outputs():
                   1e-5, 4 * math.sqrt(n_seg * T))
 
 
-def test_attention_at_full_size_on_sampled_rows():
+@pytest.mark.parametrize("heads,seq,causal", [(A, S, 1), (16, S, 1), (48, S, 1), (A, 1024, 0)])
+def test_attention_at_full_size_on_sampled_rows(heads, seq, causal):
+    """Forward, backward and the QKV bias gradient taken in the backward kernels, at the head counts of the 52B-shaped
+    (64), 1.3B-shaped (16: fewer workgroups than compute units, the 128-query forward form) and deep-loop (48)
+    configurations and at the bidirectional workload's sequence length; three sampled heads against the oracle."""
+    Hh = heads * D
     g = torch.Generator(device="cuda").manual_seed(11)
-    qkv = torch.randn((1, S, 3 * H), generator=g, device="cuda").bfloat16()
-    dctx = torch.randn((1, S, H), generator=g, device="cuda").bfloat16()
-    ctx = torch.empty((1, S, H), dtype=torch.bfloat16, device="cuda")
-    lse = torch.empty((1, A, S), dtype=torch.float32, device="cuda")
+    qkv = torch.randn((1, seq, 3 * Hh), generator=g, device="cuda").bfloat16()
+    dctx = torch.randn((1, seq, Hh), generator=g, device="cuda").bfloat16()
+    ctx = torch.empty((1, seq, Hh), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((1, heads, seq), dtype=torch.float32, device="cuda")
     dqkv = torch.empty_like(qkv)
-    delta = torch.empty(A * S, dtype=torch.float32, device="cuda")
-    assert bf.bf_op_attention_uses_mfma(S, D)
-    bf.bf_op_attention_fwd(bf.BF_BF16, 0, 1, S, A, D, 1, qkv, ctx, lse)
-    bf.bf_op_attention_bwd(bf.BF_BF16, 0, 1, S, A, D, 1, qkv, ctx, lse, dctx, dqkv, delta)
-    qh, ch, dh, gh, lh = to_host(qkv), to_host(ctx), to_host(dctx), to_host(dqkv), to_host(lse)
+    delta = torch.empty(heads * seq, dtype=torch.float32, device="cuda")
+    assert bf.bf_op_attention_uses_mfma(seq, D)
+    bf.bf_op_attention_fwd(bf.BF_BF16, 0, 1, seq, heads, D, causal, qkv, ctx, lse)
+    part = torch.full((bf.bf_op_attention_bwd_part_elems(1, seq, heads, D),), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((3 * Hh,), float("nan"), dtype=torch.float32, device="cuda")
+    bf.bf_op_attention_bwd_bias(bf.BF_BF16, 0, 1, seq, heads, D, causal, qkv, ctx, lse, dctx, dqkv, delta, db, part, 0)
+    dqkv_plain = torch.empty_like(qkv)
+    bf.bf_op_attention_bwd(bf.BF_BF16, 0, 1, seq, heads, D, causal, qkv, ctx, lse, dctx, dqkv_plain, delta)
+    assert torch.equal(dqkv, dqkv_plain)
+    qh, ch, dh, gh, lh, bh = to_host(qkv), to_host(ctx), to_host(dctx), to_host(dqkv), to_host(lse), to_host(db)
+    # the whole bias gradient against the sums of what was stored (the kernels add the values before rounding)
+    assert rel_err(bh, gh.astype(np.float64).reshape(-1, 3 * Hh).sum(axis=0)) <= 2.0 ** -8
     rng = np.random.default_rng(3)
-    for head in rng.choice(A, 3, replace=False):
+    for head in rng.choice(heads, 3, replace=False):
         # the oracle on this one head (heads are independent)
         cols = np.r_[head * D:(head + 1) * D]
-        one = np.concatenate([qh[..., cols], qh[..., H + cols], qh[..., 2 * H + cols]], axis=-1).astype(np.float64)
-        ctx_ref, saved = L.attention_fwd(one, 1, True)
+        one = np.concatenate([qh[..., cols], qh[..., Hh + cols], qh[..., 2 * Hh + cols]], axis=-1).astype(np.float64)
+        ctx_ref, saved = L.attention_fwd(one, 1, bool(causal))
         dq_ref = L.attention_bwd(dh[..., cols].astype(np.float64), saved, 1)
         assert rel_err(ch[..., cols], ctx_ref) <= TOL["bf16"]
         for j, nm in enumerate(("dq", "dk", "dv")):
-            assert rel_err(gh[..., j * H + cols], dq_ref[..., j * D:(j + 1) * D]) <= TOL["bf16"], (head, nm)
+            assert rel_err(gh[..., j * Hh + cols], dq_ref[..., j * D:(j + 1) * D]) <= TOL["bf16"], (head, nm)
+        # bias gradient of this head's Q and V columns (the K third is zero in exact arithmetic)
+        db_ref = dq_ref.reshape(-1, 3 * D).sum(axis=0)
+        for j in (0, 2):
+            assert rel_err(bh[j * Hh + cols], db_ref[j * D:(j + 1) * D]) <= TOL["bf16"], (head, j)
+        assert np.abs(bh[Hh + cols]).max() <= TOL["bf16"] * np.abs(db_ref).max()
         q, k, v, p = saved
         s = (q[0, 0] @ k[0, 0].T) / math.sqrt(D)
-        s = np.where(np.tril(np.ones((S, S), dtype=bool)), s, -np.inf)
+        if causal:
+            s = np.where(np.tril(np.ones((seq, seq), dtype=bool)), s, -np.inf)
         lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
         assert np.abs(lh[0, head] - lse_ref).max() <= 2e-2
 
