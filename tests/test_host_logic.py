@@ -59,6 +59,25 @@ def test_config_validation_without_a_device():
     assert bf.bf_workspace_bytes(bf.make_config(256, 4, 1024, 128, 4, 4, 1, S_voc=-1)) == 0
 
 
+def test_scratch_sizes_without_a_device():
+    """Host arithmetic of the scratch areas the single kernels ask their callers for (include/bf_ops.h)."""
+    # one-pass LayerNorm backward: one row of [3][h] per workgroup, at most 256 workgroups of ceil(T / 256)-row runs
+    for T, h in [(1, 8), (255, 64), (256, 64), (257, 64), (2048, 8192), (8192, 8192), (3000, 100)]:
+        run = -(-T // 256)
+        assert bf.bf_op_layernorm_bwd_part_elems(T, h) == 3 * h * -(-T // run)
+    assert bf.bf_op_layernorm_bwd_part_elems(0, 64) == 0 and bf.bf_op_layernorm_bwd_part_elems(64, 0) == 0
+    # attention backward with the QKV bias gradient: a row of [S_hidden] per sequence and query block (256 queries when
+    # S_seq is a multiple of 256, else 128) and a row of [2 S_hidden] per sequence and block of 128 keys; nothing for
+    # shapes the matrix-core kernels do not serve
+    for S_mb, S_seq, a, d in [(1, 2048, 64, 128), (4, 2048, 64, 128), (1, 384, 2, 128), (2, 128, 4, 64), (1, 1024, 16, 128)]:
+        h = a * d
+        q_rows = S_mb * (S_seq // (256 if S_seq % 256 == 0 else 128))
+        assert bf.bf_op_attention_bwd_part_elems(S_mb, S_seq, a, d) == q_rows * h + S_mb * (S_seq // 128) * 2 * h
+        assert bf.bf_op_attention_uses_mfma(S_seq, d)
+    for S_mb, S_seq, a, d in [(1, 100, 3, 40), (1, 64, 4, 64), (1, 2048, 64, 96), (0, 2048, 64, 128), (1, 2048, 0, 128)]:
+        assert bf.bf_op_attention_bwd_part_elems(S_mb, S_seq, a, d) == 0
+
+
 @pytest.mark.parametrize("kind,code", [("BF", bf.BF_SCHED_BF), ("DF", bf.BF_SCHED_DF)])
 def test_schedule_trace_matches_oracle_and_closed_forms(kind, code):
     for N_PP in (1, 2, 4, 8):
