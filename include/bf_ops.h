@@ -50,6 +50,17 @@ bf_status bf_op_gemm(int dtype, int kernels, int layout, int epilogue, int M, in
  * NULL, or a problem that goes to the plain kernel: a second pass over C takes them.  db: device fp32 [N]. */
 bf_status bf_op_gemm_gelu_bwd_colsum(int dtype, int kernels, int M, int N, int K, const void* A, const void* Bt, void* C,
                                      const void* R, float* db, float* part, int accumulate, void* stream);
+/* bf_op_gemm for the forward / dgrad layouts (BF_NN, BF_NT; epilogues none, bias, bias + residual) with scratch for a
+ * split contraction: a bf16 product on the matrix cores whose tiles would fill at most half of the chip in its only
+ * round, with K >= 2048, runs K in bf_op_gemm_splitk_slices(...) slices on that many times the workgroups; each slice
+ * leaves an fp32 plane in `planes` (device, slices * M * N floats, owned by the caller) and a second kernel adds the
+ * planes in ascending order and applies the epilogue, so the result does not depend on the order the slices finish
+ * in.  Any other shape, dtype or kernel choice, planes == NULL or planes_elems too small: exactly bf_op_gemm. */
+bf_status bf_op_gemm_splitk(int dtype, int kernels, int layout, int epilogue, int M, int N, int K, const void* A,
+                            const void* B, void* C, const float* bias, const void* R, float* planes,
+                            size_t planes_elems, void* stream);
+/* Slices that call would use for this shape (1: the contraction is not split). */
+int bf_op_gemm_splitk_slices(int layout, int epilogue, int M, int N, int K);
 /* 1 if the MFMA kernel takes this problem in bf16 mode, 0 if the plain kernel would run. */
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
 

@@ -101,6 +101,8 @@ _SIGNATURES = {
     "bf_op_attention_fwd": (C.c_int, [C.c_int] * 7 + [_P] * 4),
     "bf_op_attention_bwd": (C.c_int, [C.c_int] * 7 + [_P] * 7),
     "bf_op_attention_bwd_static": (C.c_int, [C.c_int] * 7 + [_P] * 6),
+    "bf_op_gemm_splitk": (C.c_int, [C.c_int] * 7 + [_P] * 6 + [C.c_size_t, _P]),
+    "bf_op_gemm_splitk_slices": (C.c_int, [C.c_int] * 5),
     "bf_op_attention_bwd_bias": (C.c_int, [C.c_int] * 7 + [_P] * 8 + [C.c_int, _P]),
     "bf_op_attention_bwd_part_elems": (C.c_size_t, [C.c_int] * 4),
     "bf_op_attention_uses_mfma": (C.c_int, [C.c_int, C.c_int]),
@@ -315,6 +317,16 @@ def bf_op_wgrad(dtype, kernels, M, N, K, n_seg, X, stride_x, dY, stride_dy, G, d
 def bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, A, Bt, Cout, R, db, part=None, accumulate=0):
     check(load().bf_op_gemm_gelu_bwd_colsum(dtype, kernels, M, N, K, _ptr(A), _ptr(Bt), _ptr(Cout), _ptr(R), _ptr(db),
                                             _ptr(part), accumulate, _stream()))
+
+
+def bf_op_gemm_splitk(dtype, kernels, layout, epilogue, M, N, K, A, B, Cout, bias=None, R=None, planes=None):
+    opt = lambda t: _ptr(t) if t is not None else None
+    check(load().bf_op_gemm_splitk(dtype, kernels, layout, epilogue, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), opt(bias), opt(R),
+                                   opt(planes), planes.numel() if planes is not None else 0, _stream()))
+
+
+def bf_op_gemm_splitk_slices(layout, epilogue, M, N, K):
+    return load().bf_op_gemm_splitk_slices(layout, epilogue, M, N, K)
 
 
 def bf_op_gemm_uses_mfma(layout, epilogue, M, N, K):

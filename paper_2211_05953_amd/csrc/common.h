@@ -51,6 +51,13 @@ struct GemmArgs {
   // pass over C does.  colsum_rows: set by the MFMA launcher to the rows of partial sums written.
   float* colsum_part = nullptr;
   int* colsum_rows = nullptr;
+  // Forward / dgrad layouts with E_ACCUM (matrix-core kernel only): C is [k_slices][M][N] fp32 and slice y of the
+  // contraction (K / k_slices long) leaves its partial product in plane y; gemm_splitk_finish adds the planes.
+  int k_slices = 1;
+  // Forward / dgrad layouts: fp32 scratch for those planes.  With it, gemm() splits the contraction of a product
+  // whose tiles would leave half of the chip idle (see gemm_splitk_slices) and finishes it with a second kernel.
+  float* splitk_ws = nullptr;
+  size_t splitk_ws_elems = 0;
 };
 
 void set_error(const char* fmt, ...);
@@ -70,6 +77,12 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 // true if the MFMA kernel covers this problem (bf16, sizes multiples of its tiles)
 bool gemm_mfma_supported(int layout, int epi, int M, int N, int K);
 bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st);
+// Slices the matrix-core path would cut the contraction of this forward / dgrad product into (1: no split).
+int gemm_splitk_slices(int layout, int epi, int M, int N, int K);
+// C[M,N] (bf16) = epilogue(sum over the planes of part[slices][M][N], added in ascending order); epilogues
+// E_NONE, E_BIAS, E_BIAS_RES.
+bf_status gemm_splitk_finish(int epi, int M, int N, int slices, const float* part, const float* bias, const void* R,
+                             void* C, hipStream_t st);
 bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, hipStream_t st);
 
 bf_status layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps,

@@ -721,6 +721,57 @@ bf_status attn_bias_finish(const float* pq, int rows_q, const float* pkv, int ro
   return BF_OK;
 }
 
+// C = epilogue(sum of the planes of a split contraction), 8 adjacent columns per thread; planes added in ascending order
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(int slices, size_t MN, int N, const float* __restrict__ part,
+                                                            const float* __restrict__ bias, const bf16_t* __restrict__ R,
+                                                            bf16_t* __restrict__ C) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= MN) return;
+  float v[8];
+  load_vec<float, 8>(part + i, v);
+  for (int s = 1; s < slices; ++s) {
+    float u[8];
+    load_vec<float, 8>(part + (size_t)s * MN + i, u);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += u[j];
+  }
+  if (EPI == E_BIAS || EPI == E_BIAS_RES) {
+    float b[8];
+    load_vec<float, 8>(bias + (i % (size_t)N), b);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += b[j];
+  }
+  if (EPI == E_BIAS_RES) {
+    float r[8];
+    load_vec<bf16_t, 8>(R + i, r);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += r[j];
+  }
+  store_vec<bf16_t, 8>(C + i, v);
+}
+
+bf_status gemm_splitk_finish(int epi, int M, int N, int slices, const float* part, const float* bias, const void* R, void* C,
+                             hipStream_t st) {
+  if (M < 1 || N < 8 || N % 8 || slices < 2 || !part || !C) { set_error("gemm_splitk_finish: bad argument"); return BF_EINVAL; }
+  if ((epi == E_BIAS || epi == E_BIAS_RES) && !bias) { set_error("gemm_splitk_finish: bias is null"); return BF_EINVAL; }
+  if (epi == E_BIAS_RES && !R) { set_error("gemm_splitk_finish: residual is null"); return BF_EINVAL; }
+  if (!aligned16(part) || !aligned16(C) || (bias && !aligned16(bias)) || (R && !aligned16(R))) {
+    set_error("gemm_splitk_finish: operands must be 16-byte aligned");
+    return BF_EINVAL;
+  }
+  const size_t MN = (size_t)M * N;
+  const unsigned grid = (unsigned)((MN / 8 + 255) / 256);
+  switch (epi) {
+    case E_NONE: splitk_finish_kernel<E_NONE><<<grid, 256, 0, st>>>(slices, MN, N, part, bias, (const bf16_t*)R, (bf16_t*)C); break;
+    case E_BIAS: splitk_finish_kernel<E_BIAS><<<grid, 256, 0, st>>>(slices, MN, N, part, bias, (const bf16_t*)R, (bf16_t*)C); break;
+    case E_BIAS_RES: splitk_finish_kernel<E_BIAS_RES><<<grid, 256, 0, st>>>(slices, MN, N, part, bias, (const bf16_t*)R, (bf16_t*)C); break;
+    default: set_error("gemm_splitk_finish: epilogue %d is not finished here", epi); return BF_EINVAL;
+  }
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
 __global__ void bump_step_kernel(int* t) { *t += 1; }
 
 bf_status bump_step(int* t_dev, hipStream_t st) {

@@ -147,6 +147,19 @@ bf_status gemm(int dtype, int kernels, int layout, int epi, const GemmArgs& a, h
     }
     GemmArgs b = a;
     b.colsum_part = nullptr;
+    const int slices = a.splitk_ws ? gemm_splitk_slices(layout, epi, a.M, a.N, a.K) : 1;
+    if (slices > 1 && a.splitk_ws_elems >= (size_t)slices * a.M * a.N && ((uintptr_t)a.splitk_ws & 15) == 0) {
+      // few tiles, long contraction: slices of K on more workgroups into fp32 planes, then the planes added in order
+      b.C = a.splitk_ws;
+      b.bias = nullptr;
+      b.R = nullptr;
+      b.C2 = nullptr;
+      b.accumulate = 0;
+      b.k_slices = slices;
+      s = gemm_mfma(layout, E_ACCUM, b, st);
+      if (s != BF_OK) return s;
+      return gemm_splitk_finish(epi, a.M, a.N, slices, a.splitk_ws, a.bias, a.R, a.C, st);
+    }
     s = gemm_mfma(layout, epi, b, st);
   } else {
     s = gemm_plain(dtype, layout, epi, a, st);

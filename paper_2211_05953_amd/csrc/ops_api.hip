@@ -76,6 +76,19 @@ bf_status bf_op_gemm_gelu_bwd_colsum(int dtype, int kernels, int M, int N, int K
   return gemm(dtype, kernels, L_NT, E_GELU_BWD, a, (hipStream_t)stream);
 }
 
+bf_status bf_op_gemm_splitk(int dtype, int kernels, int layout, int epilogue, int M, int N, int K, const void* A,
+                            const void* B, void* C, const float* bias, const void* R, float* planes, size_t planes_elems,
+                            void* stream) {
+  if (!dtype_ok(dtype, kernels)) return BF_EINVAL;
+  if (epilogue == E_ACCUM || layout == L_TN) { set_error("bf_op_gemm_splitk: forward and dgrad layouts only"); return BF_EINVAL; }
+  GemmArgs a{M, N, K, A, B, C, bias, R, nullptr, 0};
+  a.splitk_ws = planes;
+  a.splitk_ws_elems = planes_elems;
+  return gemm(dtype, kernels, layout, epilogue, a, (hipStream_t)stream);
+}
+
+int bf_op_gemm_splitk_slices(int layout, int epilogue, int M, int N, int K) { return gemm_splitk_slices(layout, epilogue, M, N, K); }
+
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K) {
   return gemm_mfma_supported(layout, epilogue, M, N, K) ? 1 : 0;
 }

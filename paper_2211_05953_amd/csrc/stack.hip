@@ -11,6 +11,7 @@
 //   backward temporaries, per-micro-batch gradient hand-off buffers, output scratch
 // Parameters of a layer are contiguous and layers follow each other, so a stage is one
 // contiguous range and its Adam step is one launch.
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -140,7 +141,7 @@ RecSizes rec_sizes(const bf_config& c) {
   return r;
 }
 
-struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, attnpart, total; };
+struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, attnpart, splitk, total; };
 
 TmpSizes tmp_sizes(const bf_config& c) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
@@ -154,7 +155,19 @@ TmpSizes tmp_sizes(const bf_config& c) {
   t.lnpart = up(layernorm_bwd_part_elems((int)T, (int)h) * 4);
   // partial column sums of dqkv that the attention backward kernels leave per query / key block
   t.attnpart = up(attention_bwd_part_elems(c.S_mb_max, c.S_seq, c.N_heads, c.S_head) * 4);
-  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart + t.lnpart + t.attnpart;
+  // fp32 planes of the products whose contraction is split (few tiles, long K): the largest such product of a layer
+  size_t planes = 0;
+  if (c.dtype == BF_BF16 && c.kernels == BF_KERNELS_AUTO) {
+    const int Ti = (int)T, hi = (int)h, fi = (int)f;
+    const int cand[6][5] = {{L_NN, E_BIAS, Ti, 3 * hi, hi},     {L_NN, E_BIAS_RES, Ti, hi, hi}, {L_NN, E_BIAS_RES, Ti, hi, fi},
+                            {L_NT, E_NONE, Ti, hi, 3 * hi},     {L_NT, E_NONE, Ti, hi, hi},     {L_NT, E_NONE, Ti, hi, fi}};
+    for (const auto& k : cand) {
+      const int sl = gemm_splitk_slices(k[0], k[1], k[2], k[3], k[4]);
+      if (sl > 1) planes = std::max(planes, (size_t)sl * k[2] * k[3]);
+    }
+  }
+  t.splitk = up(planes * 4);
+  t.total = t.du + t.dc + t.dx1 + t.dctx + t.dqkv + t.delta + 2 * t.ping + t.colpart + t.lnpart + t.attnpart + t.splitk;
   return t;
 }
 
@@ -315,7 +328,7 @@ Record record_for(bf_stack* s, int layer, int mb) {
   return R;
 }
 
-struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart, *lnpart, *attnpart; };
+struct Tmp { char *du, *dc, *dx1, *dctx, *dqkv, *ping[2]; float *delta, *colpart, *lnpart, *attnpart, *splitk; size_t splitk_elems; };
 
 // Per (layer, micro-batch) gradients kept for the fused weight gradient of a stage.
 struct GradRec { char *dy, *du, *dx1, *dqkv; };
@@ -344,6 +357,9 @@ Tmp tmp_of(bf_stack* s) {
   T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
   T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p; p += t.colpart; T.lnpart = (float*)p; p += t.lnpart;
   T.attnpart = t.attnpart ? (float*)p : nullptr;
+  p += t.attnpart;
+  T.splitk = t.splitk ? (float*)p : nullptr;
+  T.splitk_elems = t.splitk / 4;
   return T;
 }
 
@@ -379,7 +395,13 @@ bf_status p_gemm(bf_stack* s, int layout, int epi, const GemmArgs& g, hipStream_
   double bytes = es * ((double)g.M * g.K + (double)g.K * g.N) + (layout == L_TN ? (g.accumulate ? 8.0 : 4.0) : es) * g.M * g.N;
   const double nseg = g.n_seg > 1 ? g.n_seg : 1;
   if (nseg > 1) bytes = es * nseg * ((double)g.M * g.K + (double)g.K * g.N) + 4.0 * g.M * g.N;
-  return timed(s, cls, 2.0 * g.M * g.N * g.K * nseg, bytes, st, [&] { return gemm(s->cfg.dtype, s->cfg.kernels, layout, epi, g, st); });
+  GemmArgs a = g;
+  if (layout != L_TN) {  // scratch for a split contraction; gemm() decides whether the product takes it
+    const Tmp t = tmp_of(s);
+    a.splitk_ws = t.splitk;
+    a.splitk_ws_elems = t.splitk_elems;
+  }
+  return timed(s, cls, 2.0 * g.M * g.N * g.K * nseg, bytes, st, [&] { return gemm(s->cfg.dtype, s->cfg.kernels, layout, epi, a, st); });
 }
 bf_status p_ln_fwd(bf_stack* s, int T, int h, const void* x, const float* g, const float* b, float eps, void* y, float* stats,
                    hipStream_t st) {

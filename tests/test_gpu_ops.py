@@ -233,6 +233,54 @@ def test_attention_fwd_bwd(mode, dtype, kernels, causal, S_mb, S_seq, a, d):
         assert rel_err(to_host(db), 2.0 * first.astype(np.float64)) <= 1e-6
 
 
+@pytest.mark.parametrize("M,N,K", [(2048, 2048, 8192), (2048, 2048, 6144), (1024, 1024, 4096), (256, 128, 2048)])
+def test_gemm_with_a_split_contraction(M, N, K):
+    """bf_op_gemm_splitk: few tiles and a long contraction run K in two slices into fp32 planes that a second kernel adds
+    in order, with each of the epilogues it serves, in both layouts; the result agrees with the unsplit product to the
+    rounding of the output (the fp32 sum associates differently) and with the fp64 product to the bf16 bar."""
+    assert bf.bf_op_gemm_splitk_slices(bf.BF_NN, bf.BF_EPI_BIAS_RES, M, N, K) == 2
+    assert bf.bf_op_gemm_splitk_slices(bf.BF_NT, bf.BF_EPI_NONE, M, N, K) == 2
+    A = bf_inputs.normal(15, 0, (M, K), bf16=True)
+    B = bf_inputs.normal(15, 1, (K, N), 0.05, bf16=True)
+    bias = bf_inputs.normal(15, 2, (N,), 0.5)
+    R = bf_inputs.normal(15, 3, (M, N), bf16=True)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    dA, dB, dBt, dR, dbias = to_dev(A, True), to_dev(B, True), to_dev(np.ascontiguousarray(B.T), True), to_dev(R, True), to_dev(bias, False)
+    planes = torch.full((2 * M * N,), float("nan"), dtype=torch.float32, device="cuda")
+    for layout, Bd in ((bf.BF_NN, dB), (bf.BF_NT, dBt)):
+        for epi, want in ((bf.BF_EPI_NONE, acc), (bf.BF_EPI_BIAS, acc + bias), (bf.BF_EPI_BIAS_RES, acc + bias + R)):
+            out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ref = torch.empty_like(out)
+            bf.bf_op_gemm_splitk(bf.BF_BF16, 0, layout, epi, M, N, K, dA, Bd, out, bias=dbias, R=dR, planes=planes)
+            bf.bf_op_gemm(bf.BF_BF16, 0, layout, epi, M, N, K, dA, Bd, ref, bias=dbias, R=dR)
+            assert rel_err(to_host(out), want) <= TOL["bf16"], (layout, epi)
+            assert rel_err(to_host(out), to_host(ref).astype(np.float64)) <= 2.0 ** -7, (layout, epi)
+            # deterministic: a second call gives the same bits
+            again = torch.empty_like(out)
+            bf.bf_op_gemm_splitk(bf.BF_BF16, 0, layout, epi, M, N, K, dA, Bd, again, bias=dbias, R=dR, planes=planes)
+            assert torch.equal(out, again)
+    # without the scratch, or with too little of it, the call is the plain product
+    out, ref = torch.empty((M, N), dtype=torch.bfloat16, device="cuda"), torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NN, bf.BF_EPI_BIAS, M, N, K, dA, dB, ref, bias=dbias)
+    bf.bf_op_gemm_splitk(bf.BF_BF16, 0, bf.BF_NN, bf.BF_EPI_BIAS, M, N, K, dA, dB, out, bias=dbias, planes=None)
+    assert torch.equal(out, ref)
+    bf.bf_op_gemm_splitk(bf.BF_BF16, 0, bf.BF_NN, bf.BF_EPI_BIAS, M, N, K, dA, dB, out, bias=dbias, planes=planes[:M * N])
+    assert torch.equal(out, ref)
+
+
+def test_split_contraction_is_chosen_only_where_it_pays():
+    s = bf.bf_op_gemm_splitk_slices
+    assert s(bf.BF_NN, bf.BF_EPI_BIAS_RES, 2048, 2048, 2048) == 2
+    assert s(bf.BF_NN, bf.BF_EPI_BIAS_RES, 2048, 2048, 1024) == 1      # contraction too short
+    assert s(bf.BF_NN, bf.BF_EPI_BIAS, 2048, 8192, 8192) == 1          # a full round of tiles already
+    assert s(bf.BF_NT, bf.BF_EPI_NONE, 2048, 6144, 18432) == 1
+    assert s(bf.BF_NN, bf.BF_EPI_BIAS_GELU, 2048, 2048, 8192) == 1     # epilogues with a second output are not split
+    assert s(bf.BF_NT, bf.BF_EPI_GELU_BWD, 2048, 2048, 8192) == 1
+    assert s(bf.BF_TN, bf.BF_EPI_ACCUM, 2048, 2048, 8192) == 1
+    assert s(bf.BF_NN, bf.BF_EPI_NONE, 2000, 2048, 8192) == 1          # not a shape of the matrix-core kernel
+    assert s(bf.BF_NN, bf.BF_EPI_NONE, 2048, 2048, 8192 + 64) == 1     # slices must be whole k-tiles
+
+
 @pytest.mark.parametrize("M,N,K", [(2048, 4096, 512), (4096, 2048, 192), (512, 16384, 128)])
 def test_gemm_mfma_large_tile(M, N, K):
     """Shapes that take the 256 x 256 workgroup tile of the MFMA kernel, all layouts."""
