@@ -143,7 +143,22 @@ RecSizes rec_sizes(const bf_config& c) {
 
 struct TmpSizes { size_t du, dc, dx1, dctx, dqkv, delta, ping, colpart, lnpart, attnpart, splitk, total; };
 
+TmpSizes tmp_sizes_of(const bf_config& c);
+
+// Asked for on every launch that uses the scratch areas: the last answer is kept per thread (a stack's configuration
+// is one object that does not change, so the bytes compare equal from call to call).
 TmpSizes tmp_sizes(const bf_config& c) {
+  static thread_local bool have = false;
+  static thread_local bf_config last_c;
+  static thread_local TmpSizes last_t;
+  if (have && std::memcmp(&last_c, &c, sizeof(bf_config)) == 0) return last_t;
+  last_t = tmp_sizes_of(c);
+  std::memcpy(&last_c, &c, sizeof(bf_config));
+  have = true;
+  return last_t;
+}
+
+TmpSizes tmp_sizes_of(const bf_config& c) {
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
   const size_t T = (size_t)c.S_mb_max * c.S_seq, h = c.S_hidden, f = c.S_mlp;
   TmpSizes t;
