@@ -136,14 +136,15 @@ def step_stats(reports):
     return {"median": 0.5 * (ms[(n - 1) // 2] + ms[n // 2]), "min": ms[0], "max": ms[-1], "n": n}
 
 
-def other_workload(bf, name, steps=3, warmup=1):
+def other_workload(bf, name, steps=3, warmup=1, mb_chains=1):
     """One of the other configurations, BF and DF, a few timed steps after one warm-up: model and executed
-    TFLOP/s, step time, peak checkpoints and activation bytes.  The stack is built and freed here."""
+    TFLOP/s, step time, peak checkpoints and activation bytes.  The stack is built and freed here.
+    mb_chains = 2: the BF step with its micro-batches on two streams (DF is then left out: it runs as one chain)."""
     import torch
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, ckpt = WORKLOADS[name]
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16,
                          ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
-                         fuse_wgrad=1, N_loop_min=N_loop, **EXTRA.get(name, {}))
+                         fuse_wgrad=1, N_loop_min=N_loop, mb_chains=mb_chains, **EXTRA.get(name, {}))
     st = bf.Stack(cfg, device="cuda:0")
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x221105953)
@@ -154,9 +155,11 @@ def other_workload(bf, name, steps=3, warmup=1):
     out = {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]), "N_layers": Lyr, "N_loop": N_loop, "S_hidden": h, "S_mb": S_mb,
            "N_mb": N_mb, "ckpt": ckpt, "steps": steps, "warmup": warmup, "workspace_bytes": int(bf.bf_workspace_bytes(cfg))}
     for tag, sched in (("bf", bf.BF_SCHED_BF), ("df", bf.BF_SCHED_DF)):
+        if mb_chains == 2 and tag == "df":
+            continue
         sec, reps = time_steps(st, bf, sched, N_loop, N_mb, S_mb, x, dy, y, dx, steps, warmup, 1)
         rp = reps[-1]
-        out[tag] = {"ms_per_step": sec * 1e3, "gpu_ms": step_stats(reps), "model_tflops": rp.flops_model / sec / 1e12,
+        out[tag] = {"mb_chains": int(rp.mb_chains), "ms_per_step": sec * 1e3, "gpu_ms": step_stats(reps), "model_tflops": rp.flops_model / sec / 1e12,
                     "frac_bf16_mfma_peak": rp.flops_model / sec / 1e12 / PEAK_BF16_TFLOPS,
                     "executed_tflops": rp.flops_executed / sec / 1e12,
                     "executed_frac_bf16_mfma_peak": rp.flops_executed / sec / 1e12 / PEAK_BF16_TFLOPS,
@@ -223,6 +226,8 @@ def main():
                     help="skip the product timed on random and on zero operands reported under \"power_check\"")
     ap.add_argument("--sweep", choices=["N_mb", "N_loop"],
                     help="instead of the benchmark line: both orders over the micro-batch count or the loop count")
+    ap.add_argument("--mb-chains", type=int, default=1, choices=[1, 2],
+                    help="2: the micro-batches of the BF step on two streams (stacks without S_voc; the dp_fs steps are skipped)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the c2 / c4 / c5 steps (BF and DF) reported under \"other_workloads\" of the default workload")
     args = ap.parse_args()
@@ -240,7 +245,8 @@ def main():
     b16 = dtype == "bf16"
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
                          ckpt_mode=bf.BF_CKPT_LAYER if ckpt == "layer" else bf.BF_CKPT_NONE, lr=1e-5, queue_depth=0,
-                         fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop, **EXTRA.get(args.workload, {}))
+                         fuse_wgrad=0 if args.no_fuse_wgrad else 1, N_loop_min=N_loop, mb_chains=args.mb_chains,
+                         **EXTRA.get(args.workload, {}))
     S_voc = cfg.S_voc
     torch.cuda.set_device(0)
     if args.sweep:
@@ -342,7 +348,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "N_layers": Lyr, "N_loop": N_loop,
                    "S_hidden": h, "N_heads": a, "S_mlp": f, "S_seq": S_seq, "S_mb": S_mb, "N_mb": N_mb,
-                   "schedule": "BF", "ckpt": ckpt, "causal": int(cfg.causal), "S_voc": int(S_voc), "fuse_wgrad": not args.no_fuse_wgrad, "tokens_per_step": N_mb * S_mb * S_seq},
+                   "schedule": "BF", "ckpt": ckpt, "causal": int(cfg.causal), "S_voc": int(S_voc), "fuse_wgrad": not args.no_fuse_wgrad, "mb_chains": int(r.mb_chains), "tokens_per_step": N_mb * S_mb * S_seq},
         "frac_bf16_mfma_peak": value / PEAK_BF16_TFLOPS,
         "paper_eq_tflops": r.flops_paper / sec_bf / 1e12,
         "executed_tflops": r.flops_executed / sec_bf / 1e12,
@@ -359,7 +365,7 @@ def main():
     st.close()
     del st
     torch.cuda.empty_cache()
-    if b16 and not args.no_dp_fs:
+    if b16 and not args.no_dp_fs and args.mb_chains == 1:
         # the same step with the bf16 weights rebuilt per interval of use into a two-stage double buffer
         # (Sec. 3.1, App. D.1): BF rebuilds a stage twice per step, DF twice per micro-batch
         cfg.dp_fs = 1
@@ -385,6 +391,8 @@ def main():
     torch.cuda.empty_cache()
     if args.workload == "c3" and not args.no_other_workloads:
         line["other_workloads"] = {name: other_workload(bf, name) for name in ("c2", "c4", "c5")}
+        # the small stack again with two micro-batches in flight: its kernels do not fill the chip one at a time
+        line["other_workloads"]["c2_two_chains"] = other_workload(bf, "c2", mb_chains=2)
     if b16 and not args.no_power_check and h % 256 == 0:
         line["power_check"] = power_check(bf, h)
     if not args.no_cpu_baseline:

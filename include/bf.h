@@ -100,6 +100,19 @@ typedef struct {
   float init_std;
   float ln_eps;
   float lr, beta1, beta2, adam_eps, weight_decay;  /* Adam, bias-corrected, decoupled decay */
+  int32_t mb_chains;    /* 2: a breadth-first step runs two micro-batches of a stage side by side.  In breadth-first
+                           order every micro-batch of a stage is there before the stage starts and none depends on
+                           another (Sec. 4.1), which depth-first order, with one micro-batch in flight, cannot offer:
+                           even micro-batches run on the caller's stream, odd ones on a second stream of the stack's,
+                           each chain with its own backward temporaries; the chains meet once per stage, for the
+                           stage-wide weight-gradient products and the optimizer step.  Pays where one micro-batch's
+                           kernels do not fill the chip (a 2048-wide model: step 44 -> 38 ms); costs an 8192-wide one
+                           2 to 7 %.  The workspace grows by a second set of backward temporaries and a second fp32
+                           gradient arena of the layers' size.  Needs fuse_wgrad = 1, BF_CKPT_NONE, dp_fs = 0, queue_depth = 0, S_voc = 0, and y and
+                           dx given to bf_run_step; depth-first steps, bf_run_rank_step with N_PP > 1 and steps of
+                           one micro-batch run as with 1.  Bias and LayerNorm gradients are then (sum over even) +
+                           (sum over odd micro-batches): equal to the one-chain result to fp32 rounding, and the
+                           same bits from run to run.  0 or 1: one micro-batch at a time. */
 } bf_config;
 
 /* Integer event trace of a step. op: 0 forward, 1 backward, 2 optimizer (mb = -1).
@@ -151,6 +164,7 @@ typedef struct {
    * BF_CKPT_LAYER also the recomputed operands) of one stage that are kept until the stage's
    * weight-gradient products have run; part of peak_act_bytes. */
   int64_t fused_wgrad_bytes;
+  int64_t mb_chains;        /* micro-batch chains the step ran side by side (1 or 2) */
 } bf_step_report;
 
 typedef struct {

@@ -24,7 +24,8 @@ class bf_config(C.Structure):
                                          "S_mb_max", "dtype", "ckpt_mode", "causal", "kernels", "queue_depth",
                                          "fuse_wgrad", "N_loop_min", "dp_fs", "S_voc")] + \
                [("seed", C.c_uint64)] + \
-               [(n, C.c_float) for n in ("init_std", "ln_eps", "lr", "beta1", "beta2", "adam_eps", "weight_decay")]
+               [(n, C.c_float) for n in ("init_std", "ln_eps", "lr", "beta1", "beta2", "adam_eps", "weight_decay")] + \
+               [("mb_chains", C.c_int32)]
 
 
 class bf_event(C.Structure):
@@ -38,7 +39,7 @@ class bf_step_report(C.Structure):
                [("kernel_ms", C.c_double * 11), ("kernel_flops", C.c_double * 11), ("kernel_bytes", C.c_double * 11),
                 ("kernel_launches", C.c_int64 * 11)] + \
                [(n, C.c_int64) for n in ("n_weight_intervals", "n_reconstruct", "reconstruct_bytes", "weight_buffer_bytes",
-                                         "fused_wgrad_bytes")]
+                                         "fused_wgrad_bytes", "mb_chains")]
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "adam",
@@ -160,10 +161,10 @@ def _stream():
 
 def make_config(S_hidden, N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype=BF_BF16, ckpt_mode=BF_CKPT_NONE,
                 causal=1, kernels=BF_KERNELS_AUTO, queue_depth=0, fuse_wgrad=0, N_loop_min=0, dp_fs=0, S_voc=0, seed=0x221105953, init_std=0.02, ln_eps=1e-5,
-                lr=1e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0):
+                lr=1e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.0, mb_chains=1):
     return bf_config(S_hidden, N_heads, S_hidden // N_heads, S_mlp, S_seq, N_layers, N_mb_max, S_mb_max, dtype,
                      ckpt_mode, causal, kernels, queue_depth, fuse_wgrad, N_loop_min, dp_fs, S_voc, seed, init_std, ln_eps, lr, beta1, beta2, adam_eps,
-                     weight_decay)
+                     weight_decay, mb_chains)
 
 
 def bf_workspace_bytes(cfg):

@@ -149,6 +149,9 @@ bf_status adam_step(size_t n, float* w, float* m, float* v, const float* g, bf16
 bf_status bump_step(int* t_dev, hipStream_t st);
 bf_status cast_f32_to_bf16(size_t n, const float* src, bf16_t* dst, hipStream_t st);
 bf_status fill_f32(size_t n, float* dst, float value, hipStream_t st);
+// dst[l * layer_stride + off[k] + i] += src[same] for l < n_layers, k < n_seg <= 8, i < cnt[k]
+bf_status add_segments(int n_layers, size_t layer_stride, int n_seg, const size_t* off, const size_t* cnt, float* dst,
+                       const float* src, hipStream_t st);
 // N(0, std) from a counter-based hash of (seed, index)
 bf_status init_normal(size_t n, float* dst, uint64_t seed, float std, hipStream_t st);
 

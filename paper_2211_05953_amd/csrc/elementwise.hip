@@ -816,6 +816,32 @@ bf_status fill_f32(size_t n, float* dst, float value, hipStream_t st) {
   return BF_OK;
 }
 
+namespace {
+struct AddSegs { int n; size_t off[8]; size_t cnt[8]; };
+
+// dst += src over up to eight element ranges of each of gridDim.y equally laid out layers
+__global__ __launch_bounds__(256) void add_segments_kernel(size_t layer_stride, AddSegs sg, float* __restrict__ dst,
+                                                           const float* __restrict__ src) {
+  const size_t base = (size_t)blockIdx.y * layer_stride;
+  for (int k = 0; k < sg.n; ++k) {
+    float* d = dst + base + sg.off[k];
+    const float* a = src + base + sg.off[k];
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < sg.cnt[k]; i += (size_t)gridDim.x * 256) d[i] += a[i];
+  }
+}
+}  // namespace
+
+bf_status add_segments(int n_layers, size_t layer_stride, int n_seg, const size_t* off, const size_t* cnt, float* dst,
+                       const float* src, hipStream_t st) {
+  if (n_layers < 1 || n_seg < 1 || n_seg > 8 || !dst || !src) { set_error("add_segments: bad arguments"); return BF_EINVAL; }
+  AddSegs sg{};
+  sg.n = n_seg;
+  for (int k = 0; k < n_seg; ++k) { sg.off[k] = off[k]; sg.cnt[k] = cnt[k]; }
+  add_segments_kernel<<<dim3(16, n_layers), 256, 0, st>>>(layer_stride, sg, dst, src);
+  BF_LAUNCH_CHECK();
+  return BF_OK;
+}
+
 bf_status init_normal(size_t n, float* dst, uint64_t seed, float std, hipStream_t st) {
   if (n == 0) return BF_OK;
   init_normal_kernel<<<grid_for(n, 256), 256, 0, st>>>(n, dst, seed, std);

@@ -88,6 +88,11 @@ bool valid_config(const bf_config* c) {
   if (c->dp_fs && c->dtype != BF_BF16) { set_error("config: dp_fs reconstructs bf16 weights: dtype must be BF_BF16"); return false; }
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
   if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
+  if (c->mb_chains < 0 || c->mb_chains > 2) { set_error("config: mb_chains must be 0, 1 or 2"); return false; }
+  if (c->mb_chains == 2 && (c->fuse_wgrad != 1 || c->ckpt_mode != BF_CKPT_NONE || c->dp_fs || c->queue_depth || c->S_voc)) {
+    set_error("config: mb_chains = 2 needs fuse_wgrad = 1, BF_CKPT_NONE, dp_fs = 0, queue_depth = 0 and S_voc = 0");
+    return false;
+  }
   return true;
 }
 
@@ -118,6 +123,8 @@ struct WsLayout {
   size_t n_full_records;
   size_t off_ckpt;         // LAYER: L * N_mb_max [T, h] tensors (outputs of each layer)
   size_t off_tmp;          // backward temporaries
+  size_t off_tmp2;         // mb_chains = 2: the second chain's backward temporaries
+  size_t off_g32b;         // mb_chains = 2: where the second chain accumulates its bias / LayerNorm gradients
   size_t off_grec;         // fused weight gradient: (layers per stage) * N_mb_max records {dy, du, dx1, dqkv}
   size_t grec_bytes;
   size_t off_wrec;         // with checkpointing: as many records {a, ctx, c, g}, the recomputed wgrad operands
@@ -231,6 +238,11 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
     off += slots * Lo->y_bytes;
   }
   Lo->off_tmp = off; off += tmp_sizes(c).total;
+  Lo->off_tmp2 = Lo->off_g32b = 0;
+  if (c.mb_chains == 2) {
+    Lo->off_tmp2 = off; off += tmp_sizes(c).total;
+    Lo->off_g32b = off; off += up(Lo->P_layers * 4);
+  }
   {
     TmpSizes t = tmp_sizes(c);
     RecSizes r = rec_sizes(c);
@@ -289,6 +301,13 @@ struct bf_stack {
                           // optimizer step: a step recorded in a HIP graph keeps counting when replayed
   bool have_grads;
   int device;
+  // mb_chains = 2: the chain (0 or 1) whose op is being issued selects the backward temporaries and the arena the
+  // bias / LayerNorm gradients go to; the second chain's stream; events for the fork at the start of a step, the two
+  // directions of the meeting at a stage's end and the join at the step's end
+  int chain;
+  float* g32b;
+  hipStream_t chain_st;
+  hipEvent_t ev_chain[4];
 };
 
 namespace bf {
@@ -368,7 +387,7 @@ void redirect_wgrad_operands(bf_stack* s, int ls, int mb, Record* R) {
 Tmp tmp_of(bf_stack* s) {
   TmpSizes t = tmp_sizes(s->cfg);
   Tmp T;
-  char* p = s->ws + s->Lo.off_tmp;
+  char* p = s->ws + (s->chain ? s->Lo.off_tmp2 : s->Lo.off_tmp);
   T.du = p; p += t.du; T.dc = p; p += t.dc; T.dx1 = p; p += t.dx1; T.dctx = p; p += t.dctx; T.dqkv = p; p += t.dqkv;
   T.delta = (float*)p; p += t.delta; T.ping[0] = p; p += t.ping; T.ping[1] = p; p += t.ping; T.colpart = (float*)p; p += t.colpart; T.lnpart = (float*)p; p += t.lnpart;
   T.attnpart = t.attnpart ? (float*)p : nullptr;
@@ -493,7 +512,9 @@ bf_status layer_backward(bf_stack* s, int layer, int S_mb, const void* x, const 
   char* dx1 = keep ? keep->dx1 : t.dx1;
   char* dqkv = keep ? keep->dqkv : t.dqkv;
   auto P = [&](int tid) { return param_ptr(s, s->w32, layer, tid); };
-  auto G = [&](int tid) { return param_ptr(s, s->g32, layer, tid); };
+  // the second chain of a two-chain step sums its bias / LayerNorm gradients in an arena of its own
+  if (s->chain && !keep) { set_error("layer_backward: the second chain takes no weight-matrix gradients"); return BF_ESTATE; }
+  auto G = [&](int tid) { return param_ptr(s, s->chain ? s->g32b : s->g32, layer, tid); };
   GemmArgs g{};
   // y = x1 + gelu(u) W_fc2 + b_fc2
   if (!keep) {
@@ -633,6 +654,10 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   s->prof_mask = 0;
   s->side = nullptr;
   s->ev_grad_ready = s->ev_side_done = s->ev_t0 = s->ev_t1 = nullptr;
+  s->chain = 0;
+  s->g32b = cfg->mb_chains == 2 ? (float*)(s->ws + s->Lo.off_g32b) : nullptr;
+  s->chain_st = nullptr;
+  for (auto& e : s->ev_chain) e = nullptr;
   hipStream_t st = (hipStream_t)stream;
   auto fail = [&](bf_status code) { bf_destroy_stack(s); return code; };
 #define CK(expr)                                                                                  \
@@ -646,6 +671,10 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
   CK(hipEventCreateWithFlags(&s->ev_side_done, hipEventDisableTiming));
   CK(hipEventCreate(&s->ev_t0));
   CK(hipEventCreate(&s->ev_t1));
+  if (cfg->mb_chains == 2) {
+    CK(hipStreamCreateWithFlags(&s->chain_st, hipStreamNonBlocking));
+    for (auto& e : s->ev_chain) CK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  }
   if (cfg->dp_fs)
     for (int i = 0; i < 2; ++i) {
       CK(hipEventCreateWithFlags(&s->fs_ready[i], hipEventDisableTiming));
@@ -695,6 +724,8 @@ bf_status bf_create_stack(const bf_config* cfg, void* workspace, size_t bytes, v
 bf_status bf_destroy_stack(bf_stack* s) {
   if (!s) return BF_OK;
   if (s->side) { (void)hipStreamSynchronize(s->side); (void)hipStreamDestroy(s->side); }
+  if (s->chain_st) { (void)hipStreamSynchronize(s->chain_st); (void)hipStreamDestroy(s->chain_st); }
+  for (hipEvent_t e : s->ev_chain) if (e) (void)hipEventDestroy(e);
   hipEvent_t evs[8] = {s->ev_grad_ready, s->ev_side_done, s->ev_t0, s->ev_t1,
                        s->fs_ready[0], s->fs_ready[1], s->fs_free[0], s->fs_free[1]};
   for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
@@ -829,6 +860,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   const size_t es = c.dtype == BF_BF16 ? 2 : 4;
   const int per_stage = c.N_layers / N_loop;
   const size_t mb_bytes = (size_t)S_mb * c.S_seq * c.S_hidden * es;
+  s->chain = 0;
   Tmp tmp = tmp_of(s);
   // gradient hand-off between stages: stage j reads set j & 1 and writes set (j - 1) & 1, so the
   // gradients a stage received stay intact until its fused weight-gradient products have run
@@ -853,6 +885,13 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     dx = nullptr;
   }
   const bool fuse = schedule == BF_SCHED_BF && fuse_wgrad_possible(c) && per_stage <= lps_max(c);
+  // Two chains: micro-batch m runs on stream m & 1, so two micro-batches of a stage are in flight side by side and a
+  // kernel with fewer workgroups than the chip has compute units shares it with the other chain's.  Micro-batches
+  // of one stage are independent of each other in both directions (Sec. 4.2), which is what breadth-first order
+  // leaves room for; depth-first order, the input / output layers, stages that do not feed each other and steps
+  // without caller buffers for the outputs (they would share one scratch tensor) run as one chain.
+  const int chains = c.mb_chains == 2 && fuse && chained && !lm && N_mb >= 2 && y && dx ? 2 : 1;
+  auto stream_of = [&](int m) { return chains == 2 && (m & 1) ? s->chain_st : st; };
   if (c.dp_fs && per_stage > lps_max(c)) {
     set_error("bf_run_step: dp_fs holds stages of up to %d layers (N_loop_min = %d), N_loop = %d gives %d", lps_max(c),
               c.N_loop_min, N_loop, per_stage);
@@ -920,6 +959,11 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   int64_t peak_live = 0;
   size_t n_adam = 0, qi = 0;
   if (timing) BF_HIP_CHECK(hipEventRecord(s->ev_t0, st));
+  if (chains == 2) {
+    // the second chain starts after everything the caller's stream holds so far
+    BF_HIP_CHECK(hipEventRecord(s->ev_chain[0], st));
+    BF_HIP_CHECK(hipStreamWaitEvent(s->chain_st, s->ev_chain[0], 0));
+  }
 
   // where a stage meets the caller's buffers: the first layer's input and outgoing gradient, the
   // last layer's output and incoming gradient (chained: only the rank's first and last layer)
@@ -934,11 +978,15 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   for (size_t oi = 0; oi < ops.size(); ++oi) {
     const SchedOp& op = ops[oi];
     const int ls = local(op), l0 = ls * per_stage, l1 = l0 + per_stage, m = op.mb;
+    // the stream this op is issued on, and with it the set of temporaries and the arena of the small gradients
+    hipStream_t os = stream_of(m);
+    s->chain = chains == 2 ? m & 1 : 0;
+    const int first = m < chains ? 0 : 1;  // 0: the chain's first micro-batch overwrites its gradient sums
     if (c.dp_fs && (oi == 0 || iv_of[oi] != iv_of[oi - 1])) {
       // a new interval starts: its weights must have arrived, and the next interval's are sent for
       const int j = iv_of[oi];
       if (j == 0 && ivs[0].load) BF_TRY(reconstruct(0));
-      if (ivs[j].load) BF_HIP_CHECK(hipStreamWaitEvent(st, s->fs_ready[ivs[j].half], 0));
+      if (ivs[j].load) BF_HIP_CHECK(hipStreamWaitEvent(os, s->fs_ready[ivs[j].half], 0));
       s->fs_cur = ivs[j].half;
       s->fs_cur_l0 = l0;
       if (j + 1 < (int)ivs.size() && ivs[j + 1].load) BF_TRY(reconstruct(j + 1));
@@ -946,17 +994,17 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     if (op.op == 0) {
       if (lm && l0 == 0) {
         if (m == 0)  // the token rows' gradients are added to, use by use: start from zero
-          BF_TRY(fill_f32(s->D.voc_elems[0], param_ptr(s, s->g32, 0, BF_E_TOK), 0.f, st));
-        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (8.0 + es), st, [&] {
+          BF_TRY(fill_f32(s->D.voc_elems[0], param_ptr(s, s->g32, 0, BF_E_TOK), 0.f, os));
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (8.0 + es), os, [&] {
           return embedding_fwd(c.dtype, T_mb, c.S_seq, c.S_voc, c.S_hidden, lm->tokens + (size_t)m * T_mb,
-                               param_ptr(s, s->w32, 0, BF_E_TOK), param_ptr(s, s->w32, 0, BF_E_POS), emb_x(m), st);
+                               param_ptr(s, s->w32, 0, BF_E_TOK), param_ptr(s, s->w32, 0, BF_E_POS), emb_x(m), os);
         }));
       }
       for (int l = l0; l < l1; ++l) {
         Record R = record_for(s, l, m);
         void* out = R.y;
         if (is_top(l)) out = lm ? y_top : y ? (char*)y + io_off(ls, m) : scratch_out;
-        BF_TRY(layer_forward(s, l, S_mb, input_of(l, m), R, out, false, st));
+        BF_TRY(layer_forward(s, l, S_mb, input_of(l, m), R, out, false, os));
         ++live;
       }
       if (lm && l1 == c.N_layers) {
@@ -964,19 +1012,19 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         const int h = c.S_hidden, V = c.S_voc;
         float* gw = param_ptr(s, s->g32, 0, BF_W_OUT);
         BF_TRY(p_ln_fwd(s, T_mb, h, y_top, param_ptr(s, s->w32, 0, BF_LNF_G), param_ptr(s, s->w32, 0, BF_LNF_B), c.ln_eps, hn,
-                        lnf_stats, st));
+                        lnf_stats, os));
         GemmArgs g{T_mb, V, h, hn, weight_ptr(s, 0, BF_W_OUT), logits, nullptr, nullptr, nullptr, 0};
-        BF_TRY(p_gemm(s, L_NT, E_NONE, g, st));
+        BF_TRY(p_gemm(s, L_NT, E_NONE, g, os));
         const float scale = 1.0f / ((float)N_mb * (float)T_mb);
-        BF_TRY(timed(s, BF_K_VOCAB, 0.0, 3.0 * es * T_mb * V, st, [&] {
-          return ce_loss(c.dtype, T_mb, V, logits, lm->labels + (size_t)m * T_mb, scale, row_loss, lm->loss + m, st);
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, 3.0 * es * T_mb * V, os, [&] {
+          return ce_loss(c.dtype, T_mb, V, logits, lm->labels + (size_t)m * T_mb, scale, row_loss, lm->loss + m, os);
         }));
         g = GemmArgs{T_mb, h, V, logits, weight_ptr(s, 0, BF_W_OUT), dhn, nullptr, nullptr, nullptr, 0};
-        BF_TRY(p_gemm(s, L_NN, E_NONE, g, st));
+        BF_TRY(p_gemm(s, L_NN, E_NONE, g, os));
         g = GemmArgs{V, h, T_mb, logits, hn, gw, nullptr, nullptr, nullptr, m > 0};
-        BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, st));
+        BF_TRY(p_gemm(s, L_TN, E_ACCUM, g, os));
         BF_TRY(p_ln_bwd(s, T_mb, h, dhn, y_top, param_ptr(s, s->w32, 0, BF_LNF_G), lnf_stats, nullptr, dy_lm(m),
-                        param_ptr(s, s->g32, 0, BF_LNF_G), param_ptr(s, s->g32, 0, BF_LNF_B), nullptr, m > 0, st));
+                        param_ptr(s, s->g32, 0, BF_LNF_G), param_ptr(s, s->g32, 0, BF_LNF_B), nullptr, m > 0, os));
       }
     } else {
       for (int l = l1 - 1; l >= l0; --l) {
@@ -984,7 +1032,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         const void* xin = input_of(l, m);
         if (c.ckpt_mode == BF_CKPT_LAYER) {
           if (fuse) redirect_wgrad_operands(s, l - l0, m, &R);
-          BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, st));
+          BF_TRY(layer_forward(s, l, S_mb, xin, R, nullptr, true, os));
         }
         // gradient in: caller's dy for the last layer, the hand-off buffer at a stage top, else the ping-pong
         // (with the fused weight gradient every layer's incoming gradient is kept per micro-batch instead)
@@ -1001,18 +1049,23 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         // A layer whose incoming gradient was written by the layer above on this rank (everything but the top of
         // the chain, or of a stage when the stages do not feed each other) has had its FC2 bias gradient taken there.
         const bool fed_from_above = !is_top(l);
-        float* below = is_bottom(l) ? nullptr : param_ptr(s, s->g32, l - 1, BF_B_FC2);
-        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, m > 0, fuse ? &keep : nullptr, fed_from_above, below, st));
+        float* below = is_bottom(l) ? nullptr : param_ptr(s, s->chain ? s->g32b : s->g32, l - 1, BF_B_FC2);
+        BF_TRY(layer_backward(s, l, S_mb, xin, R, din, dout, first, fuse ? &keep : nullptr, fed_from_above, below, os));
         --live;
       }
       if (lm && l0 == 0) {
         char* dxe = scratch_out + s->Lo.y_bytes;  // where layer 0 left the gradient of its input
-        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (es + 16.0), st, [&] {
+        BF_TRY(timed(s, BF_K_VOCAB, 0.0, (double)T_mb * c.S_hidden * (es + 16.0), os, [&] {
           return embedding_bwd(c.dtype, S_mb, c.S_seq, c.S_voc, c.S_hidden, lm->tokens + (size_t)m * T_mb, dxe,
-                               param_ptr(s, s->g32, 0, BF_E_TOK), param_ptr(s, s->g32, 0, BF_E_POS), m > 0, st);
+                               param_ptr(s, s->g32, 0, BF_E_TOK), param_ptr(s, s->g32, 0, BF_E_POS), m > 0, os);
         }));
       }
       if (fuse && m == N_mb - 1) {
+        if (chains == 2) {
+          // the stage's last micro-batch: wait for the other chain's, which the products below read
+          BF_HIP_CHECK(hipEventRecord(s->ev_chain[1], stream_of(m + 1)));
+          BF_HIP_CHECK(hipStreamWaitEvent(os, s->ev_chain[1], 0));
+        }
         // every micro-batch of the stage is through: one weight-gradient product per matrix
         for (int l = l1 - 1; l >= l0; --l) {
           const void* dy0;
@@ -1020,7 +1073,18 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
           if (is_top(l)) { dy0 = (const char*)dy + io_off(ls, 0); stride = io_stride / es; }
           else if (l == l1 - 1) { dy0 = bhand(ls, 0); stride = s->Lo.y_bytes / es; }
           else { dy0 = grad_rec(s, l - l0, 0).dy; stride = s->Lo.grec_bytes / es; }
-          BF_TRY(layer_wgrad_fused(s, l, l - l0, S_mb, N_mb, dy0, stride, st));
+          BF_TRY(layer_wgrad_fused(s, l, l - l0, S_mb, N_mb, dy0, stride, os));
+        }
+        if (chains == 2) {
+          // the two chains' bias / LayerNorm gradient sums become one, always in this order
+          const int small[8] = {BF_LN1_G, BF_LN1_B, BF_B_QKV, BF_B_O, BF_LN2_G, BF_LN2_B, BF_B_FC1, BF_B_FC2};
+          size_t off[8], cnt[8];
+          for (int k = 0; k < 8; ++k) { off[k] = s->D.tensor_off[small[k]]; cnt[k] = s->D.tensor_elems[small[k]]; }
+          const size_t lo = (size_t)l0 * s->D.layer_elems;
+          BF_TRY(add_segments(per_stage, s->D.layer_elems, 8, off, cnt, s->g32 + lo, s->g32b + lo, os));
+          // the next stage's backward reuses the buffers those products read: the other chain goes on only now
+          BF_HIP_CHECK(hipEventRecord(s->ev_chain[2], os));
+          BF_HIP_CHECK(hipStreamWaitEvent(stream_of(m + 1), s->ev_chain[2], 0));
         }
       }
     }
@@ -1036,7 +1100,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
         // hold every compute unit, so the two do not overlap but take turns, a product that shares
         // the chip with the update's workgroups runs in more rounds, and under the power limit an
         // overlap would buy nothing anyway.  Measured: 1 % at C3, 7 % at the bidirectional workload.)
-        hipStream_t as = st;
+        hipStream_t as = os;
         if (timing) BF_HIP_CHECK(hipEventRecord(s->adam_ev[2 * n_adam], as));
         BF_TRY(timed(s, BF_K_ADAM, 0.0, (double)n * (s->wlp ? 30.0 : 28.0), as, [&] {
           return adam_step(n, s->w32 + off, s->m + off, s->v + off, s->g32 + off, s->wlp ? s->wlp + off : nullptr, s->step,
@@ -1066,9 +1130,15 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
       // bounded launch queue (App. D.2): wait for the op issued queue_depth ops ago
       hipEvent_t e = s->queue_ev[qi % s->queue_ev.size()];
       if (qi >= s->queue_ev.size()) BF_HIP_CHECK(hipEventSynchronize(e));
-      BF_HIP_CHECK(hipEventRecord(e, st));
+      BF_HIP_CHECK(hipEventRecord(e, os));
       ++qi;
     }
+  }
+  s->chain = 0;
+  if (chains == 2) {
+    // the step ends on the caller's stream
+    BF_HIP_CHECK(hipEventRecord(s->ev_chain[3], s->chain_st));
+    BF_HIP_CHECK(hipStreamWaitEvent(st, s->ev_chain[3], 0));
   }
   if (apply_optimizer && schedule == BF_SCHED_BF) {
     BF_HIP_CHECK(hipEventRecord(s->ev_side_done, s->side));
@@ -1113,6 +1183,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     report->reconstruct_bytes = n_recon * 6 * (int64_t)per_stage * (int64_t)s->D.layer_elems;
     report->weight_buffer_bytes = c.dp_fs ? 2 * (int64_t)s->Lo.half_bytes : 0;
     report->n_events = (int32_t)s->trace.size();
+    report->mb_chains = chains;
   }
   if (timing) {
     BF_HIP_CHECK(hipEventRecord(s->ev_t1, st));

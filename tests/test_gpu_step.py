@@ -204,6 +204,95 @@ def test_optimizer_step_after_the_fused_weight_gradient(mode, dtype, Lyr, N_loop
                     assert moved.min() > 0.5 * adam["lr"] and moved.max() < 1.5 * adam["lr"], (l, name)
 
 
+MATRICES = ("W_qkv", "W_o", "W_fc1", "W_fc2")
+
+
+@pytest.mark.parametrize("mode,dtype,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", [
+    ("fp32", bf.BF_FP32, 3, 3, 72, 3, 200, 50, 2, 3),          # generic kernels, odd N_mb
+    ("fp32", bf.BF_FP32, 4, 2, 256, 4, 1024, 128, 1, 2),       # one micro-batch per chain
+    ("bf16", bf.BF_BF16, 4, 2, 256, 2, 1024, 256, 1, 4),       # MFMA kernels
+    ("bf16", bf.BF_BF16, 4, 4, 512, 4, 2048, 128, 2, 5),
+    ("bf16", bf.BF_BF16, 4, 1, 256, 2, 1024, 256, 1, 3),       # one stage
+])
+def test_two_chains_of_micro_batches_side_by_side(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+    """mb_chains = 2: the micro-batches of a breadth-first step run on two streams (Sec. 4.2: within a stage
+    they do not depend on each other).  Outputs and weight-matrix gradients are those of the one-chain step
+    bit for bit, the bias / LayerNorm gradients are two partial sums added in a fixed order (equal up to fp32
+    rounding, the same bits on every run), and everything matches the oracle."""
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(19, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(19, N_mb, S_mb, S_seq, h, bf16=b16)
+    mk = lambda chains: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, mb_chains=chains)
+    assert bf.bf_workspace_bytes(mk(2)) > bf.bf_workspace_bytes(mk(1)) == bf.bf_workspace_bytes(mk(0))
+    ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a)
+    two = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    again = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    one = _run_gpu(mk(1), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
+    assert two["report"].mb_chains == 2 and one["report"].mb_chains == 1
+    _compare(two, ref, TOL[mode], Lyr)
+    assert np.array_equal(two["y"], one["y"]) and np.array_equal(two["dx"], one["dx"])
+    assert np.array_equal(two["y"], again["y"]) and np.array_equal(two["dx"], again["dx"])
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            assert np.array_equal(two["grads"][l][name], again["grads"][l][name]), (l, name)
+            if name in MATRICES:
+                assert np.array_equal(two["grads"][l][name], one["grads"][l][name]), (l, name)
+            else:
+                assert rel_err(two["grads"][l][name], one["grads"][l][name]) <= 2e-6, (l, name)
+    assert two["trace"] == one["trace"] == [tuple(e) for e in ref["trace"]]
+    assert two["report"].peak_ckpt_count == one["report"].peak_ckpt_count
+    # depth-first order has one micro-batch in flight per stage visit: the flag changes nothing there
+    df2 = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_DF, N_loop, N_mb, S_mb)
+    df1 = _run_gpu(mk(1), params, x, dy, bf.BF_SCHED_DF, N_loop, N_mb, S_mb)
+    assert df2["report"].mb_chains == 1
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            assert np.array_equal(df2["grads"][l][name], df1["grads"][l][name]), (l, name)
+    # a single micro-batch leaves nothing to run beside it
+    solo = _run_gpu(mk(2), params, x[:1], dy[:1], bf.BF_SCHED_BF, N_loop, 1, S_mb)
+    solo1 = _run_gpu(mk(1), params, x[:1], dy[:1], bf.BF_SCHED_BF, N_loop, 1, S_mb)
+    assert solo["report"].mb_chains == 1
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            assert np.array_equal(solo["grads"][l][name], solo1["grads"][l][name]), (l, name)
+
+
+@pytest.mark.parametrize("mode,dtype,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", [
+    ("fp32", bf.BF_FP32, 3, 3, 72, 3, 200, 50, 2, 3),
+    ("bf16", bf.BF_BF16, 4, 2, 256, 2, 1024, 256, 1, 4),
+])
+def test_optimizer_steps_with_two_chains(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+    """Two steps with the per-stage update between the chains' work: the update of a stage runs while the other
+    chain is already in the stage below, and the next step's forward must see every updated weight."""
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(23, Lyr, h, f, bf16=b16)
+    x, dy = bf_inputs.make_batch(23, N_mb, S_mb, S_seq, h, bf16=b16)
+    adam = {k: float(np.float32(v)) for k, v in dict(lr=1e-3, beta1=0.9, beta2=0.999, adam_eps=1e-8, weight_decay=0.01).items()}
+    mk = lambda chains: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, lr=adam["lr"],
+                                       weight_decay=adam["weight_decay"], fuse_wgrad=1, mb_chains=chains)
+    for steps in (1, 2):
+        two = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        again = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        one = _run_gpu(mk(1), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, apply_optimizer=1, steps=steps)
+        ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a, adam=adam, steps=steps)
+        assert two["report"].mb_chains == 2
+        tol = TOL[mode] * (1 if steps == 1 else 20)
+        for l in range(Lyr):
+            for name in bf.TENSOR_IDS:
+                g_ref = ref["grads"][l][name].reshape(-1)
+                m_ref, v_ref = (t.reshape(-1) for t in ref["new_adam_state"][l][name])
+                assert rel_err(two["grads"][l][name], g_ref) <= tol, (steps, l, name)
+                assert rel_err(two["m"][l][name], m_ref) <= tol, (steps, l, name)
+                assert rel_err(two["v"][l][name], v_ref) <= 2 * tol, (steps, l, name)
+                for k in ("grads", "params", "m", "v"):
+                    assert np.array_equal(two[k][l][name], again[k][l][name]), (steps, k, l, name)
+                if steps == 1 and name in MATRICES:
+                    for k in ("grads", "params", "m", "v"):
+                        assert np.array_equal(two[k][l][name], one[k][l][name]), (k, l, name)
+                elif steps == 1:
+                    assert rel_err(two["m"][l][name], one["m"][l][name]) <= 1e-5, (l, name)
+
+
 def test_run_step_argument_errors():
     cfg = bf.make_config(64, 2, 256, 16, 4, 2, 1, dtype=bf.BF_FP32)
     st = bf.Stack(cfg)
