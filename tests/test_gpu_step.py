@@ -539,16 +539,17 @@ def test_randomly_drawn_pipeline_ranks(c):
     test_rank_of_a_deeper_pipeline_matches_oracle(*c)
 
 
-@pytest.mark.parametrize("schedule", [bf.BF_SCHED_BF, bf.BF_SCHED_DF])
-def test_gradient_step_replays_from_a_hip_graph(schedule):
+@pytest.mark.parametrize("schedule,chains", [(bf.BF_SCHED_BF, 1), (bf.BF_SCHED_DF, 1), (bf.BF_SCHED_BF, 2)])
+def test_gradient_step_replays_from_a_hip_graph(schedule, chains):
     """With timing = 0 and queue_depth = 0 a step is kernel launches and event record / wait only
     (everything pre-allocated, App. D.2; buffers cleared by fill kernels): it can be captured into a HIP graph.
     Three replays, with unrelated eager work and synchronisations in between, each bit-identical to the
-    eager step."""
+    eager step.  With two chains of micro-batches the second stream forks from the captured one at the start of
+    the step and joins it at the end, so the recording holds both."""
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 3
     params = bf_inputs.make_params(29, Lyr, h, f, bf16=True)
     x, dy = bf_inputs.make_batch(29, N_mb, S_mb, S_seq, h, bf16=True)
-    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=0)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=0, mb_chains=chains)
     st = bf.Stack(cfg)
     for l, p in enumerate(params):
         for name, tid in bf.TENSOR_IDS.items():
