@@ -391,8 +391,10 @@ def main():
     torch.cuda.empty_cache()
     if args.workload == "c3" and not args.no_other_workloads:
         line["other_workloads"] = {name: other_workload(bf, name) for name in ("c2", "c4", "c5")}
-        # the small stack again with two micro-batches in flight: its kernels do not fill the chip one at a time
+        # the small stack and the 6144-wide one (192 tiles on 256 compute units in five of its eight products per
+        # layer) again with two micro-batches in flight: their kernels do not fill the chip one at a time
         line["other_workloads"]["c2_two_chains"] = other_workload(bf, "c2", mb_chains=2)
+        line["other_workloads"]["c5_two_chains"] = other_workload(bf, "c5", mb_chains=2)
     if b16 and not args.no_power_check and h % 256 == 0:
         line["power_check"] = power_check(bf, h)
     if not args.no_cpu_baseline:

@@ -89,8 +89,8 @@ bool valid_config(const bf_config* c) {
   if ((int64_t)c->S_mb_max * c->S_seq > (1 << 24)) { set_error("config: S_mb_max * S_seq too large"); return false; }
   if (!(c->ln_eps > 0.f) || !(c->init_std >= 0.f)) { set_error("config: ln_eps must be > 0, init_std >= 0"); return false; }
   if (c->mb_chains < 0 || c->mb_chains > 2) { set_error("config: mb_chains must be 0, 1 or 2"); return false; }
-  if (c->mb_chains == 2 && (c->fuse_wgrad != 1 || c->ckpt_mode != BF_CKPT_NONE || c->dp_fs || c->queue_depth || c->S_voc)) {
-    set_error("config: mb_chains = 2 needs fuse_wgrad = 1, BF_CKPT_NONE, dp_fs = 0, queue_depth = 0 and S_voc = 0");
+  if (c->mb_chains == 2 && (c->fuse_wgrad != 1 || c->dp_fs || c->queue_depth || c->S_voc)) {
+    set_error("config: mb_chains = 2 needs fuse_wgrad = 1, dp_fs = 0, queue_depth = 0 and S_voc = 0");
     return false;
   }
   return true;
@@ -232,8 +232,8 @@ void fill_layout(const bf_config& c, const Dims& D, WsLayout* Lo) {
     off += slots * (Lo->rec_bytes + Lo->y_bytes);
     Lo->off_ckpt = off;
   } else {
-    Lo->n_full_records = 1;
-    off += Lo->rec_bytes;
+    Lo->n_full_records = c.mb_chains == 2 ? 2 : 1;  // one scratch record per chain of micro-batches
+    off += Lo->n_full_records * Lo->rec_bytes;
     Lo->off_ckpt = off;
     off += slots * Lo->y_bytes;
   }
@@ -348,7 +348,8 @@ Record record_at(bf_stack* s, char* base) {
   return R;
 }
 
-// Record used by (layer, mb): its own slot without checkpointing, the shared scratch record with.
+// Record used by (layer, mb): its own slot without checkpointing, the scratch record (of the chain that is
+// being issued) with.
 Record record_for(bf_stack* s, int layer, int mb) {
   if (s->cfg.ckpt_mode == BF_CKPT_NONE) {
     const size_t slot = (size_t)layer * s->cfg.N_mb_max + mb;
@@ -357,7 +358,7 @@ Record record_for(bf_stack* s, int layer, int mb) {
     R.y = base + s->Lo.rec_bytes;
     return R;
   }
-  Record R = record_at(s, s->ws + s->Lo.off_records);
+  Record R = record_at(s, s->ws + s->Lo.off_records + (s->chain ? s->Lo.rec_bytes : 0));
   R.y = s->ws + s->Lo.off_ckpt + ((size_t)layer * s->cfg.N_mb_max + mb) * s->Lo.y_bytes;
   return R;
 }
@@ -1165,7 +1166,7 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
     const double frac = (double)S_mb / c.S_mb_max;
     const int64_t rec_live = (int64_t)((double)(s->Lo.rec_bytes) * frac) + (int64_t)mb_bytes;
     report->peak_act_bytes = c.ckpt_mode == BF_CKPT_NONE ? peak_live * rec_live
-                                                         : peak_live * (int64_t)mb_bytes + (int64_t)((double)s->Lo.rec_bytes * frac);
+                                                         : peak_live * (int64_t)mb_bytes + chains * (int64_t)((double)s->Lo.rec_bytes * frac);
     // The fused weight gradient keeps, per layer of the stage and micro-batch, the gradients {dy, du, dx1, dqkv}
     // (with checkpointing also the recomputed operands {a, ctx, c, g}) until the stage's products have run.  The
     // last stage's set is complete while every stored activation of the step is still alive, so it adds to the peak.

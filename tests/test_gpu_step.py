@@ -214,15 +214,18 @@ MATRICES = ("W_qkv", "W_o", "W_fc1", "W_fc2")
     ("bf16", bf.BF_BF16, 4, 4, 512, 4, 2048, 128, 2, 5),
     ("bf16", bf.BF_BF16, 4, 1, 256, 2, 1024, 256, 1, 3),       # one stage
 ])
-def test_two_chains_of_micro_batches_side_by_side(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb):
+@pytest.mark.parametrize("ckpt", [bf.BF_CKPT_NONE, bf.BF_CKPT_LAYER])
+def test_two_chains_of_micro_batches_side_by_side(mode, dtype, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, ckpt):
     """mb_chains = 2: the micro-batches of a breadth-first step run on two streams (Sec. 4.2: within a stage
-    they do not depend on each other).  Outputs and weight-matrix gradients are those of the one-chain step
+    they do not depend on each other), with stored activations or with per-layer checkpoints (then each chain
+    recomputes into a record of its own).  Outputs and weight-matrix gradients are those of the one-chain step
     bit for bit, the bias / LayerNorm gradients are two partial sums added in a fixed order (equal up to fp32
     rounding, the same bits on every run), and everything matches the oracle."""
     b16 = dtype == bf.BF_BF16
     params = bf_inputs.make_params(19, Lyr, h, f, bf16=b16)
     x, dy = bf_inputs.make_batch(19, N_mb, S_mb, S_seq, h, bf16=b16)
-    mk = lambda chains: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, mb_chains=chains)
+    mk = lambda chains: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, mb_chains=chains,
+                                       ckpt_mode=ckpt)
     assert bf.bf_workspace_bytes(mk(2)) > bf.bf_workspace_bytes(mk(1)) == bf.bf_workspace_bytes(mk(0))
     ref = _oracle(params, x, dy, K.SCHED_BF, N_loop, a)
     two = _run_gpu(mk(2), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)

@@ -119,13 +119,14 @@ def test_product_package_does_not_import_the_oracle():
 
 
 def test_two_chain_configurations_are_validated_without_a_device():
-    """mb_chains = 2 goes with the fused weight gradient, stored activations, resident weights, no launch
+    """mb_chains = 2 goes with the fused weight gradient, resident weights, no launch
     queue and no input / output layers; anything else is refused when the workspace is sized."""
     import paper_2211_05953_amd as bf
     ok = dict(dtype=bf.BF_BF16, fuse_wgrad=1, mb_chains=2)
     base = bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, dtype=bf.BF_BF16, fuse_wgrad=1))
     assert bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, **ok)) > base > 0
-    for bad in (dict(fuse_wgrad=0), dict(ckpt_mode=bf.BF_CKPT_LAYER), dict(dp_fs=1, N_loop_min=4), dict(queue_depth=4),
+    for bad in (dict(fuse_wgrad=0), dict(dp_fs=1, N_loop_min=4), dict(queue_depth=4),
                 dict(S_voc=512), dict(mb_chains=3), dict(mb_chains=-1)):
         assert bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, **{**ok, **bad})) == 0, bad
         assert "mb_chains" in bf.binding.last_error(), bad
+    assert bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, ckpt_mode=bf.BF_CKPT_LAYER, **ok)) > 0
