@@ -127,6 +127,14 @@ def power_check(bf, h):
     return out
 
 
+T_START = time.time()
+
+
+def note(msg):
+    """A progress line on stderr (stdout carries the one JSON line): a run of some minutes should not look hung."""
+    print("bench.py [%5.0f s] %s" % (time.time() - T_START, msg), file=sys.stderr, flush=True)
+
+
 def step_stats(reports):
     """Median, minimum and maximum of the per-step device times (events around each step on its stream)."""
     ms = sorted(rp.gpu_ms for rp in reports if rp.timed)
@@ -286,13 +294,16 @@ def main():
     # The timed region: the step as it runs in production (Adam of a stage as soon as its gradient is
     # final), with HIP events around the weight-gradient products only, the
     # class with the most time (timing 3: 64 events per step at C3 instead of 2000 and more).
+    note("%s: breadth-first, %d warm-up + %d timed steps" % (args.workload, args.warmup, args.steps))
     sec_bf, rep_bf = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, args.steps, args.warmup, 3)
     r = rep_bf[-1]
+    note("breadth-first: %.1f ms per step" % (sec_bf * 1e3))
     out_df = None
     if not args.no_df:
         # the other order under the same protocol, at a quarter of the steps (its time is not the headline)
         k_df, w_df = max(3, args.steps // 4), max(1, args.warmup // 4)
         sec_df, rep_df = time_steps(st, bf, bf.BF_SCHED_DF, N_loop, N_mb, S_mb, x, dy, y, dx, k_df, w_df, 1)
+        note("depth-first: %.1f ms per step" % (sec_df * 1e3))
         rd = rep_df[-1]
         out_df = {"ms_per_step": sec_df * 1e3, "steps": k_df, "warmup": w_df, "gpu_ms": step_stats(rep_df),
                   "model_tflops": rd.flops_model / sec_df / 1e12,
@@ -303,6 +314,7 @@ def main():
     # other classes
     sec_plain, _ = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 1, 0, 1)
     sec_instr, rep_instr = time_steps(st, bf, bf.BF_SCHED_BF, N_loop, N_mb, S_mb, x, dy, y, dx, 2, 0, 2)
+    note("instrumented steps done")
 
     def classes(reps):
         out = {}
@@ -385,19 +397,26 @@ def main():
                             "reconstruct_bytes": rp.reconstruct_bytes, "reconstruct_ms": rp.kernel_ms[i],
                             "weight_buffer_bytes": rp.weight_buffer_bytes, "state_bytes": rp.state_bytes}
         line["dp_fs"] = out_fs
+        note("fully sharded steps done")
         fs.close()
         del fs
     del x, dy, y, dx
     torch.cuda.empty_cache()
     if args.workload == "c3" and not args.no_other_workloads:
-        line["other_workloads"] = {name: other_workload(bf, name) for name in ("c2", "c4", "c5")}
+        line["other_workloads"] = {}
+        for name in ("c2", "c4", "c5"):
+            line["other_workloads"][name] = other_workload(bf, name)
+            note("%s done" % name)
         # the small stack and the 6144-wide one (192 tiles on 256 compute units in five of its eight products per
         # layer) again with two micro-batches in flight: their kernels do not fill the chip one at a time
         line["other_workloads"]["c2_two_chains"] = other_workload(bf, "c2", mb_chains=2)
         line["other_workloads"]["c5_two_chains"] = other_workload(bf, "c5", mb_chains=2)
+        note("c2 and c5 with two chains done")
     if b16 and not args.no_power_check and h % 256 == 0:
         line["power_check"] = power_check(bf, h)
+        note("power check done")
     if not args.no_cpu_baseline:
+        note("CPU oracle on the reduced sample (about half a minute)")
         line["cpu_baseline"] = cpu_baseline(w, causal=bool(EXTRA.get(args.workload, {}).get("causal", 1)))
     print(json.dumps(line))
 
