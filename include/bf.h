@@ -106,12 +106,14 @@ typedef struct {
                            even micro-batches run on the caller's stream, odd ones on a second stream of the stack's,
                            each chain with its own backward temporaries; the chains meet once per stage, for the
                            stage-wide weight-gradient products and the optimizer step.  Pays where one micro-batch's
-                           kernels do not fill the chip (a 2048-wide model: step 44 -> 38 ms); costs an 8192-wide one
+                           kernels do not fill the chip (a 2048-wide model: step 44 -> 37 ms); costs an 8192-wide one
                            2 to 7 %.  The workspace grows by a second set of backward temporaries and a second fp32
                            gradient arena of the layers' size (with BF_CKPT_LAYER also by a second recomputation
                            record).  Needs fuse_wgrad = 1, dp_fs = 0, queue_depth = 0, S_voc = 0, and y and
                            dx given to bf_run_step; depth-first steps, bf_run_rank_step with N_PP > 1 and steps of
-                           one micro-batch run as with 1.  Bias and LayerNorm gradients are then (sum over even) +
+                           one micro-batch run as with 1.  A two-chain step splits no contraction (the one-chain step
+                           does where a product has few tiles; results then differ by the rounding of the outputs,
+                           otherwise outputs and weight-matrix gradients are the same bits).  Bias and LayerNorm gradients are then (sum over even) +
                            (sum over odd micro-batches): equal to the one-chain result to fp32 rounding, and the
                            same bits from run to run.  0 or 1: one micro-batch at a time. */
 } bf_config;

@@ -207,6 +207,15 @@ def test_optimizer_step_after_the_fused_weight_gradient(mode, dtype, Lyr, N_loop
 MATRICES = ("W_qkv", "W_o", "W_fc1", "W_fc2")
 
 
+def _a_product_splits_its_contraction(dtype, T, h, f):
+    """Whether one of a layer's forward / dgrad products runs as two slices of K in a one-chain step."""
+    if dtype != bf.BF_BF16:
+        return False
+    shapes = [(bf.BF_NN, bf.BF_EPI_BIAS, T, 3 * h, h), (bf.BF_NN, bf.BF_EPI_BIAS_RES, T, h, h), (bf.BF_NN, bf.BF_EPI_BIAS_RES, T, h, f),
+              (bf.BF_NT, bf.BF_EPI_NONE, T, h, f), (bf.BF_NT, bf.BF_EPI_NONE, T, h, h), (bf.BF_NT, bf.BF_EPI_NONE, T, h, 3 * h)]
+    return any(bf.bf_op_gemm_splitk_slices(*sh) > 1 for sh in shapes)
+
+
 @pytest.mark.parametrize("mode,dtype,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb", [
     ("fp32", bf.BF_FP32, 3, 3, 72, 3, 200, 50, 2, 3),          # generic kernels, odd N_mb
     ("fp32", bf.BF_FP32, 4, 2, 256, 4, 1024, 128, 1, 2),       # one micro-batch per chain
@@ -219,7 +228,8 @@ def test_two_chains_of_micro_batches_side_by_side(mode, dtype, Lyr, N_loop, h, a
     """mb_chains = 2: the micro-batches of a breadth-first step run on two streams (Sec. 4.2: within a stage
     they do not depend on each other), with stored activations or with per-layer checkpoints (then each chain
     recomputes into a record of its own).  Outputs and weight-matrix gradients are those of the one-chain step
-    bit for bit, the bias / LayerNorm gradients are two partial sums added in a fixed order (equal up to fp32
+    bit for bit (unless that step splits a contraction, which a two-chain step does not: then to the rounding of
+    the outputs), the bias / LayerNorm gradients are two partial sums added in a fixed order (equal up to fp32
     rounding, the same bits on every run), and everything matches the oracle."""
     b16 = dtype == bf.BF_BF16
     params = bf_inputs.make_params(19, Lyr, h, f, bf16=b16)
@@ -233,12 +243,19 @@ def test_two_chains_of_micro_batches_side_by_side(mode, dtype, Lyr, N_loop, h, a
     one = _run_gpu(mk(1), params, x, dy, bf.BF_SCHED_BF, N_loop, N_mb, S_mb)
     assert two["report"].mb_chains == 2 and one["report"].mb_chains == 1
     _compare(two, ref, TOL[mode], Lyr)
-    assert np.array_equal(two["y"], one["y"]) and np.array_equal(two["dx"], one["dx"])
+    split = _a_product_splits_its_contraction(dtype, S_mb * S_seq, h, f)
+    assert split == (h == 512)   # the cases cover both
+    if split:
+        assert rel_err(two["y"], one["y"]) <= TOL[mode] and rel_err(two["dx"], one["dx"]) <= TOL[mode]
+    else:
+        assert np.array_equal(two["y"], one["y"]) and np.array_equal(two["dx"], one["dx"])
     assert np.array_equal(two["y"], again["y"]) and np.array_equal(two["dx"], again["dx"])
     for l in range(Lyr):
         for name in bf.TENSOR_IDS:
             assert np.array_equal(two["grads"][l][name], again["grads"][l][name]), (l, name)
-            if name in MATRICES:
+            if split:
+                assert rel_err(two["grads"][l][name], one["grads"][l][name]) <= TOL[mode], (l, name)
+            elif name in MATRICES:
                 assert np.array_equal(two["grads"][l][name], one["grads"][l][name]), (l, name)
             else:
                 assert rel_err(two["grads"][l][name], one["grads"][l][name]) <= 2e-6, (l, name)
