@@ -647,15 +647,17 @@ def test_optimizer_steps_replay_from_a_hip_graph():
     st.close()
 
 
-def test_timing_modes_fill_the_report_and_leave_the_numbers_alone():
+@pytest.mark.parametrize("chains", [1, 2])
+def test_timing_modes_fill_the_report_and_leave_the_numbers_alone(chains):
     """timing 1: step time; 2: an event pair around every launch, per-class sums in the report; 3: around
     the weight-gradient products only.  Launch counts follow from the layer structure (4 forward, 4 dgrad and 4
     weight-gradient products, 2 LayerNorms each way, 1 attention each way per layer and micro-batch; one
-    fused weight-gradient product per weight and stage); the results do not depend on the mode."""
+    fused weight-gradient product per weight and stage); the results do not depend on the mode.  With two chains
+    of micro-batches the event pairs sit on two streams and the counts are the same."""
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 3
     params = bf_inputs.make_params(37, Lyr, h, f, bf16=True)
     x, dy = bf_inputs.make_batch(37, N_mb, S_mb, S_seq, h, bf16=True)
-    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1)
+    cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, mb_chains=chains)
     st = bf.Stack(cfg)
     for l, p in enumerate(params):
         for name, tid in bf.TENSOR_IDS.items():
@@ -670,6 +672,7 @@ def test_timing_modes_fill_the_report_and_leave_the_numbers_alone():
         outs.append((y.clone(), dx.clone(), st.bf_get_grads(1, bf.TENSOR_IDS["w_fc1"])))
         n = lambda cls: int(rep.kernel_launches[K_[cls]])
         lm = Lyr * N_mb
+        assert rep.mb_chains == chains
         if timing == 0:
             assert rep.timed == 0
         else:
