@@ -183,23 +183,32 @@ def test_attention_at_full_size_on_sampled_rows(heads, seq, causal):
 def _step_against_the_oracle(seed, Lyr, N_loop, N_mb, S_mb, h, a, f, ckpt=bf.BF_CKPT_NONE, orders=("bf", "df")):
     """bf_run_step with the benchmark's settings (fused weight gradient in breadth-first order) against the oracle's
     step, element by element: outputs, input gradients and every parameter gradient of every layer.  The oracle runs in
-    depth-first order, where it holds one micro-batch's activations at a time (its two orders are bitwise equal)."""
+    depth-first order, where it holds one micro-batch's activations at a time (its two orders are bitwise equal).
+    Order "bf2" is the breadth-first step with two chains of micro-batches (mb_chains = 2), on a stack of its own."""
     params = bf_inputs.make_params(seed, Lyr, h, f, bf16=True)
     x, dy = bf_inputs.make_batch(seed, N_mb, S_mb, S, h, bf16=True)
     ref = K.run_step([{k: v.astype(np.float64) for k, v in p.items()} for p in params], x.astype(np.float64),
                      dy.astype(np.float64), K.SCHED_DF, N_loop, a)
     ref = dict(y=ref["y"], dx=ref["dx"], grads=ref["grads"])
-    st = bf.Stack(bf.make_config(h, a, f, S, Lyr, N_mb, S_mb, ckpt_mode=ckpt, fuse_wgrad=1, N_loop_min=N_loop))
-    for l, p in enumerate(params):
-        for name, tid in bf.TENSOR_IDS.items():
-            st.bf_set_params(l, tid, p[name].reshape(-1))
+    def stack(chains):
+        st = bf.Stack(bf.make_config(h, a, f, S, Lyr, N_mb, S_mb, ckpt_mode=ckpt, fuse_wgrad=1, N_loop_min=N_loop,
+                                     mb_chains=chains))
+        for l, p in enumerate(params):
+            for name, tid in bf.TENSOR_IDS.items():
+                st.bf_set_params(l, tid, p[name].reshape(-1))
+        return st
+    st = stack(1)
     dX, dDY = to_dev(x, True), to_dev(dy, True)
     tol, tol_rms = tol_at_depth("bf16", Lyr, h)
     worst = {}
     for order in orders:
+        if order == "bf2":
+            st.close()
+            st = stack(2)
         y, dx = torch.empty_like(dX), torch.empty_like(dX)
-        st.bf_run_step(bf.BF_SCHED_BF if order == "bf" else bf.BF_SCHED_DF, N_loop, N_mb, S_mb, dX, dDY, y, dx)
+        rep = st.bf_run_step(bf.BF_SCHED_DF if order == "df" else bf.BF_SCHED_BF, N_loop, N_mb, S_mb, dX, dDY, y, dx)
         torch.cuda.synchronize()
+        assert rep.mb_chains == (2 if order == "bf2" else 1)
         errs = {"y": (rel_err(to_host(y), ref["y"]), rms_err(to_host(y), ref["y"])),
                 "dx": (rel_err(to_host(dx), ref["dx"]), rms_err(to_host(dx), ref["dx"]))}
         for l in range(Lyr):
@@ -216,8 +225,9 @@ def _step_against_the_oracle(seed, Lyr, N_loop, N_mb, S_mb, h, a, f, ckpt=bf.BF_
 
 
 def test_whole_1p3b_shaped_step_against_the_oracle():
-    """configs[1]: 6 layers as 3 stages of 2, S_hidden 2048, 16 heads, S_mlp 8192, S_seq 2048, 8 micro-batches of one."""
-    _step_against_the_oracle(23, 6, 3, 8, 1, 2048, 16, 8192)
+    """configs[1]: 6 layers as 3 stages of 2, S_hidden 2048, 16 heads, S_mlp 8192, S_seq 2048, 8 micro-batches of one;
+    in both orders, and breadth-first with two chains of micro-batches."""
+    _step_against_the_oracle(23, 6, 3, 8, 1, 2048, 16, 8192, orders=("bf", "df", "bf2"))
 
 
 def test_52b_width_reduced_step_against_the_oracle():
@@ -233,8 +243,9 @@ def test_52b_width_layer_on_a_micro_batch_of_four_against_the_oracle():
 
 def test_deep_loop_width_layer_with_checkpoints_against_the_oracle():
     """configs[4] at its own width: S_hidden 6144, 48 heads, S_mlp 24576, per-layer checkpoints (the forward is
-    recomputed before each backward) and the fused weight gradient over 2 micro-batches; 2 layers as 2 stages of 1."""
-    _step_against_the_oracle(27, 2, 2, 2, 1, 6144, 48, 24576, ckpt=bf.BF_CKPT_LAYER)
+    recomputed before each backward) and the fused weight gradient over 2 micro-batches; 2 layers as 2 stages of 1;
+    also with the two micro-batches side by side."""
+    _step_against_the_oracle(27, 2, 2, 2, 1, 6144, 48, 24576, ckpt=bf.BF_CKPT_LAYER, orders=("bf", "df", "bf2"))
 
 
 def test_full_52b_rank_share_step_invariants():
