@@ -110,7 +110,7 @@ typedef struct {
                            2 to 7 %.  The workspace grows by a second set of backward temporaries and a second fp32
                            gradient arena of the layers' size (with BF_CKPT_LAYER also by a second recomputation
                            record).  Needs fuse_wgrad = 1, dp_fs = 0, queue_depth = 0, S_voc = 0, and y and
-                           dx given to bf_run_step; depth-first steps, bf_run_rank_step and steps of
+                           dx given to bf_run_step / bf_run_rank_step; depth-first steps and steps of
                            one micro-batch run as with 1.  A two-chain step splits no contraction (the one-chain step
                            does where a product has few tiles; results then differ by the rounding of the outputs,
                            otherwise outputs and weight-matrix gradients are the same bits).  Bias and LayerNorm

@@ -894,9 +894,10 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
   // Two chains: micro-batch m runs on stream m & 1, so two micro-batches of a stage are in flight side by side and a
   // kernel with fewer workgroups than the chip has compute units shares it with the other chain's.  Micro-batches
   // of one stage are independent of each other in both directions (Sec. 4.2), which is what breadth-first order
-  // leaves room for; depth-first order, the input / output layers, stages that do not feed each other and steps
-  // without caller buffers for the outputs (they would share one scratch tensor) run as one chain.
-  const int chains = c.mb_chains == 2 && fuse && chained && !lm && N_mb >= 2 && y && dx ? 2 : 1;
+  // leaves room for, on a rank of a deeper pipeline as well (its order has every micro-batch of a stage in a row
+  // too); depth-first order, the input / output layers and steps without caller buffers for the outputs (they
+  // would share one scratch tensor) run as one chain.
+  const int chains = c.mb_chains == 2 && fuse && !lm && N_mb >= 2 && y && dx ? 2 : 1;
   auto stream_of = [&](int m) { return chains == 2 && (m & 1) ? s->chain_st : st; };
   s->chains_active = chains;
   if (c.dp_fs && per_stage > lps_max(c)) {

@@ -204,7 +204,7 @@ def test_optimizer_step_after_the_fused_weight_gradient(mode, dtype, Lyr, N_loop
                     assert moved.min() > 0.5 * adam["lr"] and moved.max() < 1.5 * adam["lr"], (l, name)
 
 
-MATRICES = ("W_qkv", "W_o", "W_fc1", "W_fc2")
+MATRICES = ("w_qkv", "w_o", "w_fc1", "w_fc2")
 
 
 def _a_product_splits_its_contraction(dtype, T, h, f):
@@ -462,6 +462,42 @@ def test_rank_of_a_deeper_pipeline_matches_oracle(mode, dtype, N_PP, rank, Lyr, 
                 assert rel_err(got["BF"]["grads"][l][name], got["DF"]["grads"][l][name]) <= 1e-5, (l, name)
             else:
                 assert np.array_equal(got["BF"]["grads"][l][name], got["DF"]["grads"][l][name]), (l, name)
+
+
+@pytest.mark.parametrize("mode,dtype,N_PP,rank,Lyr,N_loop,h,a,f,S_seq,S_mb,N_mb,ckpt", [
+    ("fp32", bf.BF_FP32, 2, 1, 4, 2, 128, 2, 512, 64, 1, 4, bf.BF_CKPT_LAYER),
+    ("fp32", bf.BF_FP32, 4, 2, 3, 3, 72, 3, 200, 50, 2, 8, bf.BF_CKPT_NONE),
+    ("bf16", bf.BF_BF16, 4, 3, 4, 2, 256, 2, 1024, 128, 1, 7, bf.BF_CKPT_NONE),
+])
+def test_rank_of_a_deeper_pipeline_with_two_chains(mode, dtype, N_PP, rank, Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, ckpt):
+    """A rank's breadth-first order (Sec. 4.2) also has every micro-batch of a stage in a row, so the two chains
+    of mb_chains = 2 apply to bf_run_rank_step as well: the oracle's numbers and trace, outputs and
+    weight-matrix gradients those of the one-chain step bit for bit."""
+    b16 = dtype == bf.BF_BF16
+    params = bf_inputs.make_params(31, Lyr, h, f, bf16=b16)
+    p64 = [{k: v.astype(np.float64) for k, v in p.items()} for p in params]
+    xs, dys = zip(*[bf_inputs.make_batch(200 + l, N_mb, S_mb, S_seq, h, bf16=b16) for l in range(N_loop)])
+    x, dy = np.stack(xs), np.stack(dys)
+    mk = lambda chains: bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=dtype, fuse_wgrad=1, ckpt_mode=ckpt,
+                                       N_loop_min=N_loop, mb_chains=chains)
+    ref = K.run_rank_step(p64, x.astype(np.float64), dy.astype(np.float64), "BF", N_PP, rank, N_loop, a)
+    two = _run_gpu_rank(mk(2), params, x, dy, bf.BF_SCHED_BF, N_PP, rank, N_loop, N_mb, S_mb)
+    one = _run_gpu_rank(mk(1), params, x, dy, bf.BF_SCHED_BF, N_PP, rank, N_loop, N_mb, S_mb)
+    assert two["report"].mb_chains == 2 and one["report"].mb_chains == 1
+    _compare(two, ref, TOL[mode], Lyr)
+    assert two["trace"] == one["trace"] == [tuple(e) for e in ref["trace"]]
+    assert not _a_product_splits_its_contraction(dtype, S_mb * S_seq, h, f)
+    assert np.array_equal(two["y"], one["y"]) and np.array_equal(two["dx"], one["dx"])
+    for l in range(Lyr):
+        for name in bf.TENSOR_IDS:
+            if name in MATRICES:
+                assert np.array_equal(two["grads"][l][name], one["grads"][l][name]), (l, name)
+            else:
+                assert rel_err(two["grads"][l][name], one["grads"][l][name]) <= 2e-6, (l, name)
+    # the rank's depth-first order has one micro-batch of a stage at a time
+    df = _run_gpu_rank(mk(2), params, x, dy, bf.BF_SCHED_DF, N_PP, rank, N_loop, N_mb if N_mb % N_PP == 0 else N_PP, S_mb) \
+        if N_mb % N_PP == 0 else None
+    assert df is None or df["report"].mb_chains == 1
 
 
 def test_rank_step_argument_errors():
