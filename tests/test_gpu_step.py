@@ -564,6 +564,13 @@ def test_randomly_drawn_configurations(c):
     assert np.array_equal(g_bf["y"], g_df["y"]) and np.array_equal(g_bf["dx"], g_df["dx"])
     assert g_bf["report"].peak_ckpt_count == F.ckpt_count("BF", c["N_mb"], c["Lyr"], 1)
     assert g_df["report"].peak_ckpt_count == F.ckpt_count("DF", c["N_mb"], c["Lyr"], 1)
+    if c["fuse"] and not c["fs"]:
+        # the same step with two chains of micro-batches, where the configuration allows them
+        cfg.mb_chains = 2
+        g_two = _run_gpu(cfg, params, x, dy, bf.BF_SCHED_BF, c["N_loop"], c["N_mb"], c["S_mb"])
+        assert g_two["report"].mb_chains == (2 if c["N_mb"] >= 2 else 1)
+        _compare(g_two, ref, TOL[mode], c["Lyr"])
+        assert g_two["trace"] == g_bf["trace"]
 
 
 def _random_rank_cases(n, seed):
