@@ -1103,7 +1103,8 @@ static bf_status run_rank_step(bf_stack* s, int schedule, int N_PP, int rank, bo
       // this stage's gradient is final (Sec. 4.2: breadth-first groups the work by stage)
       if (apply_optimizer) {
         const size_t off = (size_t)l0 * s->D.layer_elems, n = (size_t)per_stage * s->D.layer_elems;
-        // The update runs in line, on the caller's stream, as soon as the stage's gradient is final.
+        // The update runs in line, on the stream that issued the stage's last backward (the caller's, unless the step
+        // runs two chains of micro-batches), as soon as the stage's gradient is final.
         // (On a side stream, "beside" the backward of the earlier stages, it is slower: the products
         // hold every compute unit, so the two do not overlap but take turns, a product that shares
         // the chip with the update's workgroups runs in more rounds, and under the power limit an
