@@ -63,6 +63,11 @@ bf_status bf_op_gemm_splitk(int dtype, int kernels, int layout, int epilogue, in
 int bf_op_gemm_splitk_slices(int layout, int epilogue, int M, int N, int K);
 /* 1 if the MFMA kernel takes this problem in bf16 mode, 0 if the plain kernel would run. */
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
+/* The tile of C (rows x columns per workgroup) that the MFMA kernel runs an unsplit product of this shape on: 256 x 256,
+ * 256 x 128, 128 x 128, or 256 x 192 (dgrad layout with the plain epilogue and N a multiple of 192, where that fills
+ * the rounds better: 6144 columns).  Host arithmetic only.  Returns 1 and the tile in tile_m / tile_n (host ints), or 0
+ * (and 0 x 0) where bf_op_gemm_uses_mfma is 0. */
+int bf_op_gemm_tile(int layout, int epilogue, int M, int N, int K, int* tile_m, int* tile_n);
 
 /* Weight and bias gradient of one linear layer over all the micro-batches of a stage in one
  * product (breadth-first order: every micro-batch of the stage has been through its backward

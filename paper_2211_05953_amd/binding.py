@@ -93,6 +93,7 @@ _SIGNATURES = {
     "bf_op_gemm": (C.c_int, [C.c_int] * 7 + [_P] * 6 + [C.c_int, _P]),
     "bf_op_gemm_gelu_bwd_colsum": (C.c_int, [C.c_int] * 5 + [_P] * 6 + [C.c_int, _P]),
     "bf_op_gemm_uses_mfma": (C.c_int, [C.c_int] * 5),
+    "bf_op_gemm_tile": (C.c_int, [C.c_int] * 5 + [C.POINTER(C.c_int)] * 2),
     "bf_op_wgrad": (C.c_int, [C.c_int] * 6 + [_P, C.c_size_t, _P, C.c_size_t, _P, _P, C.c_int, _P]),
     "bf_op_layernorm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
     "bf_op_layernorm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int] + [_P] * 8 + [C.c_int, _P]),
@@ -332,6 +333,13 @@ def bf_op_gemm_splitk_slices(layout, epilogue, M, N, K):
 
 def bf_op_gemm_uses_mfma(layout, epilogue, M, N, K):
     return bool(load().bf_op_gemm_uses_mfma(layout, epilogue, M, N, K))
+
+
+def bf_op_gemm_tile(layout, epilogue, M, N, K):
+    """(rows, columns) of the MFMA kernel's tile for this product, or None where the plain kernel runs."""
+    bm, bn = C.c_int(0), C.c_int(0)
+    ok = load().bf_op_gemm_tile(layout, epilogue, M, N, K, C.byref(bm), C.byref(bn))
+    return (bm.value, bn.value) if ok else None
 
 
 def bf_op_layernorm_fwd(dtype, T, h, x, g, b, eps, y, stats):

@@ -77,6 +77,8 @@ bf_status gemm_plain(int dtype, int layout, int epi, const GemmArgs& a, hipStrea
 // true if the MFMA kernel covers this problem (bf16, sizes multiples of its tiles)
 bool gemm_mfma_supported(int layout, int epi, int M, int N, int K);
 bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st);
+// tile (rows x columns of C per workgroup) the MFMA kernel runs an unsplit product of this shape on; 0 x 0 if none fits
+void gemm_mfma_tile(int layout, int epi, int M, int N, int* bm, int* bn);
 // Slices the matrix-core path would cut the contraction of this forward / dgrad product into (1: no split).
 int gemm_splitk_slices(int layout, int epi, int M, int N, int K);
 // C[M,N] (bf16) = epilogue(sum over the planes of part[slices][M][N], added in ascending order); epilogues

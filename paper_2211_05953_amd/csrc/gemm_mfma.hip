@@ -34,7 +34,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int BK = 64;
 // measured throughput of a compute unit on the smaller tiles relative to the 256 x 256 tile
-constexpr double TILE_RATE_MID = 0.84, TILE_RATE_SMALL = 0.68;
+constexpr double TILE_RATE_MID = 0.84, TILE_RATE_SMALL = 0.68, TILE_RATE_WIDE = 0.95;
 constexpr int TPAD = 32;  // padding (elements) of a transposed LDS row: stride = 64 bytes mod 128
 
 template <int BM_, int BN_, int WM_, int WN_>
@@ -496,6 +496,10 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave (8 x 4 MFMA tiles)
 typedef Tile<256, 128, 4, 2> TileMid;    // 8 waves, 64 x 64 per wave
 typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
+// 8 waves, 64 x 96 per wave, for outputs of 6144 columns (a multiple of 192 but of 24, not 32, times 256): 2048 rows
+// are 256 such tiles, one round, where 256 x 256 gives 192.  Its staging and epilogue maps only come out whole for
+// K-contiguous operands and the plain epilogue, i.e. for the dgrad products without GeLU'.
+typedef Tile<256, 192, 4, 2> TileWide;
 
 template <typename TL, bool AK, bool BKC>
 constexpr size_t lds_bytes() { return 2 * (size_t)(stage_elems<AK, TL::BM>() + stage_elems<BKC, TL::BN>()) * sizeof(bf16_t); }
@@ -561,6 +565,7 @@ bf_status by_layout(int layout, int epi, const GemmArgs& a, hipStream_t st) {
 }
 
 inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
+inline bool wide_fits(int layout, int epi, int M, int N) { return layout == L_NT && epi == E_NONE && M % 256 == 0 && N % 192 == 0; }
 constexpr int SPLITK_TILE = 1;  // split contractions run on the 256 x 128 tile
 
 // Tile choice: the grid runs in rounds over the chip's workgroup slots, so the estimated time of a
@@ -569,14 +574,15 @@ constexpr int SPLITK_TILE = 1;  // split contractions run on the 256 x 128 tile
 // partly filled last round counts as (1 + fill) / 2 of a round: the chip runs at its power limit,
 // and the compute units that do work clock higher when the others idle (measured: 384 large tiles
 // beat 768 of 256 x 128, 128 large tiles lose to 256 of them).
-// 0: 256 x 256 (one per compute unit), 1: 256 x 128 (one), 2: 128 x 128 (two).
-inline int choose_tile(int M, int N) {
-  const int bm[3] = {256, 256, 128}, bn[3] = {256, 128, 128};
-  const long slots[3] = {256, 256, 512};
-  const double rate[3] = {1.0, TILE_RATE_MID, TILE_RATE_SMALL / 2};
+// 0: 256 x 256 (one per compute unit), 1: 256 x 128 (one), 2: 128 x 128 (two), 3: 256 x 192 (one; only where the
+// caller says the product can take it).
+inline int choose_tile(int M, int N, bool wide = false) {
+  const int bm[4] = {256, 256, 128, 256}, bn[4] = {256, 128, 128, 192};
+  const long slots[4] = {256, 256, 512, 256};
+  const double rate[4] = {1.0, TILE_RATE_MID, TILE_RATE_SMALL / 2, TILE_RATE_WIDE};
   int best = -1;
   double best_t = 0;
-  for (int i = 0; i < 3; ++i) {
+  for (int i = 0; i < (wide ? 4 : 3); ++i) {
     if (M % bm[i] || N % bn[i]) continue;
     const long tiles = (long)(M / bm[i]) * (N / bn[i]), full = tiles / slots[i], rest = tiles % slots[i];
     const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / slots[i] : 0.0);
@@ -596,6 +602,13 @@ bool gemm_mfma_supported(int layout, int epi, int M, int N, int K) {
   return small_fits(M, N);
 }
 
+void gemm_mfma_tile(int layout, int epi, int M, int N, int* bm, int* bn) {
+  const int rows[4] = {256, 256, 128, 256}, cols[4] = {256, 128, 128, 192};
+  const int t = choose_tile(M, N, wide_fits(layout, epi, M, N));
+  *bm = t < 0 ? 0 : rows[t];
+  *bn = t < 0 ? 0 : cols[t];
+}
+
 bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   const bool planes = epi == E_ACCUM && layout != L_TN;  // split contraction of a forward / dgrad product
   if (planes) {
@@ -611,9 +624,10 @@ bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
-  switch (planes ? SPLITK_TILE : choose_tile(a.M, a.N)) {
+  switch (planes ? SPLITK_TILE : choose_tile(a.M, a.N, wide_fits(layout, epi, a.M, a.N))) {
     case 0: return by_layout<TileBig>(layout, epi, a, st);
     case 1: return by_layout<TileMid>(layout, epi, a, st);
+    case 3: return launch<TileWide, true, true, E_NONE, bf16_t>(a, st);
     default: return by_layout<TileSmall>(layout, epi, a, st);
   }
 }

@@ -93,6 +93,14 @@ int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K) {
   return gemm_mfma_supported(layout, epilogue, M, N, K) ? 1 : 0;
 }
 
+int bf_op_gemm_tile(int layout, int epilogue, int M, int N, int K, int* tile_m, int* tile_n) {
+  if (!tile_m || !tile_n) return 0;
+  *tile_m = *tile_n = 0;
+  if (!gemm_mfma_supported(layout, epilogue, M, N, K)) return 0;
+  gemm_mfma_tile(layout, epilogue, M, N, tile_m, tile_n);
+  return 1;
+}
+
 bf_status bf_op_layernorm_fwd(int dtype, int T, int h, const void* x, const float* g, const float* b, float eps, void* y,
                               float* stats, void* stream) {
   if (!dtype_ok(dtype, 0)) return BF_EINVAL;

@@ -306,6 +306,29 @@ def test_gemm_mfma_large_tile(M, N, K):
     assert rel_err(to_host(G), 2 * acc) <= 1e-5   # bf16 products are exact in fp32; only the summation order differs
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 3072, 192), (2048, 6144, 64), (256, 49152, 128)])
+def test_gemm_mfma_tile_of_192_columns(M, N, K):
+    """Dgrad products with the plain epilogue whose column count is a multiple of 192 take a 256 x 192 tile where
+    that fills the rounds better (6144 columns: 32 tiles where 256-column tiles give 24); every other layout and
+    epilogue of the same shape keeps its tile."""
+    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, M, N, K) == (256, 192)
+    assert bf.bf_op_gemm_tile(bf.BF_NN, bf.BF_EPI_NONE, M, N, K)[1] != 192
+    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_GELU_BWD, M, N, K)[1] != 192
+    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, 2048, 8192, 8192) == (256, 256)   # 8192 is no multiple of 192
+    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, 100, 72, 64) is None
+    A = bf_inputs.normal(6, 0, (M, K), bf16=True)
+    Bt = bf_inputs.normal(6, 1, (N, K), 0.05, bf16=True)
+    ref = A.astype(np.float64) @ Bt.astype(np.float64).T
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NT, bf.BF_EPI_NONE, M, N, K, to_dev(A, True), to_dev(Bt, True), out)
+    got = to_host(out)
+    assert np.isfinite(got).all() and rel_err(got, ref) <= TOL["bf16"]
+    # one rounding of the fp32 sum: the plain kernel (fp32 FMA over the same bf16 products) agrees to that rounding
+    plain = torch.empty_like(out)
+    bf.bf_op_gemm(bf.BF_BF16, bf.BF_KERNELS_PLAIN, bf.BF_NT, bf.BF_EPI_NONE, M, N, K, to_dev(A, True), to_dev(Bt, True), plain)
+    assert rel_err(got, to_host(plain)) <= 2.0 ** -7
+
+
 @pytest.mark.parametrize("mode,dtype,kernels", [("fp32", bf.BF_FP32, bf.BF_KERNELS_AUTO), ("bf16", bf.BF_BF16, bf.BF_KERNELS_PLAIN),
                                                 ("bf16", bf.BF_BF16, bf.BF_KERNELS_AUTO)])
 @pytest.mark.parametrize("M,N,K,n_seg,gap", [(256, 512, 128, 3, 0), (1024, 768, 128, 2, 64), (128, 384, 64, 2, 8), (512, 256, 192, 4, 0),
