@@ -58,6 +58,10 @@ struct GemmArgs {
   // whose tiles would leave half of the chip idle (see gemm_splitk_slices) and finishes it with a second kernel.
   float* splitk_ws = nullptr;
   size_t splitk_ws_elems = 0;
+  // The product shares the chip with another stream's kernels (two chains of micro-batches): compute units that
+  // its grid leaves idle are taken by those, so nothing is gained by trading a tile's efficiency for a fuller
+  // round: no 256 x 192 tile (measured on a 6144-wide stack with two chains: 3066 ms per step without, 3154 with).
+  bool shared_chip = false;
 };
 
 void set_error(const char* fmt, ...);

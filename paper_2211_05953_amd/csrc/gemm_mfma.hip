@@ -73,7 +73,7 @@ constexpr int stage_elems() { return KCONTIG ? R * BK : BK * (R + TPAD); }
 // per-thread element offset (LDS) serve all chunks: every load is "wave-uniform base (scalar
 // registers, moved per k-tile and per chunk) + 32-bit lane offset", every LDS store "lane offset
 // + immediate".
-template <bool KCONTIG, int R, int NT>
+template <bool KCONTIG, int R, int NT, bool EVEN = KCONTIG || NT % (R / 8) == 0>
 struct Stager {
   static constexpr int CHUNKS = R * BK / 8 / NT;
   static constexpr int ROWSTEP = KCONTIG ? NT / 8 : NT / (R / 8);  // tile rows between a thread's chunks
@@ -106,6 +106,38 @@ struct Stager {
     constexpr int LSTEP = KCONTIG ? ROWSTEP * BK : ROWSTEP * (R + TPAD);
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) *reinterpret_cast<u32x4*>(lds + loff + i * LSTEP) = v[i];
+  }
+};
+
+// A transposed tile whose rows (R / 8 chunks) the workgroup's threads do not divide into whole passes (192 columns:
+// 24 chunks per k-row, 512 threads): the tile's chunks are dealt out in their linear order, chunk tid + i * NT to
+// thread tid, and a thread keeps one global and one LDS offset per chunk (they sit in different rows and columns).
+template <int R, int NT>
+struct Stager<false, R, NT, false> {
+  static constexpr int CPR = R / 8;  // chunks per k-row
+  static constexpr int CHUNKS = BK * CPR / NT;
+  static_assert(BK * CPR % NT == 0, "the tile's chunks must divide among the threads");
+  u32x4 v[CHUNKS];
+  uint32_t goff[CHUNKS];
+  int loff[CHUNKS];
+
+  __device__ __forceinline__ void init(size_t ld, int tid) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = tid + i * NT, krow = c / CPR, rc = c % CPR;
+      goff[i] = (uint32_t)(((size_t)krow * ld + rc * 8) * sizeof(bf16_t));
+      loff[i] = krow * (R + TPAD) + ((rc ^ tkey(krow)) << 3);
+    }
+  }
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ g, size_t ld, int r0, int k0) {
+    const bf16_t* base = g + (size_t)k0 * ld + r0;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[i], 0, 0);
+  }
+  __device__ __forceinline__ void store(bf16_t* lds) const {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) *reinterpret_cast<u32x4*>(lds + loff[i]) = v[i];
   }
 };
 
@@ -496,9 +528,10 @@ __global__ __launch_bounds__(TL::NT) void gemm_mfma_kernel(int M, int N, int K, 
 typedef Tile<256, 256, 2, 4> TileBig;    // 8 waves, 128 x 64 per wave (8 x 4 MFMA tiles)
 typedef Tile<256, 128, 4, 2> TileMid;    // 8 waves, 64 x 64 per wave
 typedef Tile<128, 128, 2, 2> TileSmall;  // 4 waves, 64 x 64 per wave
-// 8 waves, 64 x 96 per wave, for outputs of 6144 columns (a multiple of 192 but of 24, not 32, times 256): 2048 rows
-// are 256 such tiles, one round, where 256 x 256 gives 192.  Its staging and epilogue maps only come out whole for
-// K-contiguous operands and the plain epilogue, i.e. for the dgrad products without GeLU'.
+// 8 waves, 64 x 96 per wave, for outputs of 6144 columns (24 times 256, but 32 times 192): 2048 rows are 256 such
+// tiles, one round, where 256 x 256 gives 192.  For the forward and dgrad layouts with the one-output epilogues
+// (none, bias, bias + residual); the epilogue that also takes column sums needs the threads to divide into the
+// tile's 24 column groups and keeps the other shapes.
 typedef Tile<256, 192, 4, 2> TileWide;
 
 template <typename TL, bool AK, bool BKC>
@@ -565,7 +598,11 @@ bf_status by_layout(int layout, int epi, const GemmArgs& a, hipStream_t st) {
 }
 
 inline bool small_fits(int M, int N) { return M % 128 == 0 && N % 128 == 0; }
-inline bool wide_fits(int layout, int epi, int M, int N) { return layout == L_NT && epi == E_NONE && M % 256 == 0 && N % 192 == 0; }
+inline bool wide_fits(int layout, int epi, int M, int N) {
+  if (M % 256 || N % 192) return false;
+  if (layout == L_NT) return epi == E_NONE;
+  return layout == L_NN && (epi == E_NONE || epi == E_BIAS || epi == E_BIAS_RES);
+}
 constexpr int SPLITK_TILE = 1;  // split contractions run on the 256 x 128 tile
 
 // Tile choice: the grid runs in rounds over the chip's workgroup slots, so the estimated time of a
@@ -624,10 +661,14 @@ bf_status gemm_mfma(int layout, int epi, const GemmArgs& a, hipStream_t st) {
   }
   const uintptr_t al = (uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.C | (uintptr_t)a.R | (uintptr_t)a.C2 | (uintptr_t)a.bias;
   if (al & 15) { set_error("gemm_mfma: operands must be 16-byte aligned"); return BF_EINVAL; }
-  switch (planes ? SPLITK_TILE : choose_tile(a.M, a.N, wide_fits(layout, epi, a.M, a.N))) {
+  switch (planes ? SPLITK_TILE : choose_tile(a.M, a.N, !a.shared_chip && wide_fits(layout, epi, a.M, a.N))) {
     case 0: return by_layout<TileBig>(layout, epi, a, st);
     case 1: return by_layout<TileMid>(layout, epi, a, st);
-    case 3: return launch<TileWide, true, true, E_NONE, bf16_t>(a, st);
+    case 3:
+      if (layout == L_NT) return launch<TileWide, true, true, E_NONE, bf16_t>(a, st);
+      if (epi == E_BIAS) return launch<TileWide, true, false, E_BIAS, bf16_t>(a, st);
+      if (epi == E_BIAS_RES) return launch<TileWide, true, false, E_BIAS_RES, bf16_t>(a, st);
+      return launch<TileWide, true, false, E_NONE, bf16_t>(a, st);
     default: return by_layout<TileSmall>(layout, epi, a, st);
   }
 }

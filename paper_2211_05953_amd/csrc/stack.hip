@@ -435,6 +435,7 @@ bf_status p_gemm(bf_stack* s, int layout, int epi, const GemmArgs& g, hipStream_
   // Scratch for a split contraction; gemm() decides whether the product takes it.  Not with two chains of
   // micro-batches in flight: the other chain's kernels fill the compute units a product of few tiles leaves idle,
   // and the pass that adds the planes is saved (a 2048-wide stack: 38.3 -> 36.7 ms per step).
+  a.shared_chip = s->chains_active == 2;  // and no 256 x 192 tile either, for the same reason
   if (layout != L_TN && s->chains_active == 1) {
     const Tmp t = tmp_of(s);
     a.splitk_ws = t.splitk;

@@ -306,27 +306,36 @@ def test_gemm_mfma_large_tile(M, N, K):
     assert rel_err(to_host(G), 2 * acc) <= 1e-5   # bf16 products are exact in fp32; only the summation order differs
 
 
-@pytest.mark.parametrize("M,N,K", [(4096, 3072, 192), (2048, 6144, 64), (256, 49152, 128)])
+@pytest.mark.parametrize("M,N,K", [(4096, 3072, 192), (2048, 6144, 64), (256, 49152, 128), (2048, 6144, 320)])
 def test_gemm_mfma_tile_of_192_columns(M, N, K):
-    """Dgrad products with the plain epilogue whose column count is a multiple of 192 take a 256 x 192 tile where
-    that fills the rounds better (6144 columns: 32 tiles where 256-column tiles give 24); every other layout and
-    epilogue of the same shape keeps its tile."""
-    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, M, N, K) == (256, 192)
-    assert bf.bf_op_gemm_tile(bf.BF_NN, bf.BF_EPI_NONE, M, N, K)[1] != 192
-    assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_GELU_BWD, M, N, K)[1] != 192
+    """Forward and dgrad products with a one-output epilogue whose column count is a multiple of 192 take a 256 x 192
+    tile where that fills the rounds better (6144 columns: 32 tiles where 256-column tiles give 24); the epilogues
+    with a second output or with column sums, and the weight-gradient layout, keep their tiles."""
+    for layout, epi in ((bf.BF_NT, bf.BF_EPI_NONE), (bf.BF_NN, bf.BF_EPI_NONE), (bf.BF_NN, bf.BF_EPI_BIAS), (bf.BF_NN, bf.BF_EPI_BIAS_RES)):
+        assert bf.bf_op_gemm_tile(layout, epi, M, N, K) == (256, 192), (layout, epi)
+    for layout, epi in ((bf.BF_NT, bf.BF_EPI_GELU_BWD), (bf.BF_NN, bf.BF_EPI_BIAS_GELU), (bf.BF_TN, bf.BF_EPI_ACCUM)):
+        assert bf.bf_op_gemm_tile(layout, epi, M, N, K)[1] != 192, (layout, epi)
     assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, 2048, 8192, 8192) == (256, 256)   # 8192 is no multiple of 192
+    assert bf.bf_op_gemm_tile(bf.BF_NN, bf.BF_EPI_BIAS, 2048, 24576, 8192) == (256, 256)  # three whole rounds already
     assert bf.bf_op_gemm_tile(bf.BF_NT, bf.BF_EPI_NONE, 100, 72, 64) is None
     A = bf_inputs.normal(6, 0, (M, K), bf16=True)
-    Bt = bf_inputs.normal(6, 1, (N, K), 0.05, bf16=True)
-    ref = A.astype(np.float64) @ Bt.astype(np.float64).T
-    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    bf.bf_op_gemm(bf.BF_BF16, 0, bf.BF_NT, bf.BF_EPI_NONE, M, N, K, to_dev(A, True), to_dev(Bt, True), out)
-    got = to_host(out)
-    assert np.isfinite(got).all() and rel_err(got, ref) <= TOL["bf16"]
-    # one rounding of the fp32 sum: the plain kernel (fp32 FMA over the same bf16 products) agrees to that rounding
-    plain = torch.empty_like(out)
-    bf.bf_op_gemm(bf.BF_BF16, bf.BF_KERNELS_PLAIN, bf.BF_NT, bf.BF_EPI_NONE, M, N, K, to_dev(A, True), to_dev(Bt, True), plain)
-    assert rel_err(got, to_host(plain)) <= 2.0 ** -7
+    B = bf_inputs.normal(6, 1, (K, N), 0.05, bf16=True)
+    bias = bf_inputs.normal(6, 2, (N,), 0.5)
+    R = bf_inputs.normal(6, 3, (M, N), bf16=True)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    dA, dB, dBt = to_dev(A, True), to_dev(B, True), to_dev(np.ascontiguousarray(B.T), True)
+    dR, dbias = to_dev(R, True), to_dev(bias, False)
+    cases = (("dgrad", bf.BF_NT, bf.BF_EPI_NONE, dBt, acc), ("fwd", bf.BF_NN, bf.BF_EPI_NONE, dB, acc),
+             ("fwd+bias", bf.BF_NN, bf.BF_EPI_BIAS, dB, acc + bias), ("fwd+bias+res", bf.BF_NN, bf.BF_EPI_BIAS_RES, dB, acc + bias + R))
+    for name, layout, epi, dOp, ref in cases:
+        out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        bf.bf_op_gemm(bf.BF_BF16, 0, layout, epi, M, N, K, dA, dOp, out, bias=dbias, R=dR)
+        got = to_host(out)
+        assert np.isfinite(got).all() and rel_err(got, ref) <= TOL["bf16"], name
+        # one rounding of the fp32 result: the plain kernel (fp32 FMA over the same bf16 products) agrees to that rounding
+        plain = torch.empty_like(out)
+        bf.bf_op_gemm(bf.BF_BF16, bf.BF_KERNELS_PLAIN, layout, epi, M, N, K, dA, dOp, plain, bias=dbias, R=dR)
+        assert rel_err(got, to_host(plain)) <= 2.0 ** -7, name
 
 
 @pytest.mark.parametrize("mode,dtype,kernels", [("fp32", bf.BF_FP32, bf.BF_KERNELS_AUTO), ("bf16", bf.BF_BF16, bf.BF_KERNELS_PLAIN),
