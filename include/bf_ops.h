@@ -63,9 +63,10 @@ bf_status bf_op_gemm_splitk(int dtype, int kernels, int layout, int epilogue, in
 int bf_op_gemm_splitk_slices(int layout, int epilogue, int M, int N, int K);
 /* 1 if the MFMA kernel takes this problem in bf16 mode, 0 if the plain kernel would run. */
 int bf_op_gemm_uses_mfma(int layout, int epilogue, int M, int N, int K);
-/* The tile of C (rows x columns per workgroup) that the MFMA kernel runs an unsplit product of this shape on: 256 x 256,
- * 256 x 128, 128 x 128, or 256 x 192 (dgrad layout with the plain epilogue and N a multiple of 192, where that fills
- * the rounds better: 6144 columns).  Host arithmetic only.  Returns 1 and the tile in tile_m / tile_n (host ints), or 0
+/* The tile of C (rows x columns per workgroup) that the MFMA kernel runs an unsplit product of this shape on by itself:
+ * 256 x 256, 256 x 128, 128 x 128, or 256 x 192 (forward and dgrad layouts with the epilogues none, bias, bias + residual
+ * and N a multiple of 192, where that fills the rounds of the grid better: 2048 x 6144 outputs are 256 such tiles).  A
+ * step that runs two chains of micro-batches does not take the last shape.  Host arithmetic only.  Returns 1 and the tile in tile_m / tile_n (host ints), or 0
  * (and 0 x 0) where bf_op_gemm_uses_mfma is 0. */
 int bf_op_gemm_tile(int layout, int epilogue, int M, int N, int K, int* tile_m, int* tile_n);
 
