@@ -151,7 +151,9 @@ typedef struct {
   /* timing == 2 (every class) or 3 (the weight-gradient products): per kernel class, summed over
    * the step's launches: device time between events recorded around each launch on its stream, launch count, algorithmic flops
    * (2 M N K per product; attention with the causal half; backward attention 2.5 x forward) and
-   * algorithmic HBM bytes (every operand read once, every result written once). */
+   * algorithmic HBM bytes (every operand read once, every result written once).  With two chains of
+   * micro-batches (mb_chains = 2) launches of the two streams overlap, so the classes' times add up to
+   * more than the step's. */
   double kernel_ms[BF_N_KERNEL_CLASSES];
   double kernel_flops[BF_N_KERNEL_CLASSES];
   double kernel_bytes[BF_N_KERNEL_CLASSES];
@@ -219,9 +221,11 @@ bf_status bf_reset_optimizer(bf_stack* s);
  *                3: as 1, plus event pairs around the weight-gradient products only (the class with
  *                   the most time): a few dozen to a few hundred events per step instead of thousands
  *   stream       hipStream_t of the caller (NULL = default stream).  The call is asynchronous
- *                on it (unless timing != 0); the library's side stream (dp_fs reconstructions) joins
- *                it before returning control of the stream to later work.  The optimizer runs on
- *                the caller's stream.
+ *                on it (unless timing != 0); the library's own streams (dp_fs reconstructions; the
+ *                second chain of cfg.mb_chains = 2) start after what the stream holds at the call and
+ *                join it before the call returns, so that later work on the stream comes after the
+ *                whole step.  The optimizer runs on the caller's stream (with two chains: on the
+ *                stream of the stage's last micro-batch).
  *   report       may be NULL
  * With timing = 0 and cfg.queue_depth = 0 the call enqueues kernel launches and event record / wait
  * only (no allocation, no memset or copy, no host synchronisation) and may be recorded into a HIP
