@@ -130,3 +130,28 @@ def test_two_chain_configurations_are_validated_without_a_device():
         assert bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, **{**ok, **bad})) == 0, bad
         assert "mb_chains" in bf.binding.last_error(), bad
     assert bf.bf_workspace_bytes(bf.make_config(256, 2, 1024, 128, 4, 4, 1, ckpt_mode=bf.BF_CKPT_LAYER, **ok)) > 0
+
+
+def test_tile_choice_invariants_without_a_device():
+    """The tile a product runs on divides its output, the 192-column tile appears only for the layouts and epilogues
+    that have it and only where it gives fewer rounds of the grid than 256 columns, and shapes outside the matrix-core
+    kernel's reach report none."""
+    import itertools
+    import paper_2211_05953_amd as bf
+    one_output = {(bf.BF_NT, bf.BF_EPI_NONE), (bf.BF_NN, bf.BF_EPI_NONE), (bf.BF_NN, bf.BF_EPI_BIAS), (bf.BF_NN, bf.BF_EPI_BIAS_RES)}
+    combos = [(bf.BF_NN, e) for e in (bf.BF_EPI_NONE, bf.BF_EPI_BIAS, bf.BF_EPI_BIAS_RES, bf.BF_EPI_BIAS_GELU)] + \
+             [(bf.BF_NT, bf.BF_EPI_NONE), (bf.BF_NT, bf.BF_EPI_GELU_BWD), (bf.BF_TN, bf.BF_EPI_ACCUM)]
+    seen = set()
+    for (layout, epi), M, N in itertools.product(combos, (128, 256, 1024, 2048, 8192), (128, 384, 768, 2048, 6144, 8192, 18432, 24576, 50304)):
+        t = bf.bf_op_gemm_tile(layout, epi, M, N, 256)
+        assert t in ((256, 256), (256, 128), (128, 128), (256, 192)), (layout, epi, M, N, t)
+        assert M % t[0] == 0 and N % t[1] == 0
+        if t == (256, 192):
+            assert (layout, epi) in one_output
+            rounds = lambda bn: -(-((M // 256) * (N // bn)) // 256)
+            assert N % 256 or rounds(192) * 192 < rounds(256) * 256 * 1.2, (M, N)
+        seen.add(t)
+    assert seen == {(256, 256), (256, 128), (128, 128), (256, 192)}
+    assert bf.bf_op_gemm_tile(bf.BF_NN, bf.BF_EPI_NONE, 100, 128, 64) is None      # rows not a multiple of 128
+    assert bf.bf_op_gemm_tile(bf.BF_NN, bf.BF_EPI_NONE, 128, 128, 96) is None      # K not a multiple of 64
+    assert bf.bf_op_gemm_tile(bf.BF_TN, bf.BF_EPI_NONE, 128, 128, 64) is None      # the weight-gradient layout stores fp32
