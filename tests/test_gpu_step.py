@@ -642,15 +642,17 @@ def test_gradient_step_replays_from_a_hip_graph(schedule, chains):
     st.close()
 
 
-def test_optimizer_steps_replay_from_a_hip_graph():
+@pytest.mark.parametrize("chains,N_mb", [(1, 2), (2, 2), (2, 5)])
+def test_optimizer_steps_replay_from_a_hip_graph(chains, N_mb):
     """The optimizer's step count lives on the device and is advanced by the step itself, so a recorded
-    training step (breadth-first, Adam per stage on the side stream) keeps its bias corrections right
-    from replay to replay: eager step 1, then the graph replayed as steps 2 and 3, equals three eager steps."""
-    Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb = 4, 2, 256, 2, 1024, 128, 1, 2
+    training step (breadth-first, Adam per stage as soon as its gradient is final) keeps its bias corrections right
+    from replay to replay: eager step 1, then the graph replayed as steps 2 and 3, equals three eager steps.
+    Also with two chains of micro-batches, whose second stream is part of the recording."""
+    Lyr, N_loop, h, a, f, S_seq, S_mb = 4, 2, 256, 2, 1024, 128, 1
     params = bf_inputs.make_params(31, Lyr, h, f, bf16=True)
     x, dy = bf_inputs.make_batch(31, N_mb, S_mb, S_seq, h, bf16=True)
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16, fuse_wgrad=1, queue_depth=0, lr=1e-3,
-                         weight_decay=0.01)
+                         weight_decay=0.01, mb_chains=chains)
     dX, dDY = to_dev(x, True), to_dev(dy, True)
 
     def fresh():
