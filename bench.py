@@ -249,6 +249,9 @@ def main():
     import paper_2211_05953_amd as bf
     bf.load()   # no fallback: a missing library is an error
     w = WORKLOADS[args.workload]
+    if args.mb_chains == 2 and EXTRA.get(args.workload, {}).get("S_voc"):
+        print("bench.py: --mb-chains 2 runs the stack on activations (workloads without S_voc)", file=sys.stderr)
+        sys.exit(2)
     Lyr, N_loop, h, a, f, S_seq, S_mb, N_mb, dtype, ckpt = w
     b16 = dtype == "bf16"
     cfg = bf.make_config(h, a, f, S_seq, Lyr, N_mb, S_mb, dtype=bf.BF_BF16 if b16 else bf.BF_FP32,
